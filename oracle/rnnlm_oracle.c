@@ -1,0 +1,325 @@
+/*
+ * fp64 CPU oracle for the minibatched Elman RNN language-model step.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the checker the HIP path is judged
+ * against; it is never part of the product path.  It shares no code, header,
+ * table or helper with the HIP library, and neither includes the other.
+ *
+ * What it computes (plain definitions, loops only, no blocking or fusion):
+ *   - the "standard RNN architecture" without hidden bias units of Sec. 4.1:
+ *       a_t = E[w_t] + U h_{t-1},  h_t = 1/(1+exp(-a_t)),
+ *     a distribution "over all words in a given vocabulary" from h_t (Sec. 4.1),
+ *     explicitly normalised as Sec. 4.2 does when reporting perplexity:
+ *       z = Wo h_t + b,  log P(w | history) = z_w - log sum_v exp(z_v);
+ *   - noffset = B token streams read from B different points of one corpus, each
+ *     with its own carried hidden state (Sec. 4.2 data-offset scheme); the state is
+ *     never reset at sentence markers (Sec. 2.3 keeps between-sentence context);
+ *   - one update per window of T positions (the "minibatch" of Sec. 4.2): the
+ *     gradient of the mean negative log-likelihood of the B*T tokens of the window,
+ *     back-propagated through time to the window start and no further, followed by
+ *     one plain SGD step (Sec. 4.2 names stochastic gradient descent);
+ *   - perplexity = exp(-mean log P) (Sec. 1 names it the primary metric).
+ *
+ * Layouts: row-major; E[V][H], U[H][H] (a_i = sum_j U[i][j] h_j), Wo[V][H], b[V],
+ * h[B][H]; token windows are time-major x[T][B], y[T][B].
+ *
+ * Readings where the paper is silent: sigmoid hidden units, zero initial state,
+ * an output bias b (trained), mean (not summed) loss over the window, natural log.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG (-1)
+#define ORACLE_ERR_TOKEN (-2)
+#define ORACLE_ERR_NOMEM (-3)
+
+static int check_tokens(const int32_t *a, long n, int V) {
+  for (long i = 0; i < n; ++i)
+    if (a[i] < 0 || a[i] >= V) return ORACLE_ERR_TOKEN;
+  return ORACLE_OK;
+}
+
+/* Stream indexing of window k (Sec. 4.2 data-offset scheme): L = floor((N-1)/B)
+ * positions per stream; stream s reads inputs tok[s*L + k*T + t] and predicts the
+ * next token of the corpus. Returns the number of full windows floor(L/T). */
+long oracle_stream_chunk(const int32_t *tok, long N, int B, int T, long k, int32_t *x, int32_t *y) {
+  if (!tok || B <= 0 || T <= 0 || N < 2) return ORACLE_ERR_ARG;
+  long L = (N - 1) / B;
+  long nchunks = L / T;
+  if (x && y) {
+    if (k < 0 || k >= nchunks) return ORACLE_ERR_ARG;
+    for (int t = 0; t < T; ++t)
+      for (int s = 0; s < B; ++s) {
+        long p = (long)s * L + k * T + t;
+        x[(long)t * B + s] = tok[p];
+        y[(long)t * B + s] = tok[p + 1];
+      }
+  }
+  return nchunks;
+}
+
+/* Forward pass of one window from state h0.  Fills Hs[T][B][H], logp[T][B] and,
+ * when P != NULL, the full normalised distributions P[T][B][V]. */
+static int forward_window(int V, int H, int B, int T, const double *E, const double *U, const double *Wo,
+                          const double *b, const double *h0, const int32_t *x, const int32_t *y, double *Hs,
+                          double *P, double *logp) {
+  int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int s = 0; s < B; ++s) {
+    double *z = (double *)malloc(sizeof(double) * (size_t)V);
+    if (!z) {
+#pragma omp atomic write
+      err = 1;
+      continue;
+    }
+    const double *hprev = h0 + (size_t)s * H;
+    for (int t = 0; t < T; ++t) {
+      const size_t m = (size_t)t * B + s;
+      const double *e = E + (size_t)x[m] * H;
+      double *h = Hs + m * H;
+      for (int i = 0; i < H; ++i) {
+        const double *u = U + (size_t)i * H;
+        double a = 0.0;
+#pragma omp simd reduction(+ : a)
+        for (int j = 0; j < H; ++j) a += u[j] * hprev[j];
+        a += e[i];
+        h[i] = 1.0 / (1.0 + exp(-a));
+      }
+      double mx = -INFINITY;
+      for (int v = 0; v < V; ++v) {
+        const double *w = Wo + (size_t)v * H;
+        double acc = 0.0;
+#pragma omp simd reduction(+ : acc)
+        for (int j = 0; j < H; ++j) acc += w[j] * h[j];
+        z[v] = acc + b[v];
+        if (z[v] > mx) mx = z[v];
+      }
+      double sum = 0.0;
+      for (int v = 0; v < V; ++v) sum += exp(z[v] - mx);
+      const double lse = mx + log(sum);
+      logp[m] = z[y[m]] - lse;
+      if (P) {
+        double *p = P + m * V;
+        for (int v = 0; v < V; ++v) p[v] = exp(z[v] - lse);
+      }
+      hprev = h;
+    }
+    free(z);
+  }
+  return err ? ORACLE_ERR_NOMEM : ORACLE_OK;
+}
+
+/* log P(y | history) for one window; advances h in place. Optional outputs
+ * (may be NULL): Hs_out[T][B][H] hidden states, P_out[T][B][V] distributions. */
+int oracle_forward_logprob(int V, int H, int B, int T, const double *E, const double *U, const double *Wo,
+                           const double *b, double *h, const int32_t *x, const int32_t *y, double *logp,
+                           double *Hs_out, double *P_out) {
+  if (V <= 0 || H <= 0 || B <= 0 || T <= 0 || !E || !U || !Wo || !b || !h || !x || !y || !logp) return ORACLE_ERR_ARG;
+  if (check_tokens(x, (long)B * T, V) || check_tokens(y, (long)B * T, V)) return ORACLE_ERR_TOKEN;
+  double *Hs = Hs_out ? Hs_out : (double *)malloc(sizeof(double) * (size_t)T * B * H);
+  if (!Hs) return ORACLE_ERR_NOMEM;
+  int rc = forward_window(V, H, B, T, E, U, Wo, b, h, x, y, Hs, P_out, logp);
+  if (rc == ORACLE_OK) memcpy(h, Hs + (size_t)(T - 1) * B * H, sizeof(double) * (size_t)B * H);
+  if (!Hs_out) free(Hs);
+  return rc;
+}
+
+/* Gradient of the window's mean negative log-likelihood
+ *   Loss = -(1/(B*T)) * sum_{t,s} log P(y[t][s] | ...)
+ * with respect to E, U, Wo, b, all evaluated at the given parameters; the carried
+ * state h0 is a constant (truncated back-propagation through time: the gradient
+ * stops at the window start).  h0 is not modified; h_out (may be NULL) receives the
+ * state after the window.  Optional debug outputs (may be NULL): Hs[T][B][H],
+ * dZ[T][B][V] (= dLoss/dz), dHs[T][B][H] (= Wo^T dz only), dA[T][B][H] (= dLoss/da). */
+int oracle_grad_chunk(int V, int H, int B, int T, const double *E, const double *U, const double *Wo,
+                      const double *b, const double *h0, const int32_t *x, const int32_t *y, double *logp,
+                      double *gE, double *gU, double *gWo, double *gb, double *h_out, double *Hs_out,
+                      double *dZ_out, double *dHs_out, double *dA_out) {
+  if (V <= 0 || H <= 0 || B <= 0 || T <= 0 || !E || !U || !Wo || !b || !h0 || !x || !y || !logp || !gE || !gU ||
+      !gWo || !gb)
+    return ORACLE_ERR_ARG;
+  const size_t M = (size_t)B * T;
+  if (check_tokens(x, (long)M, V) || check_tokens(y, (long)M, V)) return ORACLE_ERR_TOKEN;
+  double *Hs = Hs_out ? Hs_out : (double *)malloc(sizeof(double) * M * H);
+  double *dZ = dZ_out ? dZ_out : (double *)malloc(sizeof(double) * M * V);
+  double *dHs = dHs_out ? dHs_out : (double *)malloc(sizeof(double) * M * H);
+  double *dA = dA_out ? dA_out : (double *)malloc(sizeof(double) * M * H);
+  int rc = ORACLE_ERR_NOMEM;
+  if (Hs && dZ && dHs && dA) {
+    rc = forward_window(V, H, B, T, E, U, Wo, b, h0, x, y, Hs, dZ, logp);
+  }
+  if (rc == ORACLE_OK) {
+    const double scale = 1.0 / (double)M;
+    /* dz = (p - onehot(y)) / (B*T) */
+#pragma omp parallel for schedule(static)
+    for (long m = 0; m < (long)M; ++m) {
+      double *d = dZ + (size_t)m * V;
+      d[y[m]] -= 1.0;
+      for (int v = 0; v < V; ++v) d[v] *= scale;
+    }
+    /* gWo[v][j] = sum_m dz[m][v] Hs[m][j];  gb[v] = sum_m dz[m][v] */
+#pragma omp parallel for schedule(static)
+    for (int v = 0; v < V; ++v) {
+      double *g = gWo + (size_t)v * H;
+      for (int j = 0; j < H; ++j) g[j] = 0.0;
+      double sb = 0.0;
+      for (size_t m = 0; m < M; ++m) {
+        const double d = dZ[m * V + v];
+        const double *h = Hs + m * H;
+        sb += d;
+        for (int j = 0; j < H; ++j) g[j] += d * h[j];
+      }
+      gb[v] = sb;
+    }
+    /* per stream, backwards in time:
+     *   dh_j = sum_v Wo[v][j] dz_v + sum_i U[i][j] da_next_i ; da = dh * h * (1-h) */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int s = 0; s < B; ++s) {
+      for (int t = T - 1; t >= 0; --t) {
+        const size_t m = (size_t)t * B + s;
+        double *dh = dHs + m * H;
+        for (int j = 0; j < H; ++j) dh[j] = 0.0;
+        const double *d = dZ + m * V;
+        for (int v = 0; v < V; ++v) {
+          const double dv = d[v];
+          const double *w = Wo + (size_t)v * H;
+          for (int j = 0; j < H; ++j) dh[j] += w[j] * dv;
+        }
+        double *da = dA + m * H;
+        const double *h = Hs + m * H;
+        if (t == T - 1) {
+          for (int j = 0; j < H; ++j) da[j] = dh[j] * h[j] * (1.0 - h[j]);
+        } else {
+          const double *dan = dA + ((size_t)(t + 1) * B + s) * H;
+          for (int j = 0; j < H; ++j) da[j] = dh[j];
+          for (int i = 0; i < H; ++i) {
+            const double *u = U + (size_t)i * H;
+            const double di = dan[i];
+            for (int j = 0; j < H; ++j) da[j] += u[j] * di;
+          }
+          for (int j = 0; j < H; ++j) da[j] *= h[j] * (1.0 - h[j]);
+        }
+      }
+    }
+    /* gU[i][j] = sum_{t,s} da[t][s][i] * hprev[t][s][j], hprev = h0 at t = 0 */
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < H; ++i) {
+      double *g = gU + (size_t)i * H;
+      for (int j = 0; j < H; ++j) g[j] = 0.0;
+      for (int t = 0; t < T; ++t)
+        for (int s = 0; s < B; ++s) {
+          const size_t m = (size_t)t * B + s;
+          const double *hp = (t > 0) ? Hs + ((size_t)(t - 1) * B + s) * H : h0 + (size_t)s * H;
+          const double di = dA[m * H + i];
+          for (int j = 0; j < H; ++j) g[j] += di * hp[j];
+        }
+    }
+    /* gE[w] = sum over window positions whose input id is w of da */
+    memset(gE, 0, sizeof(double) * (size_t)V * H);
+    for (size_t m = 0; m < M; ++m) {
+      double *g = gE + (size_t)x[m] * H;
+      const double *da = dA + m * H;
+      for (int j = 0; j < H; ++j) g[j] += da[j];
+    }
+    if (h_out) memcpy(h_out, Hs + (size_t)(T - 1) * B * H, sizeof(double) * (size_t)B * H);
+  }
+  if (!Hs_out) free(Hs);
+  if (!dZ_out) free(dZ);
+  if (!dHs_out) free(dHs);
+  if (!dA_out) free(dA);
+  return rc;
+}
+
+/* One training step on one window: gradients at the current parameters, then
+ * theta <- theta - lr * g for E, U, Wo, b; h <- state after the window (computed with
+ * the pre-update parameters).  logp[T][B]; *sum_logp (may be NULL) = sum of logp. */
+int oracle_train_chunk(int V, int H, int B, int T, double *E, double *U, double *Wo, double *b, double *h,
+                       const int32_t *x, const int32_t *y, double lr, double *logp, double *sum_logp) {
+  if (V <= 0 || H <= 0 || B <= 0 || T <= 0) return ORACLE_ERR_ARG;
+  const size_t nVH = (size_t)V * H, nHH = (size_t)H * H;
+  double *gE = (double *)malloc(sizeof(double) * nVH);
+  double *gWo = (double *)malloc(sizeof(double) * nVH);
+  double *gU = (double *)malloc(sizeof(double) * nHH);
+  double *gb = (double *)malloc(sizeof(double) * (size_t)V);
+  double *hn = (double *)malloc(sizeof(double) * (size_t)B * H);
+  int rc = ORACLE_ERR_NOMEM;
+  if (gE && gWo && gU && gb && hn)
+    rc = oracle_grad_chunk(V, H, B, T, E, U, Wo, b, h, x, y, logp, gE, gU, gWo, gb, hn, NULL, NULL, NULL, NULL);
+  if (rc == ORACLE_OK) {
+    for (size_t i = 0; i < nVH; ++i) E[i] -= lr * gE[i];
+    for (size_t i = 0; i < nVH; ++i) Wo[i] -= lr * gWo[i];
+    for (size_t i = 0; i < nHH; ++i) U[i] -= lr * gU[i];
+    for (int v = 0; v < V; ++v) b[v] -= lr * gb[v];
+    memcpy(h, hn, sizeof(double) * (size_t)B * H);
+    if (sum_logp) {
+      double sacc = 0.0;
+      for (size_t m = 0; m < (size_t)B * T; ++m) sacc += logp[m];
+      *sum_logp = sacc;
+    }
+  }
+  free(gE); free(gWo); free(gU); free(gb); free(hn);
+  return rc;
+}
+
+/* Perplexity of a token array: B streams from a zero state, every full window of T
+ * positions scored, PPL = exp(-sum logp / #scored).  The result does not depend on
+ * T except through which tail positions are dropped. */
+int oracle_perplexity(int V, int H, int B, int T, const double *E, const double *U, const double *Wo,
+                      const double *b, const int32_t *tok, long N, double *ppl, long *scored) {
+  if (V <= 0 || H <= 0 || B <= 0 || T <= 0 || !tok || !ppl || N < 2) return ORACLE_ERR_ARG;
+  long nchunks = oracle_stream_chunk(tok, N, B, T, 0, NULL, NULL);
+  if (nchunks < 1) return ORACLE_ERR_ARG;
+  const size_t M = (size_t)B * T;
+  double *h = (double *)calloc((size_t)B * H, sizeof(double));
+  int32_t *x = (int32_t *)malloc(sizeof(int32_t) * M);
+  int32_t *y = (int32_t *)malloc(sizeof(int32_t) * M);
+  double *lp = (double *)malloc(sizeof(double) * M);
+  int rc = (h && x && y && lp) ? ORACLE_OK : ORACLE_ERR_NOMEM;
+  double total = 0.0;
+  for (long k = 0; k < nchunks && rc == ORACLE_OK; ++k) {
+    oracle_stream_chunk(tok, N, B, T, k, x, y);
+    rc = oracle_forward_logprob(V, H, B, T, E, U, Wo, b, h, x, y, lp, NULL, NULL);
+    for (size_t m = 0; m < M && rc == ORACLE_OK; ++m) total += lp[m];
+  }
+  if (rc == ORACLE_OK) {
+    *ppl = exp(-total / (double)(nchunks * (long)M));
+    if (scored) *scored = nchunks * (long)M;
+  }
+  free(h); free(x); free(y); free(lp);
+  return rc;
+}
+
+/* Integer helper for the embedding gradient: positions m = 0..M-1 of a window
+ * ordered by (x[m], m) (a stable sort by id), and the start of each run of equal
+ * ids.  perm[M]; seg_start[M+1] (first nseg+1 entries valid, seg_start[nseg] = M).
+ * Returns nseg. */
+int oracle_sort_segments(const int32_t *x, int M, int32_t *perm, int32_t *seg_start) {
+  if (!x || M <= 0 || !perm || !seg_start) return ORACLE_ERR_ARG;
+  for (int m = 0; m < M; ++m) perm[m] = m;
+  for (int i = 1; i < M; ++i) { /* insertion sort: stable by construction */
+    int32_t p = perm[i];
+    int j = i - 1;
+    while (j >= 0 && x[perm[j]] > x[p]) {
+      perm[j + 1] = perm[j];
+      --j;
+    }
+    perm[j + 1] = p;
+  }
+  int nseg = 0;
+  for (int r = 0; r < M; ++r)
+    if (r == 0 || x[perm[r]] != x[perm[r - 1]]) seg_start[nseg++] = r;
+  seg_start[nseg] = M;
+  return nseg;
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  extern int omp_get_max_threads(void);
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
