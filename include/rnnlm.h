@@ -1,0 +1,149 @@
+/*
+ * rnnlm.h - C ABI of the MI355X (gfx950) Elman RNN language-model training step.
+ *
+ * The model is the "standard RNN architecture" without hidden bias units of Sec. 4.1 of
+ * "Scaling Recurrent Neural Network Language Models":
+ *     h_t = sigmoid(E[w_t] + U h_{t-1}),   z_t = Wo h_t + b,
+ *     log P(w | history) = z_t[w] - log sum_v exp(z_t[v])   (explicitly normalised, Sec. 4.2)
+ * trained on B = "noffset" token streams read from B points of one corpus, each with its
+ * own carried hidden state (data-offset scheme, Sec. 4.2), with one update per window of T
+ * positions (the "minibatch" of Sec. 4.2): truncated back-propagation through time over the
+ * window, then plain stochastic gradient descent (Sec. 4.2).  The hidden state is never reset
+ * at sentence markers (Sec. 2.3 keeps between-sentence context).  Perplexity (Sec. 1) is
+ * exp(-mean log P).
+ *
+ * Conventions
+ *   - Every array is row-major.  E[V][H], U[H][H] (a_i = sum_j U[i][j] h_j), Wo[V][H], b[V],
+ *     h_state[B][H].  Token windows are time-major: x[T][B], y[T][B], logp[T][B]; the row index
+ *     of position (t, s) is m = t*B + s.  Log-probabilities are natural logs.
+ *   - "dev" pointers are DEVICE pointers of the configured HIP device; "host" pointers are
+ *     ordinary host memory.  The library borrows the caller's parameter, state and workspace
+ *     buffers (it allocates no device memory itself) and updates E, U, Wo, b, h_state in place.
+ *     The buffers must stay alive and must not be written by the caller while a call is in
+ *     flight on the stream.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work and return without waiting unless stated otherwise.  Calls on one handle must be
+ *     issued on one stream at a time (they share the workspace).
+ *   - Every function returns RNNLM_OK (0) or a negative rnnlm_status; nothing throws.
+ *   - Token ids outside [0, V) never cause an out-of-bounds access: they are clamped on the
+ *     device and a sticky flag is raised, reported as RNNLM_ERR_TOKEN_RANGE by the next
+ *     synchronising call (rnnlm_perplexity, rnnlm_check).
+ *   - Gradients are those of the MEAN negative log-likelihood of the B*T tokens of a window.
+ *     All T positions of a window use the same (pre-update) parameters; duplicates of an input
+ *     id within a window add up in fixed (ascending m) order, so results are run-to-run
+ *     bitwise reproducible.
+ */
+#ifndef RNNLM_H
+#define RNNLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rnnlm rnnlm_t; /* opaque host-side handle */
+
+typedef enum {
+  RNNLM_FP32 = 0,            /* fp32 storage, fp32 MFMA contraction */
+  RNNLM_BF16_FP32MASTER = 1  /* bf16 operands (round-to-nearest-even), fp32 accumulation, fp32 master weights */
+} rnnlm_precision;
+
+typedef enum {
+  RNNLM_OK = 0,
+  RNNLM_ERR_ARG = -1,         /* null pointer, non-positive size, T > T_max, workspace too small, misaligned */
+  RNNLM_ERR_TOKEN_RANGE = -2, /* some token id was outside [0, V) (ids were clamped, results are meaningless) */
+  RNNLM_ERR_NONFINITE = -3,   /* a window's sum of log-probabilities was not finite */
+  RNNLM_ERR_HIP = -4,         /* a HIP runtime call failed */
+  RNNLM_ERR_NOMEM = -5        /* host allocation failed */
+} rnnlm_status;
+
+typedef struct {
+  int32_t V;         /* vocabulary size, > 0 */
+  int32_t H;         /* hidden units ("nstate"), > 0 */
+  int32_t B;         /* parallel token streams ("noffset"), > 0 */
+  int32_t T_max;     /* longest window a call may pass, > 0 */
+  int32_t precision; /* rnnlm_precision */
+  int32_t device;    /* HIP device ordinal */
+} rnnlm_config;
+
+typedef struct {
+  float *E;               /* dev [V][H]  input->state matrix (embedding rows), fp32 master */
+  float *U;               /* dev [H][H]  state->state matrix */
+  float *Wo;              /* dev [V][H]  state->output matrix */
+  float *b;               /* dev [V]     output bias */
+  float *h_state;         /* dev [B][H]  carried hidden state */
+  void *workspace;        /* dev, 256-byte aligned, >= rnnlm_workspace_bytes(cfg) */
+  size_t workspace_bytes;
+} rnnlm_buffers;
+
+/* Device bytes of workspace the configuration needs (0 if cfg is invalid). */
+size_t rnnlm_workspace_bytes(const rnnlm_config *cfg);
+
+/* Validates cfg/buffers, binds the caller's buffers, clears the workspace and h_state (zero initial
+ * state), and builds the compute copies of U and Wo (bf16 or fp32, tile-padded) inside the
+ * workspace.  *out receives the handle.  Synchronises the device before returning. */
+int rnnlm_init(const rnnlm_config *cfg, const rnnlm_buffers *buf, rnnlm_t **out);
+
+/* Releases the host handle (device buffers belong to the caller). NULL is allowed. */
+void rnnlm_free(rnnlm_t *h);
+
+/* Stream indexing of window k under the data-offset scheme of Sec. 4.2: with L = floor((N-1)/B),
+ * x[t][s] = tok[s*L + k*T + t] and y[t][s] = tok[s*L + k*T + t + 1].  tok: dev int32[N];
+ * x, y: dev int32[T][B].  Requires 0 <= k < floor(L/T), 1 <= T <= T_max. Integer-exact. */
+int rnnlm_stream_chunk(rnnlm_t *h, const int32_t *tok, int64_t N, int64_t k, int32_t T, int32_t *x, int32_t *y,
+                       void *stream);
+
+/* log P(y[t][s] | stream s up to x[t][s]) for one window (Sec. 4.1 / 4.2 normalised output),
+ * starting from h_state, which is advanced to the state after the window.
+ * x, y: dev int32[T][B]; logp: dev float[T][B]. */
+int rnnlm_forward_logprob(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *logp, void *stream);
+
+/* One training step on one window (Sec. 4.2): forward, truncated BPTT gradients of the mean
+ * negative log-likelihood at the current parameters, then theta <- theta - lr*g for E, U, Wo, b, and
+ * h_state <- state after the window (computed with the pre-update parameters).
+ * logp: dev float[T][B] or NULL; sum_logp: dev double (sum of the window's log-probs) or NULL. */
+int rnnlm_train_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lr, float *logp,
+                      double *sum_logp, void *stream);
+
+/* Same kernels as rnnlm_train_chunk but the update epilogues write the gradients (of the mean
+ * negative log-likelihood) into caller buffers instead of updating: dE: dev float[V][H] (rows of ids
+ * not in x are zero), dU: dev float[H][H], dWo: dev float[V][H], db: dev float[V]; logp as above or
+ * NULL.  Parameters and h_state are left unchanged. */
+int rnnlm_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *dE, float *dU, float *dWo,
+                     float *db, float *logp, void *stream);
+
+/* Perplexity (Sec. 1, Sec. 4.2: normalised output) of tok: dev int32[N]: h_state is reset to zero,
+ * the array is split into B streams as in rnnlm_stream_chunk and every full window of T positions
+ * is scored; *ppl (HOST) = exp(-sum logp / scored), *scored (HOST, may be NULL) = windows*B*T.
+ * Waits for the stream; reports RNNLM_ERR_TOKEN_RANGE / RNNLM_ERR_NONFINITE. */
+int rnnlm_perplexity(rnnlm_t *h, const int32_t *tok, int64_t N, int32_t T, double *ppl, int64_t *scored,
+                     void *stream);
+
+/* h_state <- 0. */
+int rnnlm_reset_state(rnnlm_t *h, void *stream);
+
+/* Rebuilds the compute copies of U and Wo from the fp32 masters (after the caller overwrote the
+ * masters, e.g. when loading a checkpoint). */
+int rnnlm_sync_compute_copies(rnnlm_t *h, void *stream);
+
+/* Waits for the stream and returns RNNLM_ERR_TOKEN_RANGE if any call since the last check saw an
+ * out-of-range token id (the flag is cleared), RNNLM_ERR_HIP on a device error, else RNNLM_OK. */
+int rnnlm_check(rnnlm_t *h, void *stream);
+
+/* Integer intermediates of the embedding-gradient step for the window x: dev int32[T][B]:
+ * perm: dev int32[B*T] = positions m ordered by (x[m], m) (stable sort by id); seg_start: dev
+ * int32[B*T+1] = start of each run of equal ids in that order, followed by B*T; nseg: dev int32 =
+ * number of runs.  Integer-exact. */
+int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, int32_t *seg_start, int32_t *nseg,
+                        void *stream);
+
+/* Name and average duration bookkeeping is left to the caller's profiler; this returns a static
+ * description of a status code. */
+const char *rnnlm_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RNNLM_H */

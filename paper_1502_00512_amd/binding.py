@@ -1,0 +1,195 @@
+"""Thin ctypes binding of include/rnnlm.h: argument marshalling only.
+
+Every step of the path runs in the HIP library; PyTorch only owns device memory and
+streams.  Function names mirror the C ABI.  Importing this module needs the built
+librnnlm_hip.so next to it (see build.py) and raises if it is missing: there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librnnlm_hip.so")
+
+RNNLM_FP32 = 0
+RNNLM_BF16_FP32MASTER = 1
+
+SYMBOLS = [
+    "rnnlm_workspace_bytes", "rnnlm_init", "rnnlm_free", "rnnlm_stream_chunk", "rnnlm_forward_logprob",
+    "rnnlm_train_chunk", "rnnlm_grad_chunk", "rnnlm_perplexity", "rnnlm_reset_state",
+    "rnnlm_sync_compute_copies", "rnnlm_check", "rnnlm_sort_segments", "rnnlm_status_string",
+]
+
+
+class rnnlm_config(C.Structure):
+    _fields_ = [("V", C.c_int32), ("H", C.c_int32), ("B", C.c_int32), ("T_max", C.c_int32),
+                ("precision", C.c_int32), ("device", C.c_int32)]
+
+
+class rnnlm_buffers(C.Structure):
+    _fields_ = [("E", C.c_void_p), ("U", C.c_void_p), ("Wo", C.c_void_p), ("b", C.c_void_p),
+                ("h_state", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class RnnlmError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_1502_00512_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.rnnlm_workspace_bytes.restype = C.c_size_t
+    lib.rnnlm_workspace_bytes.argtypes = [C.POINTER(rnnlm_config)]
+    lib.rnnlm_init.argtypes = [C.POINTER(rnnlm_config), C.POINTER(rnnlm_buffers), C.POINTER(vp)]
+    lib.rnnlm_free.argtypes = [vp]
+    lib.rnnlm_free.restype = None
+    lib.rnnlm_stream_chunk.argtypes = [vp, vp, i64, i64, i32, vp, vp, vp]
+    lib.rnnlm_forward_logprob.argtypes = [vp, vp, vp, i32, vp, vp]
+    lib.rnnlm_train_chunk.argtypes = [vp, vp, vp, i32, C.c_float, vp, vp, vp]
+    lib.rnnlm_grad_chunk.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.rnnlm_perplexity.argtypes = [vp, vp, i64, i32, C.POINTER(C.c_double), C.POINTER(i64), vp]
+    lib.rnnlm_reset_state.argtypes = [vp, vp]
+    lib.rnnlm_sync_compute_copies.argtypes = [vp, vp]
+    lib.rnnlm_check.argtypes = [vp, vp]
+    lib.rnnlm_sort_segments.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    lib.rnnlm_status_string.argtypes = [C.c_int]
+    lib.rnnlm_status_string.restype = C.c_char_p
+    for name in SYMBOLS:
+        if name not in ("rnnlm_workspace_bytes", "rnnlm_free", "rnnlm_status_string"):
+            getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().rnnlm_status_string(int(status)).decode()
+
+
+def _ok(rc: int, what: str):
+    if rc != 0:
+        raise RnnlmError(rc, what)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def rnnlm_workspace_bytes(V, H, B, T_max, precision, device=0) -> int:
+    cfg = rnnlm_config(V, H, B, T_max, precision, device)
+    return int(load().rnnlm_workspace_bytes(C.byref(cfg)))
+
+
+class Rnnlm:
+    """Owns the torch tensors (masters, state, workspace) and the library handle."""
+
+    def __init__(self, E, U, Wo, b, B: int, T_max: int, precision: int, device: int = 0):
+        import torch
+        self.lib = load()
+        dev = torch.device("cuda", device)
+        f = lambda a: torch.as_tensor(a, dtype=torch.float32).contiguous().to(dev).clone()
+        self.E, self.U, self.Wo, self.b = f(E), f(U), f(Wo), f(b)
+        self.V, self.H = self.E.shape
+        self.B, self.T_max, self.precision, self.device = int(B), int(T_max), int(precision), dev
+        assert self.U.shape == (self.H, self.H) and self.Wo.shape == (self.V, self.H) and self.b.shape == (self.V,)
+        self.h_state = torch.zeros(self.B, self.H, dtype=torch.float32, device=dev)
+        cfg = rnnlm_config(self.V, self.H, self.B, self.T_max, self.precision, device)
+        nbytes = int(self.lib.rnnlm_workspace_bytes(C.byref(cfg)))
+        if nbytes == 0:
+            raise RnnlmError(-1, "rnnlm_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        buf = rnnlm_buffers(self.E.data_ptr(), self.U.data_ptr(), self.Wo.data_ptr(), self.b.data_ptr(),
+                            self.h_state.data_ptr(), self.workspace.data_ptr(), nbytes)
+        self.handle = C.c_void_p()
+        torch.cuda.synchronize(dev)
+        _ok(self.lib.rnnlm_init(C.byref(cfg), C.byref(buf), C.byref(self.handle)), "rnnlm_init")
+
+    def close(self):
+        if getattr(self, "handle", None):
+            import torch
+            torch.cuda.synchronize(self.device)
+            self.lib.rnnlm_free(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the calls of the C ABI, same names ----------------------------------------------------
+    def rnnlm_stream_chunk(self, tok, k: int, T: int, x=None, y=None, stream=None):
+        import torch
+        if x is None:
+            x = torch.empty(T, self.B, dtype=torch.int32, device=self.device)
+            y = torch.empty(T, self.B, dtype=torch.int32, device=self.device)
+        _ok(self.lib.rnnlm_stream_chunk(self.handle, _ptr(tok), tok.numel(), k, T, _ptr(x), _ptr(y), _stream(stream)),
+            "rnnlm_stream_chunk")
+        return x, y
+
+    def rnnlm_forward_logprob(self, x, y, logp=None, stream=None):
+        import torch
+        T = x.shape[0]
+        if logp is None:
+            logp = torch.empty(T, self.B, dtype=torch.float32, device=self.device)
+        _ok(self.lib.rnnlm_forward_logprob(self.handle, _ptr(x), _ptr(y), T, _ptr(logp), _stream(stream)),
+            "rnnlm_forward_logprob")
+        return logp
+
+    def rnnlm_train_chunk(self, x, y, lr: float, logp=None, sum_logp=None, stream=None):
+        _ok(self.lib.rnnlm_train_chunk(self.handle, _ptr(x), _ptr(y), x.shape[0], lr, _ptr(logp), _ptr(sum_logp),
+                                       _stream(stream)), "rnnlm_train_chunk")
+
+    def rnnlm_grad_chunk(self, x, y, want_logp=True, stream=None):
+        import torch
+        z = lambda *s: torch.empty(*s, dtype=torch.float32, device=self.device)
+        dE, dU, dWo, db = z(self.V, self.H), z(self.H, self.H), z(self.V, self.H), z(self.V)
+        logp = z(x.shape[0], self.B) if want_logp else None
+        _ok(self.lib.rnnlm_grad_chunk(self.handle, _ptr(x), _ptr(y), x.shape[0], _ptr(dE), _ptr(dU), _ptr(dWo),
+                                      _ptr(db), _ptr(logp), _stream(stream)), "rnnlm_grad_chunk")
+        return dict(gE=dE, gU=dU, gWo=dWo, gb=db, logp=logp)
+
+    def rnnlm_perplexity(self, tok, T: int, stream=None):
+        ppl = C.c_double(0.0)
+        scored = C.c_int64(0)
+        _ok(self.lib.rnnlm_perplexity(self.handle, _ptr(tok), tok.numel(), T, C.byref(ppl), C.byref(scored),
+                                      _stream(stream)), "rnnlm_perplexity")
+        return ppl.value, scored.value
+
+    def rnnlm_reset_state(self, stream=None):
+        _ok(self.lib.rnnlm_reset_state(self.handle, _stream(stream)), "rnnlm_reset_state")
+
+    def rnnlm_sync_compute_copies(self, stream=None):
+        _ok(self.lib.rnnlm_sync_compute_copies(self.handle, _stream(stream)), "rnnlm_sync_compute_copies")
+
+    def rnnlm_check(self, stream=None):
+        _ok(self.lib.rnnlm_check(self.handle, _stream(stream)), "rnnlm_check")
+
+    def rnnlm_sort_segments(self, x, stream=None):
+        import torch
+        M = x.numel()
+        perm = torch.empty(M, dtype=torch.int32, device=self.device)
+        seg = torch.empty(M + 1, dtype=torch.int32, device=self.device)
+        nseg = torch.zeros(1, dtype=torch.int32, device=self.device)
+        _ok(self.lib.rnnlm_sort_segments(self.handle, _ptr(x), x.shape[0], _ptr(perm), _ptr(seg), _ptr(nseg),
+                                         _stream(stream)), "rnnlm_sort_segments")
+        n = int(nseg.item())
+        return perm, seg[:n + 1]

@@ -1,0 +1,48 @@
+// Shared device/host definitions of the gfx950 RNNLM library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rnnlm_dev {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+// Padding granularities of every internal buffer (elements). All GEMM operands live in
+// buffers whose dimensions are multiples of these, with the padding kept at zero (or, where
+// stated, merely finite), so the contraction kernels carry no bounds checks.
+constexpr int PAD_H = 128;  // hidden dimension
+constexpr int PAD_V = 128;  // vocabulary dimension
+constexpr int PAD_B = 32;   // streams per timestep
+constexpr int PAD_M = 128;  // rows of a window (T * padded B)
+
+__host__ __device__ inline long round_up(long a, long b) { return (a + b - 1) / b * b; }
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static constexpr int BK = 32;  // K extent of one LDS tile (128 bytes)
+  static constexpr int VEC = 4;  // elements per 16-byte access
+};
+template <>
+struct Elem<bf16_t> {
+  static constexpr int BK = 64;
+  static constexpr int VEC = 8;
+};
+
+__device__ inline float to_f32(float v) { return v; }
+__device__ inline float to_f32(bf16_t v) { return (float)v; }
+template <typename T>
+__device__ inline T from_f32(float v);
+template <>
+__device__ inline float from_f32<float>(float v) { return v; }
+template <>
+__device__ inline bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // round-to-nearest-even
+
+__device__ inline float sigmoidf_(float a) { return 1.0f / (1.0f + __expf(-a)); }
+
+}  // namespace rnnlm_dev

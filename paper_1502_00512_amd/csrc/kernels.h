@@ -1,0 +1,287 @@
+// Non-contraction kernels of the RNNLM step: stream indexing, token checks, embedding gather,
+// softmax statistics merge, fused softmax-gradient pass, split-K reduction, sort/segment helpers
+// and the segmented embedding update.
+#pragma once
+#include "common.h"
+
+namespace rnnlm_dev {
+
+// ---- a0: data-offset stream indexing (Sec. 4.2) ------------------------------------------------
+__global__ void stream_chunk_kernel(const int32_t *__restrict__ tok, long L, long k, int T, int B,
+                                    int32_t *__restrict__ x, int32_t *__restrict__ y) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= T * B) return;
+  const int t = i / B, s = i % B;
+  const long p = (long)s * L + k * T + t;
+  x[i] = tok[p];
+  y[i] = tok[p + 1];
+}
+
+// Token check + re-layout into the padded window: xp/yp[t*Bp + s]; padding rows get -1.  Ids outside
+// [0, V) are clamped and raise flags[0].  Also marks padded positions with lse = +inf so that the
+// softmax-gradient pass produces exact zeros there.
+__global__ void prep_tokens_kernel(const int32_t *__restrict__ x, const int32_t *__restrict__ y, int T, int B, int Bp,
+                                   int Mp, int V, int32_t *__restrict__ xp, int32_t *__restrict__ yp,
+                                   float *__restrict__ lse, int32_t *__restrict__ flags) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= Mp) return;
+  const int t = i / Bp, s = i % Bp;
+  int xv = -1, yv = -1;
+  if (t < T && s < B) {
+    xv = x[t * B + s];
+    yv = y ? y[t * B + s] : 0;
+    if (xv < 0 || xv >= V || yv < 0 || yv >= V) {
+      flags[0] = 1;
+      xv = min(max(xv, 0), V - 1);
+      yv = min(max(yv, 0), V - 1);
+    }
+  } else {
+    lse[i] = INFINITY;
+  }
+  xp[i] = xv;
+  if (yp) yp[i] = yv;
+}
+
+// Carried state -> slot 0 of the hidden-state buffer (compute type, padded with zeros).
+template <typename T>
+__global__ void state_to_slot_kernel(const float *__restrict__ h_state, int B, int H, int Bp, int Hp,
+                                     T *__restrict__ slot) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long)Bp * Hp) return;
+  const int s = (int)(i / Hp), c = (int)(i % Hp);
+  slot[i] = from_f32<T>((s < B && c < H) ? h_state[(long)s * H + c] : 0.0f);
+}
+
+// ---- a1: embedding gather: X[row][:] = E[xp[row]][:] (fp32), zero on padding -------------------
+__global__ void gather_kernel(const float *__restrict__ E, const int32_t *__restrict__ xp, int H, int Hp,
+                              float *__restrict__ X) {
+  const int row = blockIdx.x;
+  const int w = xp[row];
+  const float *src = E + (long)max(w, 0) * H;
+  float *dst = X + (long)row * Hp;
+  if ((H & 3) == 0) {
+    for (int c = threadIdx.x * 4; c < Hp; c += blockDim.x * 4) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (w >= 0 && c < H) v = *reinterpret_cast<const float4 *>(src + c);
+      *reinterpret_cast<float4 *>(dst + c) = v;
+    }
+  } else {
+    for (int c = threadIdx.x; c < Hp; c += blockDim.x) dst[c] = (w >= 0 && c < H) ? src[c] : 0.0f;
+  }
+}
+
+template <typename T>
+__global__ void fill_kernel(T *__restrict__ p, long n, T v) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long stride = (long)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = v;
+}
+
+// fp32 master -> padded compute copy.
+template <typename T>
+__global__ void to_compute_copy_kernel(const float *__restrict__ W, int R, int C, int Cp, long n,
+                                       T *__restrict__ Wc) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long stride = (long)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    const long r = i / Cp;
+    const int c = (int)(i % Cp);
+    Wc[i] = from_f32<T>((r < R && c < C) ? W[r * C + c] : 0.0f);
+  }
+}
+
+// ---- a4 (part 1): merge the per-row-block (max, sum exp) partials of each position into the log
+// normaliser, and form log P(target) = z_target - lse (Sec. 4.2: explicitly normalised output).
+__global__ void merge_stats_kernel(const float2 *__restrict__ part, int nPart, long ldz, int T, int B, int Bp,
+                                   const float *__restrict__ zy, float *__restrict__ lse,
+                                   float *__restrict__ logp_int, float *__restrict__ logp_out) {
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m >= T * Bp) return;
+  const int t = m / Bp, s = m % Bp;
+  if (s >= B) return;  // padding keeps lse = +inf
+  float mx = -INFINITY, sum = 0.0f;
+  for (int p = 0; p < nPart; ++p) {
+    const float2 q = part[(long)p * ldz + m];
+    if (q.y > 0.0f) {
+      const float nmx = fmaxf(mx, q.x);
+      sum = sum * __expf(mx - nmx) + q.y * __expf(q.x - nmx);
+      mx = nmx;
+    }
+  }
+  const float l = mx + __logf(sum);
+  lse[m] = l;
+  const float lp = zy[m] - l;
+  logp_int[t * B + s] = lp;
+  if (logp_out) logp_out[t * B + s] = lp;
+}
+
+// Sum of the window's log-probabilities in fp64 with a fixed reduction tree; raises flags[1] when the
+// result is not finite.
+__global__ void sum_logp_kernel(const float *__restrict__ logp, int n, double *__restrict__ out,
+                                double *__restrict__ running, int32_t *__restrict__ flags) {
+  __shared__ double sh[1024];
+  double a = 0.0;
+  for (int i = threadIdx.x; i < n; i += 1024) a += (double)logp[i];
+  sh[threadIdx.x] = a;
+  __syncthreads();
+  for (int w = 512; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) sh[threadIdx.x] += sh[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double s = sh[0];
+    if (out) *out = s;
+    if (running) *running += s;
+    if (!(s == s) || s - s != 0.0) flags[1] = 1;
+  }
+}
+
+// ---- a4 (part 2) + a5: fused softmax gradient, in place on the vocabulary-major logits ----------
+//   dz[v][m] = (exp(z[v][m] - lse[m]) - [v == y[m]]) / M      (gradient of the mean NLL)
+//   db[v]    = sum_m dz[v][m];   b_out[v] = alpha*b[v] - lr*db[v]
+// One wavefront per vocabulary row; rows v >= V and padded positions (lse = +inf) become zero.
+template <typename T>
+__global__ void __launch_bounds__(256) softmax_grad_kernel(T *__restrict__ ZT, long ldz, int Mp, int V, int Vp,
+                                                           const float *__restrict__ lse,
+                                                           const int32_t *__restrict__ yp, float invM,
+                                                           const float *__restrict__ b, float *__restrict__ b_out,
+                                                           float alpha, float lr) {
+  constexpr int VEC = Elem<T>::VEC;
+  const int lane = threadIdx.x & 63;
+  const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (v >= Vp) return;
+  T *row = ZT + (long)v * ldz;
+  float db = 0.0f;
+  for (int c = lane * VEC; c < Mp; c += 64 * VEC) {
+    T vals[VEC];
+    *reinterpret_cast<uint4 *>(vals) = *reinterpret_cast<const uint4 *>(row + c);
+    if (v < V) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) {
+        float p = __expf(to_f32(vals[e]) - lse[c + e]);
+        if (yp[c + e] == v) p -= 1.0f;
+        p *= invM;
+        db += p;
+        vals[e] = from_f32<T>(p);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) vals[e] = from_f32<T>(0.0f);
+    }
+    *reinterpret_cast<uint4 *>(row + c) = *reinterpret_cast<const uint4 *>(vals);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) db += __shfl_xor(db, o, 64);
+  if (lane == 0 && v < V) b_out[v] = ((alpha != 0.0f) ? alpha * b[v] : 0.0f) - lr * db;
+}
+
+// ---- a6: fixed-order reduction of the split-K partial sums -------------------------------------
+__global__ void splitk_reduce_kernel(const float *__restrict__ part, long n, long split_stride, int splits,
+                                     float *__restrict__ out) {
+  const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n) return;
+  float4 a = *reinterpret_cast<const float4 *>(part + i);
+  for (int s = 1; s < splits; ++s) {
+    const float4 q = *reinterpret_cast<const float4 *>(part + (long)s * split_stride + i);
+    a.x += q.x;
+    a.y += q.y;
+    a.z += q.z;
+    a.w += q.w;
+  }
+  *reinterpret_cast<float4 *>(out + i) = a;
+}
+
+// ---- a10 helpers (integer-exact): stable order of window positions by input id ------------------
+// rank[m] = #{m' : (x[m'], m') < (x[m], m)};  perm[rank[m]] = m.
+__global__ void rank_sort_kernel(const int32_t *__restrict__ xp, int M, int B, int Bp, int32_t *__restrict__ perm) {
+  __shared__ int32_t keys[2048];
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  const int mykey = (m < M) ? xp[(m / B) * Bp + (m % B)] : 0;
+  int rank = 0;
+  for (int base = 0; base < M; base += 2048) {
+    const int n = min(2048, M - base);
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+      const int mm = base + i;
+      keys[i] = xp[(mm / B) * Bp + (mm % B)];
+    }
+    __syncthreads();
+    if (m < M) {
+      for (int i = 0; i < n; ++i) {
+        const int k = keys[i];
+        rank += (k < mykey) || (k == mykey && base + i < m);
+      }
+    }
+    __syncthreads();
+  }
+  if (m < M) perm[rank] = m;
+}
+
+// Run starts of equal ids in sorted order; single workgroup of 1024 threads, fixed scan order.
+__global__ void segment_kernel(const int32_t *__restrict__ xp, const int32_t *__restrict__ perm, int M, int B,
+                               int Bp, int32_t *__restrict__ seg_start, int32_t *__restrict__ nseg) {
+  __shared__ int32_t sc[1024];
+  __shared__ int32_t carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int base = 0; base < M; base += 1024) {
+    const int r = base + threadIdx.x;
+    int head = 0;
+    if (r < M) {
+      const int m = perm[r];
+      const int k = xp[(m / B) * Bp + (m % B)];
+      if (r == 0) {
+        head = 1;
+      } else {
+        const int mq = perm[r - 1];
+        head = xp[(mq / B) * Bp + (mq % B)] != k;
+      }
+    }
+    sc[threadIdx.x] = head;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+      int add = 0;
+      if ((int)threadIdx.x >= off) add = sc[threadIdx.x - off];
+      __syncthreads();
+      sc[threadIdx.x] += add;
+      __syncthreads();
+    }
+    const int incl = sc[threadIdx.x];
+    const int c0 = carry;
+    if (head) seg_start[c0 + incl - 1] = r;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry = c0 + incl;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    seg_start[carry] = M;
+    *nseg = carry;
+  }
+}
+
+// ---- a10: segmented embedding update, atomic-free and order-fixed -------------------------------
+//   out[w][:] = alpha*E[w][:] - lr * sum_{m in run of w, ascending m} dA[m][:]
+// blockIdx.x = run index (exits when >= *nseg), blockIdx.y = block of 256 columns.
+__global__ void __launch_bounds__(256) scatter_update_kernel(const float *__restrict__ dA, int Hp, int H, int B,
+                                                             int Bp, const int32_t *__restrict__ xp,
+                                                             const int32_t *__restrict__ perm,
+                                                             const int32_t *__restrict__ seg_start,
+                                                             const int32_t *__restrict__ nseg,
+                                                             const float *__restrict__ E, float *__restrict__ out,
+                                                             float alpha, float lr) {
+  const int g = blockIdx.x;
+  if (g >= *nseg) return;
+  const int col = blockIdx.y * 256 + threadIdx.x;
+  if (col >= H) return;
+  const int r0 = seg_start[g], r1 = seg_start[g + 1];
+  const int m0 = perm[r0];
+  const int w = xp[(m0 / B) * Bp + (m0 % B)];
+  float acc = 0.0f;
+  for (int r = r0; r < r1; ++r) {
+    const int m = perm[r];
+    acc += dA[((long)(m / B) * Bp + (m % B)) * Hp + col];
+  }
+  const long idx = (long)w * H + col;
+  out[idx] = ((alpha != 0.0f) ? alpha * E[idx] : 0.0f) - lr * acc;
+}
+
+}  // namespace rnnlm_dev

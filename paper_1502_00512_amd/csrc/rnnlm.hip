@@ -1,0 +1,493 @@
+// Host side of the C ABI declared in include/rnnlm.h: argument validation, workspace carving and
+// the kernel sequence of one window (Sec. 4.1 / 4.2 of the paper; see the header for the model).
+#include "../../include/rnnlm.h"
+
+#include <math.h>
+
+#include <algorithm>
+#include <new>
+
+#include "common.h"
+#include "gemm.h"
+#include "kernels.h"
+
+using namespace rnnlm_dev;
+
+#define HIP_TRY(expr)                        \
+  do {                                       \
+    hipError_t e_ = (expr);                  \
+    if (e_ != hipSuccess) return RNNLM_ERR_HIP; \
+  } while (0)
+
+struct WsLayout {
+  size_t Wo_c, U_c, Hs_c, ZT, dA_c, X32, dHs32, dA32, part32, stat, lse, zy, logp_int, xp, yp, perm, seg, xtmp, ytmp,
+      scalars, total;
+  long partElems;
+};
+
+struct rnnlm {
+  rnnlm_config cfg;
+  rnnlm_buffers buf;
+  int Hp, Vp, Bp, MpMax;
+  int nPart;
+  WsLayout L;
+  char *ws;
+};
+
+namespace {
+
+constexpr int OUT_WTM = 64;  // rows of the output-forward wave tile (one statistics partial each)
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+bool cfg_ok(const rnnlm_config *c) {
+  if (!c) return false;
+  if (c->V <= 0 || c->H <= 0 || c->B <= 0 || c->T_max <= 0) return false;
+  if (c->precision != RNNLM_FP32 && c->precision != RNNLM_BF16_FP32MASTER) return false;
+  if (c->device < 0) return false;
+  if ((long)c->B * c->T_max > (1L << 24)) return false;
+  return true;
+}
+
+int desired_splits(long Mp, long Hp, long kBlocks) {
+  const long tiles = (Mp / 128) * (Hp / 128);
+  long s = (768 + tiles - 1) / tiles;
+  if (s > 16) s = 16;
+  if (s > kBlocks) s = kBlocks;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, int &nPart, WsLayout &L) {
+  const size_t es = (c.precision == RNNLM_FP32) ? 4 : 2;
+  Hp = (int)round_up(c.H, PAD_H);
+  Vp = (int)round_up(c.V, PAD_V);
+  Bp = (int)round_up(c.B, PAD_B);
+  MpMax = (int)round_up((long)c.T_max * Bp, PAD_M);
+  nPart = Vp / OUT_WTM;
+  const int BK = (es == 4) ? 32 : 64;
+  const int S = desired_splits(MpMax, Hp, Vp / BK);
+  L.partElems = (long)S * MpMax * Hp;
+  size_t o = 0;
+  auto take = [&](size_t bytes) {
+    size_t at = o;
+    o = align256(o + bytes);
+    return at;
+  };
+  L.Wo_c = take((size_t)Vp * Hp * es);
+  L.U_c = take((size_t)Hp * Hp * es);
+  L.Hs_c = take((size_t)(MpMax + Bp) * Hp * es);
+  L.ZT = take((size_t)Vp * MpMax * es);
+  L.dA_c = take((size_t)(MpMax + Bp) * Hp * es);
+  L.X32 = take((size_t)MpMax * Hp * 4);
+  L.dHs32 = take((size_t)MpMax * Hp * 4);
+  L.dA32 = take((size_t)MpMax * Hp * 4);
+  L.part32 = take((size_t)L.partElems * 4);
+  L.stat = take((size_t)nPart * MpMax * 8);
+  L.lse = take((size_t)MpMax * 4);
+  L.zy = take((size_t)MpMax * 4);
+  L.logp_int = take((size_t)MpMax * 4);
+  L.xp = take((size_t)MpMax * 4);
+  L.yp = take((size_t)MpMax * 4);
+  L.perm = take((size_t)MpMax * 4);
+  L.seg = take((size_t)(MpMax + 1) * 4);
+  L.xtmp = take((size_t)c.T_max * c.B * 4);
+  L.ytmp = take((size_t)c.T_max * c.B * 4);
+  L.scalars = take(256);  // [0]: int nseg, [8..15]: int flags[2], [32]: double sum, [40]: double running
+  L.total = o;
+}
+
+template <typename P>
+P *at(rnnlm_t *h, size_t off) {
+  return reinterpret_cast<P *>(h->ws + off);
+}
+int32_t *p_nseg(rnnlm_t *h) { return at<int32_t>(h, h->L.scalars); }
+int32_t *p_flags(rnnlm_t *h) { return at<int32_t>(h, h->L.scalars + 8); }
+double *p_sum(rnnlm_t *h) { return at<double>(h, h->L.scalars + 32); }
+double *p_running(rnnlm_t *h) { return at<double>(h, h->L.scalars + 40); }
+
+inline unsigned blocks_for(long n, int per) { return (unsigned)((n + per - 1) / per); }
+
+template <typename T>
+int sync_copies(rnnlm_t *h, hipStream_t st) {
+  const rnnlm_config &c = h->cfg;
+  const long nWo = (long)h->Vp * h->Hp, nU = (long)h->Hp * h->Hp;
+  hipLaunchKernelGGL(to_compute_copy_kernel<T>, dim3(std::min<long>(blocks_for(nWo, 256), 65535)), dim3(256), 0, st,
+                     h->buf.Wo, c.V, c.H, h->Hp, nWo, at<T>(h, h->L.Wo_c));
+  hipLaunchKernelGGL(to_compute_copy_kernel<T>, dim3(std::min<long>(blocks_for(nU, 256), 65535)), dim3(256), 0, st,
+                     h->buf.U, c.H, c.H, h->Hp, nU, at<T>(h, h->L.U_c));
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+struct UpdateTargets {
+  // where each fused update writes: training -> the masters (alpha 1, lr), gradient export -> caller
+  // buffers (alpha 0, lr -1, no compute-copy refresh, no state advance)
+  float *E, *U, *Wo, *b;
+  float alpha, lr;
+  bool refresh_copies;
+  bool advance_state;
+};
+
+// Forward half of a window: tokens -> padded ids, state -> slot 0, gather, T recurrent steps,
+// output layer with fused statistics, log-probabilities.
+template <typename T>
+int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *logp_out, bool advance_state,
+                   hipStream_t st) {
+  const rnnlm_config &c = h->cfg;
+  const int Hp = h->Hp, Bp = h->Bp, Vp = h->Vp;
+  const int Mrows = Tn * Bp;
+  const int Mp = (int)round_up(Mrows, PAD_M);
+  const long ldz = h->MpMax;
+  T *Hs_c = at<T>(h, h->L.Hs_c);
+  float *X32 = at<float>(h, h->L.X32);
+  int32_t *xp = at<int32_t>(h, h->L.xp), *yp = at<int32_t>(h, h->L.yp);
+  float *lse = at<float>(h, h->L.lse), *zy = at<float>(h, h->L.zy);
+
+  hipLaunchKernelGGL(prep_tokens_kernel, dim3(blocks_for(Mp, 256)), dim3(256), 0, st, x, y, Tn, c.B, Bp, Mp, c.V, xp,
+                     yp, lse, p_flags(h));
+  hipLaunchKernelGGL(state_to_slot_kernel<T>, dim3(blocks_for((long)Bp * Hp, 256)), dim3(256), 0, st, h->buf.h_state,
+                     c.B, c.H, Bp, Hp, Hs_c);
+  hipLaunchKernelGGL(gather_kernel, dim3(Mrows), dim3(256), 0, st, h->buf.E, xp, c.H, Hp, X32);
+  HIP_TRY(hipGetLastError());
+
+  for (int t = 0; t < Tn; ++t) {
+    EpiRnnFwd<T> epi;
+    epi.X = X32 + (long)t * Bp * Hp;
+    epi.Hnext = Hs_c + (long)(t + 1) * Bp * Hp;
+    epi.h_state = (advance_state && t == Tn - 1) ? h->buf.h_state : nullptr;
+    epi.B = c.B;
+    epi.H = c.H;
+    epi.ld = Hp;
+    HIP_TRY((launch_gemm<T, 32, 64, 1, 2, ROWK, ROWK>(st, Hs_c + (long)t * Bp * Hp, Hp, at<T>(h, h->L.U_c), Hp, Bp, Hp,
+                                                      Hp, 1, epi)));
+  }
+  {
+    EpiOutFwd<T> epi;
+    epi.b = h->buf.b;
+    epi.ZT = at<T>(h, h->L.ZT);
+    epi.part = at<float2>(h, h->L.stat);
+    epi.yp = yp;
+    epi.zy = zy;
+    epi.V = c.V;
+    epi.ldz = ldz;
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, ROWK>(st, at<T>(h, h->L.Wo_c), Hp, Hs_c + (long)Bp * Hp, Hp, Vp, Mp,
+                                                        Hp, 1, epi)));
+  }
+  hipLaunchKernelGGL(merge_stats_kernel, dim3(blocks_for(Mrows, 256)), dim3(256), 0, st, at<float2>(h, h->L.stat),
+                     h->nPart, ldz, Tn, c.B, Bp, zy, lse, at<float>(h, h->L.logp_int), logp_out);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+template <typename T>
+int sort_segments(rnnlm_t *h, int Tn, int32_t *perm, int32_t *seg, int32_t *nseg, hipStream_t st) {
+  const int M = Tn * h->cfg.B;
+  hipLaunchKernelGGL(rank_sort_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, st, at<int32_t>(h, h->L.xp), M,
+                     h->cfg.B, h->Bp, perm);
+  hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(1024), 0, st, at<int32_t>(h, h->L.xp), perm, M, h->cfg.B, h->Bp,
+                     seg, nseg);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+// Backward half of a window + fused updates.
+template <typename T>
+int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) {
+  const rnnlm_config &c = h->cfg;
+  const int Hp = h->Hp, Bp = h->Bp, Vp = h->Vp;
+  const int Mrows = Tn * Bp;
+  const int Mp = (int)round_up(Mrows, PAD_M);
+  const long ldz = h->MpMax;
+  constexpr int BK = Elem<T>::BK;
+  T *Hs_c = at<T>(h, h->L.Hs_c);
+  T *ZT = at<T>(h, h->L.ZT);
+  T *Wo_c = at<T>(h, h->L.Wo_c);
+  T *U_c = at<T>(h, h->L.U_c);
+  T *dA_c = at<T>(h, h->L.dA_c);
+  float *dA32 = at<float>(h, h->L.dA32);
+  float *dHs32 = at<float>(h, h->L.dHs32);
+  int32_t *xp = at<int32_t>(h, h->L.xp), *yp = at<int32_t>(h, h->L.yp);
+  int32_t *perm = at<int32_t>(h, h->L.perm), *seg = at<int32_t>(h, h->L.seg);
+
+  // integer helpers of the embedding update (independent of everything above)
+  int rc = sort_segments<T>(h, Tn, perm, seg, p_nseg(h), st);
+  if (rc) return rc;
+
+  // fused softmax gradient + bias update, in place on the vocabulary-major logits
+  hipLaunchKernelGGL(softmax_grad_kernel<T>, dim3(Vp / 4), dim3(256), 0, st, ZT, ldz, Mp, c.V, Vp,
+                     at<float>(h, h->L.lse), yp, 1.0f / (float)(Tn * c.B), h->buf.b, u.b, u.alpha, u.lr);
+  HIP_TRY(hipGetLastError());
+
+  // dHs[m][j] = sum_v dz[v][m] Wo[v][j]   (contraction over the vocabulary, split-K)
+  {
+    int S = desired_splits(Mp, Hp, Vp / BK);
+    const long per = (long)Mp * Hp;
+    if ((long)S * per > h->L.partElems) S = (int)(h->L.partElems / per);
+    if (S < 1) S = 1;
+    EpiPartial epi;
+    epi.part = (S == 1) ? dHs32 : at<float>(h, h->L.part32);
+    epi.ld = Hp;
+    epi.split_stride = per;
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, ZT, ldz, Wo_c, Hp, Mp, Hp, Vp, S, epi)));
+    if (S > 1) {
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks_for(per / 4, 256)), dim3(256), 0, st,
+                         at<float>(h, h->L.part32), per, per, S, dHs32);
+      HIP_TRY(hipGetLastError());
+    }
+  }
+
+  // rows [Mrows, Mp) of dA take part in the dU contraction: keep them zero
+  if (Mp > Mrows) {
+    const long n = (long)(Mp - Mrows) * Hp * (long)sizeof(T) / 4;
+    hipLaunchKernelGGL(fill_kernel<uint32_t>, dim3(blocks_for(n, 256)), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t *>(dA_c + (long)Mrows * Hp), n, 0u);
+  }
+
+  // back-propagation through time over the window (stops at the window start)
+  for (int t = Tn - 1; t >= 0; --t) {
+    EpiRnnBwd<T> epi;
+    epi.dHs = dHs32 + (long)t * Bp * Hp;
+    epi.Hs = Hs_c + (long)(t + 1) * Bp * Hp;
+    epi.dA32 = dA32 + (long)t * Bp * Hp;
+    epi.dAc = dA_c + (long)t * Bp * Hp;
+    epi.B = c.B;
+    epi.H = c.H;
+    epi.ld = Hp;
+    const long K = (t == Tn - 1) ? 0 : Hp;
+    HIP_TRY((launch_gemm<T, 32, 64, 1, 2, ROWK, KROW>(st, dA_c + (long)(t + 1) * Bp * Hp, Hp, U_c, Hp, Bp, Hp, K, 1,
+                                                      epi)));
+  }
+
+  // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j]
+  {
+    EpiSgd<T> epi;
+    epi.W = h->buf.Wo;
+    epi.out = u.Wo;
+    epi.Wc = u.refresh_copies ? Wo_c : nullptr;
+    epi.ldw = c.H;
+    epi.ldc = Hp;
+    epi.R = c.V;
+    epi.C = c.H;
+    epi.alpha = u.alpha;
+    epi.lr = u.lr;
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, KROW>(st, ZT, ldz, Hs_c + (long)Bp * Hp, Hp, Vp, Hp, Mp, 1, epi)));
+  }
+  // U[i][j] -= lr * sum_m dA[m][i] Hprev[m][j]
+  {
+    EpiSgd<T> epi;
+    epi.W = h->buf.U;
+    epi.out = u.U;
+    epi.Wc = u.refresh_copies ? U_c : nullptr;
+    epi.ldw = c.H;
+    epi.ldc = Hp;
+    epi.R = c.H;
+    epi.C = c.H;
+    epi.alpha = u.alpha;
+    epi.lr = u.lr;
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, dA_c, Hp, Hs_c, Hp, Hp, Hp, Mp, 1, epi)));
+  }
+  // E[w] -= lr * sum_{m: x[m] = w} dA[m]
+  hipLaunchKernelGGL(scatter_update_kernel, dim3(Tn * c.B, (c.H + 255) / 256), dim3(256), 0, st, dA32, Hp, c.H, c.B, Bp,
+                     xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+template <typename T>
+int window_call(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *logp, double *sum_logp,
+                const UpdateTargets *u, bool advance_state, hipStream_t st) {
+  int rc = forward_window<T>(h, x, y, Tn, logp, advance_state, st);
+  if (rc) return rc;
+  if (sum_logp || u) {
+    hipLaunchKernelGGL(sum_logp_kernel, dim3(1), dim3(1024), 0, st, at<float>(h, h->L.logp_int), Tn * h->cfg.B,
+                       sum_logp ? sum_logp : p_sum(h), (double *)nullptr, p_flags(h));
+    HIP_TRY(hipGetLastError());
+  }
+  if (u) rc = backward_window<T>(h, Tn, *u, st);
+  return rc;
+}
+
+bool window_args_ok(rnnlm_t *h, const int32_t *x, const int32_t *y, int T) {
+  return h && x && y && T >= 1 && T <= h->cfg.T_max;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t rnnlm_workspace_bytes(const rnnlm_config *cfg) {
+  if (!cfg_ok(cfg)) return 0;
+  int Hp, Vp, Bp, MpMax, nPart;
+  WsLayout L;
+  make_layout(*cfg, Hp, Vp, Bp, MpMax, nPart, L);
+  return L.total;
+}
+
+int rnnlm_init(const rnnlm_config *cfg, const rnnlm_buffers *buf, rnnlm_t **out) {
+  if (!out) return RNNLM_ERR_ARG;
+  *out = nullptr;
+  if (!cfg_ok(cfg) || !buf) return RNNLM_ERR_ARG;
+  if (!buf->E || !buf->U || !buf->Wo || !buf->b || !buf->h_state || !buf->workspace) return RNNLM_ERR_ARG;
+  if (reinterpret_cast<uintptr_t>(buf->workspace) & 255) return RNNLM_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(buf->E) | reinterpret_cast<uintptr_t>(buf->U) |
+       reinterpret_cast<uintptr_t>(buf->Wo) | reinterpret_cast<uintptr_t>(buf->b) |
+       reinterpret_cast<uintptr_t>(buf->h_state)) & 15)
+    return RNNLM_ERR_ARG;
+  rnnlm_t *h = new (std::nothrow) rnnlm_t;
+  if (!h) return RNNLM_ERR_NOMEM;
+  h->cfg = *cfg;
+  h->buf = *buf;
+  make_layout(*cfg, h->Hp, h->Vp, h->Bp, h->MpMax, h->nPart, h->L);
+  if (buf->workspace_bytes < h->L.total) {
+    delete h;
+    return RNNLM_ERR_ARG;
+  }
+  h->ws = static_cast<char *>(buf->workspace);
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device >= ndev || hipSetDevice(cfg->device) != hipSuccess) {
+    delete h;
+    return RNNLM_ERR_HIP;
+  }
+  int rc = RNNLM_OK;
+  if (hipMemsetAsync(h->ws, 0, h->L.total, nullptr) != hipSuccess ||
+      hipMemsetAsync(buf->h_state, 0, sizeof(float) * (size_t)cfg->B * cfg->H, nullptr) != hipSuccess)
+    rc = RNNLM_ERR_HIP;
+  if (rc == RNNLM_OK)
+    rc = (cfg->precision == RNNLM_FP32) ? sync_copies<float>(h, nullptr) : sync_copies<bf16_t>(h, nullptr);
+  if (rc == RNNLM_OK && hipDeviceSynchronize() != hipSuccess) rc = RNNLM_ERR_HIP;
+  if (rc != RNNLM_OK) {
+    delete h;
+    return rc;
+  }
+  *out = h;
+  return RNNLM_OK;
+}
+
+void rnnlm_free(rnnlm_t *h) { delete h; }
+
+int rnnlm_stream_chunk(rnnlm_t *h, const int32_t *tok, int64_t N, int64_t k, int32_t T, int32_t *x, int32_t *y,
+                       void *stream) {
+  if (!h || !tok || !x || !y || N < 2 || T < 1 || T > h->cfg.T_max) return RNNLM_ERR_ARG;
+  const long L = (long)((N - 1) / h->cfg.B);
+  if (k < 0 || k >= L / T) return RNNLM_ERR_ARG;
+  hipLaunchKernelGGL(stream_chunk_kernel, dim3(blocks_for((long)T * h->cfg.B, 256)), dim3(256), 0, (hipStream_t)stream,
+                     tok, L, (long)k, T, h->cfg.B, x, y);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+int rnnlm_forward_logprob(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *logp, void *stream) {
+  if (!window_args_ok(h, x, y, T) || !logp) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, logp, nullptr, nullptr, true, st)
+                                          : window_call<bf16_t>(h, x, y, T, logp, nullptr, nullptr, true, st);
+}
+
+int rnnlm_train_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lr, float *logp,
+                      double *sum_logp, void *stream) {
+  if (!window_args_ok(h, x, y, T) || !(lr == lr)) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  UpdateTargets u{h->buf.E, h->buf.U, h->buf.Wo, h->buf.b, 1.0f, lr, true, true};
+  return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, logp, sum_logp, &u, true, st)
+                                          : window_call<bf16_t>(h, x, y, T, logp, sum_logp, &u, true, st);
+}
+
+int rnnlm_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *dE, float *dU, float *dWo,
+                     float *db, float *logp, void *stream) {
+  if (!window_args_ok(h, x, y, T) || !dE || !dU || !dWo || !db) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const long nE = (long)h->cfg.V * h->cfg.H;
+  hipLaunchKernelGGL(fill_kernel<float>, dim3(std::min<long>(blocks_for(nE, 256), 65535)), dim3(256), 0, st, dE, nE,
+                     0.0f);
+  HIP_TRY(hipGetLastError());
+  UpdateTargets u{dE, dU, dWo, db, 0.0f, -1.0f, false, false};
+  return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, logp, nullptr, &u, false, st)
+                                          : window_call<bf16_t>(h, x, y, T, logp, nullptr, &u, false, st);
+}
+
+int rnnlm_reset_state(rnnlm_t *h, void *stream) {
+  if (!h) return RNNLM_ERR_ARG;
+  const long n = (long)h->cfg.B * h->cfg.H;
+  hipLaunchKernelGGL(fill_kernel<float>, dim3(blocks_for(n, 256)), dim3(256), 0, (hipStream_t)stream, h->buf.h_state, n,
+                     0.0f);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+int rnnlm_sync_compute_copies(rnnlm_t *h, void *stream) {
+  if (!h) return RNNLM_ERR_ARG;
+  return (h->cfg.precision == RNNLM_FP32) ? sync_copies<float>(h, (hipStream_t)stream)
+                                          : sync_copies<bf16_t>(h, (hipStream_t)stream);
+}
+
+int rnnlm_check(rnnlm_t *h, void *stream) {
+  if (!h) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  int32_t flags[2] = {0, 0};
+  HIP_TRY(hipMemcpyAsync(flags, p_flags(h), sizeof(flags), hipMemcpyDeviceToHost, st));
+  hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(1), dim3(64), 0, st, p_flags(h), 2L, 0);
+  HIP_TRY(hipStreamSynchronize(st));
+  if (flags[0]) return RNNLM_ERR_TOKEN_RANGE;
+  if (flags[1]) return RNNLM_ERR_NONFINITE;
+  return RNNLM_OK;
+}
+
+int rnnlm_perplexity(rnnlm_t *h, const int32_t *tok, int64_t N, int32_t T, double *ppl, int64_t *scored,
+                     void *stream) {
+  if (!h || !tok || !ppl || N < 2 || T < 1 || T > h->cfg.T_max) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const int B = h->cfg.B;
+  const long L = (long)((N - 1) / B);
+  const long nchunks = L / T;
+  if (nchunks < 1) return RNNLM_ERR_ARG;
+  int rc = rnnlm_reset_state(h, stream);
+  if (rc) return rc;
+  hipLaunchKernelGGL(fill_kernel<double>, dim3(1), dim3(64), 0, st, p_running(h), 1L, 0.0);
+  int32_t *xt = at<int32_t>(h, h->L.xtmp), *yt = at<int32_t>(h, h->L.ytmp);
+  for (long k = 0; k < nchunks; ++k) {
+    hipLaunchKernelGGL(stream_chunk_kernel, dim3(blocks_for((long)T * B, 256)), dim3(256), 0, st, tok, L, k, T, B, xt,
+                       yt);
+    rc = (h->cfg.precision == RNNLM_FP32) ? forward_window<float>(h, xt, yt, T, nullptr, true, st)
+                                          : forward_window<bf16_t>(h, xt, yt, T, nullptr, true, st);
+    if (rc) return rc;
+    hipLaunchKernelGGL(sum_logp_kernel, dim3(1), dim3(1024), 0, st, at<float>(h, h->L.logp_int), T * B,
+                       (double *)nullptr, p_running(h), p_flags(h));
+  }
+  HIP_TRY(hipGetLastError());
+  double total = 0.0;
+  HIP_TRY(hipMemcpyAsync(&total, p_running(h), sizeof(double), hipMemcpyDeviceToHost, st));
+  rc = rnnlm_check(h, stream);
+  if (rc) return rc;
+  const long n = nchunks * (long)B * T;
+  *ppl = exp(-total / (double)n);
+  if (scored) *scored = n;
+  if (!(total == total) || total - total != 0.0) return RNNLM_ERR_NONFINITE;
+  return RNNLM_OK;
+}
+
+int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, int32_t *seg_start, int32_t *nseg,
+                        void *stream) {
+  if (!h || !x || !perm || !seg_start || !nseg || T < 1 || T > h->cfg.T_max) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const int Mp = (int)round_up((long)T * h->Bp, PAD_M);
+  hipLaunchKernelGGL(prep_tokens_kernel, dim3(blocks_for(Mp, 256)), dim3(256), 0, st, x, (const int32_t *)nullptr, T,
+                     h->cfg.B, h->Bp, Mp, h->cfg.V, at<int32_t>(h, h->L.xp), (int32_t *)nullptr, at<float>(h, h->L.lse),
+                     p_flags(h));
+  HIP_TRY(hipGetLastError());
+  return sort_segments<float>(h, T, perm, seg_start, nseg, st);
+}
+
+const char *rnnlm_status_string(int status) {
+  switch (status) {
+    case RNNLM_OK: return "ok";
+    case RNNLM_ERR_ARG: return "invalid argument";
+    case RNNLM_ERR_TOKEN_RANGE: return "token id out of range";
+    case RNNLM_ERR_NONFINITE: return "non-finite log-probability sum";
+    case RNNLM_ERR_HIP: return "HIP runtime error";
+    case RNNLM_ERR_NOMEM: return "host allocation failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,257 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Tolerances (fp32 path): log-probs |d| <= 1e-4*|ref| + 1e-6; gradients per tensor
+max|d| <= 1e-3*max|ref| and ||d||_2 <= 1e-3*||ref||_2; bf16 path: window perplexity within 1e-2
+relative.  Integer results (stream indexing, sort permutation, run starts) are bit-exact."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_1502_00512_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+FP32, BF16 = binding.RNNLM_FP32, binding.RNNLM_BF16_FP32MASTER
+
+
+def make_pair(V, H, B, T_max, precision, seed=1, init="uniform", scale=0.1, bias_scale=0.0):
+    E, U, Wo, b = synth.make_weights(V, H, init, scale, seed)
+    if bias_scale:
+        b = synth.uniform_weights((V,), -bias_scale, bias_scale, seed + 99)
+    g = binding.Rnnlm(E, U, Wo, b, B, T_max, precision)
+    o = O.Model.from_weights(E, U, Wo, b, B)
+    return g, o
+
+
+def tokens(V, n, seed, s=1.1):
+    return synth.zipf_tokens(n, V, s, seed)
+
+
+def dev(a):
+    return torch.as_tensor(np.ascontiguousarray(a)).cuda()
+
+
+def check_logp(got, ref, rel=1e-4, abs_=1e-6):
+    got = got.detach().cpu().numpy().astype(np.float64)
+    bad = np.abs(got - ref) > rel * np.abs(ref) + abs_
+    assert not bad.any(), f"max |d| = {np.abs(got - ref).max():.3e} at ref {ref[bad][:3]}"
+
+
+def check_grad(name, got, ref, rel=1e-3):
+    got = got.detach().cpu().numpy().astype(np.float64)
+    d = got - ref
+    assert np.isfinite(got).all(), name
+    assert np.abs(d).max() <= rel * np.abs(ref).max(), f"{name}: max {np.abs(d).max():.3e} vs {np.abs(ref).max():.3e}"
+    assert np.linalg.norm(d) <= rel * np.linalg.norm(ref), f"{name}: l2 {np.linalg.norm(d):.3e} vs {np.linalg.norm(ref):.3e}"
+
+
+SHAPES_FP32 = [
+    # V, H, B, T   (cfg1; ragged everything; several tiles + ragged tail; cfg2 shape; T = 1; B > 32)
+    (1000, 64, 4, 8),
+    (777, 50, 5, 7),
+    (3001, 200, 33, 3),
+    (10000, 256, 32, 10),
+    (300, 130, 3, 1),
+    (520, 96, 70, 2),
+]
+
+
+def test_stream_chunk_bit_exact():
+    g, _ = make_pair(500, 32, 6, 9, FP32)
+    tok = tokens(500, 2000, 3)
+    dtok = dev(tok)
+    for T in (9, 4, 1):
+        n = O.num_chunks(tok.size, 6, T)
+        for k in (0, 1, n // 2, n - 1):
+            x, y = g.rnnlm_stream_chunk(dtok, k, T)
+            xr, yr = O.stream_chunk(tok, 6, T, k)
+            assert np.array_equal(x.cpu().numpy(), xr) and np.array_equal(y.cpu().numpy(), yr)
+        with pytest.raises(binding.RnnlmError):
+            g.rnnlm_stream_chunk(dtok, n, T)
+
+
+@pytest.mark.parametrize("V,B,T,s", [(50, 4, 8, 1.1), (1000, 128, 20, 1.05), (7, 33, 40, 1.0), (100000, 256, 32, 1.0)])
+def test_sort_segments_bit_exact(V, B, T, s):
+    g, _ = make_pair(V if V < 5000 else 100000, 8, B, T, FP32) if V < 5000 else (None, None)
+    if g is None:
+        E = np.zeros((V, 8), np.float32)
+        g = binding.Rnnlm(E, np.zeros((8, 8), np.float32), E, np.zeros(V, np.float32), B, T, FP32)
+    x = tokens(V, B * T, 17, s).reshape(T, B)
+    perm, seg = g.rnnlm_sort_segments(dev(x))
+    pr, sr = O.sort_segments(x)
+    assert np.array_equal(perm.cpu().numpy(), pr)
+    assert np.array_equal(seg.cpu().numpy(), sr)
+
+
+@pytest.mark.parametrize("V,H,B,T", SHAPES_FP32)
+def test_forward_logprob_fp32(V, H, B, T):
+    g, o = make_pair(V, H, B, T, FP32, seed=V + H, scale=0.3, bias_scale=0.5)
+    tok = tokens(V, 3 * B * T + B + 1, 5)
+    dtok = dev(tok)
+    for k in range(3):  # three windows: exercises the carried state
+        x, y = g.rnnlm_stream_chunk(dtok, k, T)
+        got = g.rnnlm_forward_logprob(x, y)
+        xr, yr = O.stream_chunk(tok, B, T, k)
+        ref = O.forward_logprob(o, xr, yr)
+        check_logp(got, ref)
+        assert np.abs(g.h_state.cpu().numpy() - o.h).max() < 2e-5
+    g.rnnlm_check()
+
+
+@pytest.mark.parametrize("V,H,B,T", SHAPES_FP32)
+def test_grad_chunk_fp32(V, H, B, T):
+    g, o = make_pair(V, H, B, T, FP32, seed=2 * V + H, scale=0.3, bias_scale=0.5)
+    tok = tokens(V, 2 * B * T + B + 1, 6)
+    x, y = O.stream_chunk(tok, B, T, 0)
+    # non-zero carried state: score one window first on both sides
+    g.rnnlm_forward_logprob(dev(x), dev(y))
+    O.forward_logprob(o, x, y)
+    x, y = O.stream_chunk(tok, B, T, 1)
+    before = [t.clone() for t in (g.E, g.U, g.Wo, g.b, g.h_state)]
+    r = g.rnnlm_grad_chunk(dev(x), dev(y))
+    ref = O.grad_chunk(o, x, y)
+    check_logp(r["logp"], ref["logp"])
+    for k in ("gE", "gU", "gWo", "gb"):
+        check_grad(k, r[k], ref[k])
+    for a, c in zip(before, (g.E, g.U, g.Wo, g.b, g.h_state)):
+        assert torch.equal(a, c)  # gradient export leaves parameters and state untouched
+    # rows of gE for ids not in the window are exactly zero
+    unseen = np.setdiff1d(np.arange(V), x.ravel())
+    assert not r["gE"].cpu().numpy()[unseen].any()
+    g.rnnlm_check()
+
+
+@pytest.mark.parametrize("V,H,B,T,K", [(1000, 64, 4, 8, 12), (2500, 160, 20, 5, 6)])
+def test_train_chunks_fp32(V, H, B, T, K):
+    lr = 0.1
+    g, o = make_pair(V, H, B, T, FP32, seed=7, scale=0.1)
+    tok = tokens(V, K * B * T + B + 1, 8)
+    dtok = dev(tok)
+    logp = torch.empty(T, B, device="cuda")
+    s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for k in range(K):
+        x, y = g.rnnlm_stream_chunk(dtok, k, T)
+        g.rnnlm_train_chunk(x, y, lr, logp, s)
+        xr, yr = O.stream_chunk(tok, B, T, k)
+        ref, sref = O.train_chunk(o, xr, yr, lr)
+        check_logp(logp, ref, rel=2e-4)
+        assert abs(s.item() - sref) <= 2e-4 * abs(sref)
+    for name, a, c in (("E", g.E, o.E), ("U", g.U, o.U), ("Wo", g.Wo, o.Wo), ("b", g.b, o.b), ("h", g.h_state, o.h)):
+        d = np.abs(a.cpu().numpy() - c).max()
+        assert d <= 1e-4 * max(1.0, np.abs(c).max()), (name, d)
+    g.rnnlm_check()
+
+
+def test_lr_zero_keeps_parameters_bitwise_and_advances_state():
+    g, o = make_pair(400, 48, 6, 5, FP32, seed=11)
+    tok = tokens(400, 100, 2)
+    x, y = O.stream_chunk(tok, 6, 5, 0)
+    before = [t.clone() for t in (g.E, g.U, g.Wo, g.b)]
+    g.rnnlm_train_chunk(dev(x), dev(y), 0.0)
+    for a, c in zip(before, (g.E, g.U, g.Wo, g.b)):
+        assert torch.equal(a, c)
+    O.forward_logprob(o, x, y)
+    assert np.abs(g.h_state.cpu().numpy() - o.h).max() < 2e-5 and g.h_state.abs().max() > 0
+
+
+def test_shorter_window_after_longer_one():
+    """T smaller than T_max, after a call with a larger T left data behind in the workspace."""
+    V, H, B, Tm = 600, 72, 9, 11
+    g, o = make_pair(V, H, B, Tm, FP32, seed=13, scale=0.3)
+    tok = tokens(V, 400, 4)
+    for T, k in ((11, 0), (3, 1), (7, 0)):
+        x, y = O.stream_chunk(tok, B, T, k)
+        r = g.rnnlm_grad_chunk(dev(x), dev(y))
+        ref = O.grad_chunk(o, x, y)
+        for kk in ("gE", "gU", "gWo", "gb"):
+            check_grad(kk, r[kk], ref[kk])
+        g.rnnlm_train_chunk(dev(x), dev(y), 0.2)
+        O.train_chunk(o, x, y, 0.2)
+
+
+@pytest.mark.parametrize("precision", [FP32, BF16])
+def test_bitwise_determinism(precision):
+    V, H, B, T, K = 2000, 128, 16, 6, 5
+    tok = tokens(V, K * B * T + B + 1, 9)
+    outs = []
+    for _ in range(2):
+        g, _ = make_pair(V, H, B, T, precision, seed=21)
+        dtok = dev(tok)
+        for k in range(K):
+            x, y = g.rnnlm_stream_chunk(dtok, k, T)
+            g.rnnlm_train_chunk(x, y, 0.1)
+        outs.append([t.clone() for t in (g.E, g.U, g.Wo, g.b, g.h_state)])
+    for a, c in zip(*outs):
+        assert torch.equal(a, c)
+
+
+def test_uniform_model_perplexity_is_V():
+    V, H, B, T = 900, 40, 5, 6
+    E, U, _, _ = synth.make_weights(V, H, "uniform", 0.5, 3)
+    g = binding.Rnnlm(E, U, np.zeros((V, H), np.float32), np.zeros(V, np.float32), B, T, FP32)
+    ppl, scored = g.rnnlm_perplexity(dev(tokens(V, 500, 1)), T)
+    assert scored == ((500 - 1) // B // T) * B * T
+    assert abs(ppl / V - 1) < 1e-5
+
+
+@pytest.mark.parametrize("precision,tol", [(FP32, 1e-4), (BF16, 1e-2)])
+def test_perplexity_call(precision, tol):
+    V, H, B, T = 1500, 96, 7, 5
+    g, o = make_pair(V, H, B, T, precision, seed=31, scale=0.4, bias_scale=0.5)
+    tok = tokens(V, 700, 12)
+    ppl, scored = g.rnnlm_perplexity(dev(tok), T)
+    ref, sref = O.perplexity(o, tok, T)
+    assert scored == sref and abs(ppl / ref - 1) < tol
+
+
+def test_token_out_of_range_is_reported_not_faulted():
+    g, _ = make_pair(100, 16, 2, 4, FP32)
+    x = torch.tensor([[0, 1], [2, 100], [3, 4], [5, 6]], dtype=torch.int32, device="cuda")
+    y = torch.tensor([[1, 2], [3, 4], [-1, 5], [6, 7]], dtype=torch.int32, device="cuda")
+    g.rnnlm_forward_logprob(x, y)
+    with pytest.raises(binding.RnnlmError) as e:
+        g.rnnlm_check()
+    assert e.value.status == -2
+    g.rnnlm_check()  # flag was cleared
+    with pytest.raises(binding.RnnlmError):
+        g.rnnlm_forward_logprob(torch.zeros(5, 2, dtype=torch.int32, device="cuda"),
+                                torch.zeros(5, 2, dtype=torch.int32, device="cuda"))  # T > T_max
+
+
+BF16_SHAPES = [(3000, 256, 32, 4), (2049, 130, 5, 9), (5000, 384, 64, 6)]
+
+
+@pytest.mark.parametrize("V,H,B,T", BF16_SHAPES)
+def test_bf16_window_perplexity_and_gradients(V, H, B, T):
+    g, o = make_pair(V, H, B, T, BF16, seed=41, init="normal", scale=0.05, bias_scale=0.3)
+    tok = tokens(V, 2 * B * T + B + 1, 14, 1.05)
+    x, y = O.stream_chunk(tok, B, T, 0)
+    r = g.rnnlm_grad_chunk(dev(x), dev(y))
+    ref = O.grad_chunk(o, x, y)
+    ppl_g = math.exp(-r["logp"].double().mean().item())
+    ppl_r = math.exp(-ref["logp"].mean())
+    assert abs(ppl_g / ppl_r - 1) < 1e-2
+    # bf16 operands: gradients agree to a few parts in a thousand of each tensor's scale
+    for k in ("gE", "gU", "gWo", "gb"):
+        check_grad(k, r[k], ref[k], rel=2e-2)
+
+
+def test_bf16_training_tracks_oracle():
+    """Both sides train on their own for K windows from identical weights; window perplexity agrees
+    to 1e-2 at the start and at the end."""
+    V, H, B, T, K, lr = 4000, 256, 32, 8, 50, 0.1
+    g, o = make_pair(V, H, B, T, BF16, seed=43, init="normal", scale=0.05)
+    tok = tokens(V, (K + 1) * B * T + B + 1, 15, 1.05)
+    dtok = dev(tok)
+    logp = torch.empty(T, B, device="cuda")
+    ratios = []
+    for k in range(K):
+        x, y = g.rnnlm_stream_chunk(dtok, k, T)
+        g.rnnlm_train_chunk(x, y, lr, logp)
+        ref, _ = O.train_chunk(o, *O.stream_chunk(tok, B, T, k), lr)
+        ratios.append(math.exp(-logp.double().mean().item()) / math.exp(-ref.mean()))
+    assert abs(ratios[0] - 1) < 1e-2 and abs(ratios[-1] - 1) < 1e-2, (ratios[0], ratios[-1])
+    assert max(abs(r - 1) for r in ratios) < 2e-2
+    g.rnnlm_check()
