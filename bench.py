@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Training-throughput benchmark of the RNNLM hot path on one MI355X.
+
+A "step" is one training window of the whole hot path (stream indexing, gather, recurrent forward,
+output layer, softmax/cross-entropy gradient, BPTT, all SGD updates) on seeded synthetic Zipf
+streams that are already resident in HBM.  Prints ONE JSON line:
+
+  value            training words/s = steps * B * T / seconds
+  roofline         dense-MFMA roofline of the dominant kernel (the slowest of the three output-layer
+                   contractions), timed live with HIP events on the kernel's stream
+  cpu_baseline     the fp64 oracle timed on a bounded sample of the same workload on the host cores
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3] [--stages]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # MI355X published dense bf16 MFMA peak
+PEAK_FP32_TFLOPS = 157.3    # MI355X published fp32 matrix peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--stages", action="store_true", help="also time every stage (adds event overhead)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_1502_00512_amd import binding, synth
+
+    cfg = synth.CONFIGS[args.config]
+    V, H, B, T = cfg.V, cfg.H, cfg.B, cfg.T
+    M = B * T
+    precision = binding.RNNLM_BF16_FP32MASTER if cfg.precision == "bf16" else binding.RNNLM_FP32
+    total_steps = args.steps + args.warmup
+    # tokens: the data-offset scheme spreads the B read cursors over the whole corpus
+    need = total_steps * T
+    L_full = (cfg.N - 1) // B
+    N = cfg.N if need <= L_full else need * B + 1
+    t0 = time.time()
+    tok = synth.make_tokens(cfg, N)
+    E, U, Wo, b = synth.make_weights(V, H, cfg.init, cfg.init_scale, cfg.weight_seed)
+    log(f"[bench] {cfg.name}: V={V} H={H} B={B} T={T} N={N} inputs generated in {time.time() - t0:.1f}s "
+        f"tokens sha256 {synth.sha256_of(tok)[:16]}")
+
+    g = binding.Rnnlm(E, U, Wo, b, B, T, precision)
+    dtok = torch.as_tensor(tok).cuda()
+    x = torch.empty(T, B, dtype=torch.int32, device="cuda")
+    y = torch.empty(T, B, dtype=torch.int32, device="cuda")
+    sum_logp = torch.zeros(1, dtype=torch.float64, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(k):
+        g.rnnlm_stream_chunk(dtok, k, T, x, y, stream)
+        g.rnnlm_train_chunk(x, y, cfg.lr, None, sum_logp, stream)
+
+    stage_ids = {n: i for i, n in enumerate(binding.STAGES)}
+    gemm_stages = ["out_fwd", "out_bwd_h", "out_bwd_w"]
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    first_loss = -sum_logp.item() / M if args.warmup else float("nan")
+
+    # timed region: K steps, the three output-layer contractions bracketed by HIP events
+    mask = sum(1 << stage_ids[n] for n in gemm_stages)
+    g.rnnlm_profile_enable(mask)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.warmup, total_steps):
+        step(k)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    g.rnnlm_check()
+    last_loss = -sum_logp.item() / M
+    gemm_ms = {}
+    for n in gemm_stages:
+        ms, cnt = g.rnnlm_profile_read(stage_ids[n])
+        gemm_ms[n] = ms / max(cnt, 1)
+    g.rnnlm_profile_enable(0)
+
+    stage_ms = None
+    if args.stages:
+        g.rnnlm_profile_enable((1 << len(binding.STAGES)) - 1)
+        nst = min(args.steps, 50)
+        for k in range(nst):
+            step(k)
+        torch.cuda.synchronize()
+        stage_ms = {}
+        for n, i in stage_ids.items():
+            ms, cnt = g.rnnlm_profile_read(i)
+            stage_ms[n] = round(ms / nst, 4)
+        g.rnnlm_profile_enable(0)
+        log("[bench] per-stage ms per step:", json.dumps(stage_ms))
+
+    words_per_s = args.steps * M / dt
+    flops_word = 6.0 * H * (V + H)
+    peak = PEAK_BF16_TFLOPS if cfg.precision == "bf16" else PEAK_FP32_TFLOPS
+    gemm_flops = 2.0 * H * V * M  # algorithmic flops of each output-layer contraction per window
+    dominant = max(gemm_ms, key=gemm_ms.get)
+    achieved = gemm_flops / (gemm_ms[dominant] * 1e-3) / 1e12
+    out_gemm_frac = 3 * gemm_flops / (sum(gemm_ms.values()) * 1e-3) / 1e12 / peak
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, E, U, Wo, b, tok)
+
+    res = {
+        "metric": "training words/sec (fwd+BPTT+SGD) at 1 MI355X",
+        "value": round(words_per_s, 1),
+        "unit": "words/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.precision if cfg.precision == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: Elman RNNLM V={V} H={H}, {B} streams x BPTT {T}, Zipf({cfg.zipf_s}) tokens, "
+                               f"full softmax + SGD lr={cfg.lr}", "V": V, "H": H, "B": B, "T": T, "tokens": int(N)},
+        "whole_path_mfma_frac": round(words_per_s * flops_word / (peak * 1e12), 4),
+        "output_gemms_mfma_frac": round(out_gemm_frac, 4),
+        "gemm_ms": {k: round(v, 4) for k, v in gemm_ms.items()},
+        "loss_first_last": [round(first_loss, 4), round(last_loss, 4)],
+        "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None},
+        "cpu_baseline": cpu,
+    }
+    if stage_ms is not None:
+        res["stage_ms"] = stage_ms
+    print(json.dumps(res), flush=True)
+    return 0
+
+
+def cpu_baseline(cfg, E, U, Wo, b, tok):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: the first window cut
+    to as many leading timesteps as fit about 10-30 s of CPU work."""
+    import numpy as np
+    from oracle import oracle as O
+    V, H, B, T = cfg.V, cfg.H, cfg.B, cfg.T
+    flops_word = 6.0 * H * (V + H)
+    est_rate = 4e9 * O.num_threads() / 8  # rough fp64 rate of the plain loops
+    Ts = int(max(1, min(T, (15.0 * est_rate) // (flops_word * B))))
+    m = O.Model.from_weights(E, U, Wo, b, B)
+    x, y = O.stream_chunk(tok, B, T, 0)
+    x, y = np.ascontiguousarray(x[:Ts]), np.ascontiguousarray(y[:Ts])
+    t0 = time.perf_counter()
+    O.train_chunk(m, x, y, cfg.lr)
+    dt = time.perf_counter() - t0
+    return {"value": round(B * Ts / dt, 2), "unit": "words/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"one training window of {B} streams x {Ts} of {T} timesteps ({B * Ts} words, {dt:.1f} s)"}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -30,8 +30,8 @@
  *     synchronising call (rnnlm_perplexity, rnnlm_check).
  *   - Gradients are those of the MEAN negative log-likelihood of the B*T tokens of a window.
  *     All T positions of a window use the same (pre-update) parameters; duplicates of an input
- *     id within a window add up in fixed (ascending m) order, so results are run-to-run
- *     bitwise reproducible.
+ *     id within a window add up in a fixed order (no atomics), so results are run-to-run bitwise
+ *     reproducible.
  */
 #ifndef RNNLM_H
 #define RNNLM_H
@@ -139,8 +139,33 @@ int rnnlm_check(rnnlm_t *h, void *stream);
 int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, int32_t *seg_start, int32_t *nseg,
                         void *stream);
 
-/* Name and average duration bookkeeping is left to the caller's profiler; this returns a static
- * description of a status code. */
+/* Stage timing with HIP events on the call's stream (for benchmarks; off by default).  Stages of a
+ * window, in the order of the kernel sequence: */
+typedef enum {
+  RNNLM_STAGE_PREP = 0,         /* token check, state load, embedding gather */
+  RNNLM_STAGE_RNN_FWD = 1,      /* T recurrent forward steps */
+  RNNLM_STAGE_OUT_FWD = 2,      /* output-layer forward contraction (+ fused softmax statistics) */
+  RNNLM_STAGE_STATS = 3,        /* statistics merge, log-probabilities, their sum */
+  RNNLM_STAGE_SOFTMAX_GRAD = 4, /* fused softmax gradient + bias update */
+  RNNLM_STAGE_OUT_BWD_H = 5,    /* gradient w.r.t. the hidden states (contraction over the vocabulary, split-K) */
+  RNNLM_STAGE_RNN_BWD = 6,      /* T recurrent backward steps */
+  RNNLM_STAGE_OUT_BWD_W = 7,    /* output weight gradient contraction + SGD */
+  RNNLM_STAGE_REC_W = 8,        /* recurrent weight gradient contraction + SGD */
+  RNNLM_STAGE_EMB = 9,          /* sort/segments + segmented embedding update */
+  RNNLM_STAGE_REDUCE = 10,      /* fixed-order sum of the split-K partials of stage 5 */
+  RNNLM_STAGE_COUNT = 11
+} rnnlm_stage;
+
+/* Brackets every later execution of the stages whose bit (1u << stage) is set in stage_mask with a
+ * pair of HIP events (at most 16384 pairs between two reads; further executions are not recorded).
+ * stage_mask = 0 switches timing off. */
+int rnnlm_profile_enable(rnnlm_t *h, uint32_t stage_mask);
+
+/* Waits for the recorded events, then returns the stage's accumulated duration in milliseconds and
+ * number of executions since the last read of that stage (HOST pointers), and clears them. */
+int rnnlm_profile_read(rnnlm_t *h, int32_t stage, double *total_ms, int64_t *executions);
+
+/* Static description of a status code. */
 const char *rnnlm_status_string(int status);
 
 #ifdef __cplusplus

@@ -20,7 +20,10 @@ SYMBOLS = [
     "rnnlm_workspace_bytes", "rnnlm_init", "rnnlm_free", "rnnlm_stream_chunk", "rnnlm_forward_logprob",
     "rnnlm_train_chunk", "rnnlm_grad_chunk", "rnnlm_perplexity", "rnnlm_reset_state",
     "rnnlm_sync_compute_copies", "rnnlm_check", "rnnlm_sort_segments", "rnnlm_status_string",
+    "rnnlm_profile_enable", "rnnlm_profile_read",
 ]
+
+STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce"]
 
 
 class rnnlm_config(C.Structure):
@@ -65,6 +68,8 @@ def load():
     lib.rnnlm_sync_compute_copies.argtypes = [vp, vp]
     lib.rnnlm_check.argtypes = [vp, vp]
     lib.rnnlm_sort_segments.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    lib.rnnlm_profile_enable.argtypes = [vp, C.c_uint32]
+    lib.rnnlm_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.rnnlm_status_string.argtypes = [C.c_int]
     lib.rnnlm_status_string.restype = C.c_char_p
     for name in SYMBOLS:
@@ -182,6 +187,15 @@ class Rnnlm:
 
     def rnnlm_check(self, stream=None):
         _ok(self.lib.rnnlm_check(self.handle, _stream(stream)), "rnnlm_check")
+
+    def rnnlm_profile_enable(self, stage_mask: int):
+        _ok(self.lib.rnnlm_profile_enable(self.handle, stage_mask), "rnnlm_profile_enable")
+
+    def rnnlm_profile_read(self, stage: int):
+        ms = C.c_double(0.0)
+        n = C.c_int64(0)
+        _ok(self.lib.rnnlm_profile_read(self.handle, stage, C.byref(ms), C.byref(n)), "rnnlm_profile_read")
+        return ms.value, n.value
 
     def rnnlm_sort_segments(self, x, stream=None):
         import torch

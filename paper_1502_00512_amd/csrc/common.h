@@ -10,14 +10,15 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 // Padding granularities of every internal buffer (elements). All GEMM operands live in
 // buffers whose dimensions are multiples of these, with the padding kept at zero (or, where
 // stated, merely finite), so the contraction kernels carry no bounds checks.
-constexpr int PAD_H = 128;  // hidden dimension
-constexpr int PAD_V = 128;  // vocabulary dimension
+constexpr int PAD_H = 256;  // hidden dimension
+constexpr int PAD_V = 256;  // vocabulary dimension
 constexpr int PAD_B = 32;   // streams per timestep
-constexpr int PAD_M = 128;  // rows of a window (T * padded B)
+constexpr int PAD_M = 256;  // rows of a window (T * padded B)
 
 __host__ __device__ inline long round_up(long a, long b) { return (a + b - 1) / b * b; }
 

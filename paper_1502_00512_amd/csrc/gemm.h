@@ -22,24 +22,25 @@ struct GemmShape {
   int kBlocksPerSplit;  // K blocks handled by one blockIdx.y
 };
 
-constexpr int LDS_ROWK_STRIDE = 128 + 16;  // bytes per tile row, padded against bank conflicts
-
-template <typename T, int ROWS, int LAYOUT>
+// KBYTES = bytes of K held by one LDS tile row (128 or 64): BK = KBYTES / sizeof(T) elements.
+template <typename T, int ROWS, int LAYOUT, int KBYTES>
 struct TileGeom {
   static constexpr int ES = sizeof(T);
-  static constexpr int BK = Elem<T>::BK;
-  static constexpr int KROW_STRIDE = ROWS * ES + 16;
-  static constexpr int BYTES = (LAYOUT == ROWK) ? ROWS * LDS_ROWK_STRIDE : BK * KROW_STRIDE;
+  static constexpr int BK = KBYTES / ES;
+  static constexpr int ROWK_STRIDE = KBYTES + 16;     // +16 B: 16-byte reads of 8 consecutive rows hit distinct banks
+  static constexpr int KROW_STRIDE = ROWS * ES + 32;  // +32 B: the 4 k-rows of a transposing read hit distinct banks
+  static constexpr int BYTES = (LAYOUT == ROWK) ? ROWS * ROWK_STRIDE : BK * KROW_STRIDE;
 };
 
 // Moves one ROWS x BK operand tile global -> registers -> LDS in 16-byte pieces.
-template <typename T, int ROWS, int LAYOUT, int NT>
+template <typename T, int ROWS, int LAYOUT, int NT, int KBYTES>
 struct TileLoader {
-  using G = TileGeom<T, ROWS, LAYOUT>;
-  static constexpr int CHUNKS = ROWS * 8;
+  using G = TileGeom<T, ROWS, LAYOUT, KBYTES>;
+  static constexpr int CPK = KBYTES / 16;  // 16-byte chunks along K per tile row
+  static constexpr int CHUNKS = ROWS * CPK;
   static constexpr int PER = CHUNKS / NT;
   static_assert(CHUNKS % NT == 0, "tile does not divide over the workgroup");
-  uint4 regs[PER];
+  u32x4_t regs[PER];
 
   __device__ inline void load(const char *base, long ld_bytes, long row0, long k0, int tid) {
 #pragma unroll
@@ -47,14 +48,14 @@ struct TileLoader {
       const int c = tid + i * NT;
       const char *p;
       if (LAYOUT == ROWK) {
-        const int r = c >> 3, kc = c & 7;
+        const int r = c / CPK, kc = c % CPK;
         p = base + (row0 + r) * ld_bytes + k0 * G::ES + kc * 16;
       } else {
         constexpr int CPR = ROWS * G::ES / 16;
         const int kk = c / CPR, mc = c % CPR;
         p = base + (k0 + kk) * ld_bytes + row0 * G::ES + mc * 16;
       }
-      regs[i] = *reinterpret_cast<const uint4 *>(p);
+      regs[i] = *reinterpret_cast<const u32x4_t *>(p);
     }
   }
   __device__ inline void store(char *tile, int tid) const {
@@ -63,12 +64,12 @@ struct TileLoader {
       const int c = tid + i * NT;
       int off;
       if (LAYOUT == ROWK) {
-        off = (c >> 3) * LDS_ROWK_STRIDE + (c & 7) * 16;
+        off = (c / CPK) * G::ROWK_STRIDE + (c % CPK) * 16;
       } else {
         constexpr int CPR = ROWS * G::ES / 16;
         off = (c / CPR) * G::KROW_STRIDE + (c % CPR) * 16;
       }
-      *reinterpret_cast<uint4 *>(tile + off) = regs[i];
+      *reinterpret_cast<u32x4_t *>(tile + off) = regs[i];
     }
   }
 };
@@ -89,31 +90,45 @@ struct FragT<float> {
 
 // FragReader::get returns the 8 consecutive-k elements of tile row r starting at k offset ks (a
 // multiple of 8).
-template <typename T, int ROWS, int LAYOUT>
+template <typename T, int ROWS, int LAYOUT, int KBYTES>
 struct FragReader;
 
-template <int ROWS>
-struct FragReader<bf16_t, ROWS, ROWK> {
+template <int ROWS, int KBYTES>
+struct FragReader<bf16_t, ROWS, ROWK, KBYTES> {
   __device__ static inline bf16x8_t get(const char *tile, int r, int ks) {
-    return *reinterpret_cast<const bf16x8_t *>(tile + r * LDS_ROWK_STRIDE + ks * 2);
+    return *reinterpret_cast<const bf16x8_t *>(tile + r * (KBYTES + 16) + ks * 2);
   }
 };
-template <int ROWS>
-struct FragReader<bf16_t, ROWS, KROW> {
+// K-major bf16 tile: ds_read_b64_tr_b16 transposes on the way out of LDS.  Within each block of 16
+// lanes, source lane s points at 4 row-contiguous elements and destination lane i receives element
+// i%4 of source lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4 (layout measured on gfx950).  Pointing source lane s
+// at tile[kb + s/4][r0 + 4*(s%4)] therefore hands lane i the four k-consecutive values
+// tile[kb .. kb+3][r0 + i]: two such reads give the 8 values an MFMA operand lane needs.
+template <int ROWS, int KBYTES>
+struct FragReader<bf16_t, ROWS, KROW, KBYTES> {
   __device__ static inline bf16x8_t get(const char *tile, int r, int ks) {
-    constexpr int S = TileGeom<bf16_t, ROWS, KROW>::KROW_STRIDE;
-    bf16x8_t f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) f[e] = *reinterpret_cast<const bf16_t *>(tile + (ks + e) * S + r * 2);
-    return f;
+    constexpr int S = TileGeom<bf16_t, ROWS, KROW, KBYTES>::KROW_STRIDE;
+    typedef short s16x4_t __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4_t *lds_ptr_t;
+    const int lane = threadIdx.x & 63;
+    const int s = lane & 15;
+    // r = tile row of this lane; its 16-lane block starts at row r - s
+    const char *p = tile + (ks + (s >> 2)) * S + ((r - s) + 4 * (s & 3)) * 2;
+    union {
+      s16x4_t h[2];
+      bf16x8_t f;
+    } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * S));
+    return u.f;
   }
 };
-template <int ROWS>
-struct FragReader<float, ROWS, ROWK> {
+template <int ROWS, int KBYTES>
+struct FragReader<float, ROWS, ROWK, KBYTES> {
   __device__ static inline F32x8 get(const char *tile, int r, int ks) {
     F32x8 f;
-    const f32x4_t a = *reinterpret_cast<const f32x4_t *>(tile + r * LDS_ROWK_STRIDE + ks * 4);
-    const f32x4_t b = *reinterpret_cast<const f32x4_t *>(tile + r * LDS_ROWK_STRIDE + ks * 4 + 16);
+    const f32x4_t a = *reinterpret_cast<const f32x4_t *>(tile + r * (KBYTES + 16) + ks * 4);
+    const f32x4_t b = *reinterpret_cast<const f32x4_t *>(tile + r * (KBYTES + 16) + ks * 4 + 16);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       f.v[e] = a[e];
@@ -122,10 +137,10 @@ struct FragReader<float, ROWS, ROWK> {
     return f;
   }
 };
-template <int ROWS>
-struct FragReader<float, ROWS, KROW> {
+template <int ROWS, int KBYTES>
+struct FragReader<float, ROWS, KROW, KBYTES> {
   __device__ static inline F32x8 get(const char *tile, int r, int ks) {
-    constexpr int S = TileGeom<float, ROWS, KROW>::KROW_STRIDE;
+    constexpr int S = TileGeom<float, ROWS, KROW, KBYTES>::KROW_STRIDE;
     F32x8 f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) f.v[e] = *reinterpret_cast<const float *>(tile + (ks + e) * S + r * 4);
@@ -144,17 +159,26 @@ __device__ inline void mma16(f32x16_t &acc, const F32x8 &a, const F32x8 &b) {
   for (int e = 0; e < 8; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[e], b.v[e], acc, 0, 0, 0);
 }
 
-template <typename T, int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi>
-__global__ void __launch_bounds__(WGM *WGN * 64) gemm_kernel(const GemmShape g, const Epi epi) {
+// What an epilogue sees: the workgroup's LDS (reusable: the main loop ends with a barrier), the
+// origin of the workgroup tile in C, the origin of this wave's sub-tile inside it, and ids.
+struct EpiCtx {
+  char *smem;
+  int tile_row0, tile_col0;
+  int wrow, wcol;
+  int lane, tid, split;
+};
+
+template <typename T, int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi, int KBYTES, int MINWG>
+__global__ void __launch_bounds__(WGM *WGN * 64, MINWG) gemm_kernel(const GemmShape g, const Epi epi) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int NT = WGM * WGN * 64;
-  constexpr int BK = Elem<T>::BK;
   constexpr int ES = sizeof(T);
+  constexpr int BK = KBYTES / ES;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile must be made of 32x32 blocks");
-  using GA = TileGeom<T, BM, LA>;
-  using GB = TileGeom<T, BN, LB>;
+  using GA = TileGeom<T, BM, LA, KBYTES>;
+  using GB = TileGeom<T, BN, LB, KBYTES>;
   constexpr int STAGE = GA::BYTES + GB::BYTES;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -173,8 +197,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_kernel(const GemmShape g, 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  TileLoader<T, BM, LA, NT> la;
-  TileLoader<T, BN, LB, NT> lb;
+  TileLoader<T, BM, LA, NT, KBYTES> la;
+  TileLoader<T, BN, LB, NT, KBYTES> lb;
   const char *Ab = static_cast<const char *>(g.A);
   const char *Bb = static_cast<const char *>(g.B);
   const long lda_b = g.lda * ES, ldb_b = g.ldb * ES;
@@ -200,9 +224,9 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_kernel(const GemmShape g, 
     for (int ks = 0; ks < BK; ks += 16) {
       typename FragT<T>::type fa[TM], fb[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = FragReader<T, BM, LA>::get(sa, wm * WTM + i * 32 + lr, ks + lk);
+      for (int i = 0; i < TM; ++i) fa[i] = FragReader<T, BM, LA, KBYTES>::get(sa, wm * WTM + i * 32 + lr, ks + lk);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = FragReader<T, BN, LB>::get(sb, wn * WTN + j * 32 + lr, ks + lk);
+      for (int j = 0; j < TN; ++j) fb[j] = FragReader<T, BN, LB, KBYTES>::get(sb, wn * WTN + j * 32 + lr, ks + lk);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -215,14 +239,95 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_kernel(const GemmShape g, 
     }
     __syncthreads();
   }
-  epi.template run<TM, TN>(acc, tile_m * BM + wm * WTM, tile_n * BN + wn * WTN, lane, split);
+  EpiCtx ctx;
+  ctx.smem = smem;
+  ctx.tile_row0 = tile_m * BM;
+  ctx.tile_col0 = tile_n * BN;
+  ctx.wrow = wm * WTM;
+  ctx.wcol = wn * WTN;
+  ctx.lane = lane;
+  ctx.tid = tid;
+  ctx.split = split;
+  epi.template run<BM, BN, TM, TN, NT>(acc, ctx);
 }
 
 // Accumulator element r (0..15) of a 32x32 block lives at row 8*(r/4) + 4*(lane/32) + r%4,
 // column lane%32.
 #define RNNLM_ACC_ROW(r, lane) ((((r) >> 2) << 3) + (((lane) >> 5) << 2) + ((r)&3))
 
+// ---- Tile store helpers --------------------------------------------------------------------------
+
+// Pitch (bytes) of the bf16 staging tile: 144 dwords = 16 (mod 64), so the two rows and two
+// half-waves of one staged write land in distinct banks.
+template <int BN>
+struct StageGeom {
+  static constexpr int PITCH = BN * 2 + 64;
+};
+
+// Writes the workgroup's BM x BN tile of values (already final, in MFMA accumulator layout) to
+// out[row][col] (leading dimension ld, no bounds: the caller's buffer is tile-padded).
+// fp32: direct stores, 32 lanes cover 128 contiguous bytes of a row.
+template <int BM, int BN, int TM, int TN, int NT>
+__device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c, float *out, long ld) {
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const long col = c.tile_col0 + c.wcol + j * 32 + (c.lane & 31);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const long row = c.tile_row0 + c.wrow + i * 32 + RNNLM_ACC_ROW(r, c.lane);
+        out[row * ld + col] = val[i][j][r];
+      }
+    }
+}
+// bf16: a lane holds one column and runs of 4 consecutive rows.  Neighbouring lanes swap one packed
+// pair so that each lane owns two adjacent columns of one row (one dword), the tile is assembled in
+// LDS (which the main loop no longer needs) and leaves as 16-byte row-contiguous stores.
+template <int BM, int BN, int TM, int TN, int NT>
+__device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c, bf16_t *out, long ld) {
+  constexpr int PITCH = StageGeom<BN>::PITCH;
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  const bool odd = c.lane & 1;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = c.wcol + j * 32 + (c.lane & 31);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {  // rows 2q, 2q+1 of this lane's 16
+        const int r0 = 2 * q;
+        union {
+          bf16x2_t h;
+          unsigned u;
+        } pk;
+        pk.h[0] = (bf16_t)val[i][j][r0];
+        pk.h[1] = (bf16_t)val[i][j][r0 + 1];
+        const unsigned mine = pk.u;
+        const unsigned theirs = (unsigned)__builtin_amdgcn_mov_dpp((int)mine, 0xB1, 0xF, 0xF, true);  // lane ^ 1
+        const unsigned word = odd ? ((theirs >> 16) | (mine & 0xffff0000u)) : ((mine & 0xffffu) | (theirs << 16));
+        const int row = c.wrow + i * 32 + RNNLM_ACC_ROW(r0, c.lane) + (odd ? 1 : 0);
+        *reinterpret_cast<unsigned *>(c.smem + row * PITCH + (col & ~1) * 2) = word;
+      }
+    }
+  __syncthreads();
+  constexpr int CPR = BN * 2 / 16;  // 16-byte chunks per row
+#pragma unroll 4
+  for (int idx = c.tid; idx < BM * CPR; idx += NT) {
+    const int row = idx / CPR, ch = idx % CPR;
+    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(c.smem + row * PITCH + ch * 16);
+    *reinterpret_cast<u32x4_t *>(out + (long)(c.tile_row0 + row) * ld + c.tile_col0 + ch * 8) = v;
+  }
+}
+template <typename T, int BM, int BN>
+constexpr int stage_lds_bytes() {
+  return sizeof(T) == 2 ? BM * StageGeom<BN>::PITCH : 0;
+}
+
 // ---- Epilogues ---------------------------------------------------------------------------------
+// Each provides run<BM, BN, TM, TN, NT>(acc, ctx), executed by every thread of the workgroup after
+// the main loop's final barrier (so LDS may be reused and barriers are allowed), and
+// lds_bytes<BM, BN>() = LDS it needs.
 
 // Recurrent forward step (Sec. 4.1): h = sigmoid(X + Hprev U^T).  Rows = streams, cols = units.
 template <typename T>
@@ -231,8 +336,11 @@ struct EpiRnnFwd {
   T *Hnext;         // [Bp][ld]  hidden state slot of this timestep (padding written as zero)
   float *h_state;   // [B][H] or nullptr: carried state, written at the window's last step
   int B, H, ld;
-  template <int TM, int TN>
-  __device__ inline void run(f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, int) const {
+  template <int BM, int BN>
+  static constexpr int lds_bytes() { return 0; }
+  template <int BM, int BN, int TM, int TN, int NT>
+  __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
+    const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -252,9 +360,10 @@ struct EpiRnnFwd {
 };
 
 // Output layer forward: z[v][m] = Wo[v] . h[m] + b[v] (rows = vocabulary, cols = window positions),
-// stored transposed (vocabulary-major) for the softmax pass and both gradient contractions, plus
-// per-(wave row block, position) partial (max, sum exp) statistics of the fp32 logits and the fp32
-// logit of each position's target word.
+// stored vocabulary-major for the softmax pass and both gradient contractions, plus per-(wave row
+// block, position) partial (max, sum exp) statistics of the fp32 logits and the fp32 logit of each
+// position's target word.  A lane owns one position (column), so its statistics need no cross-lane
+// traffic except one exchange between the two half-waves.
 template <typename T>
 struct EpiOutFwd {
   const float *b;   // [V]
@@ -264,8 +373,21 @@ struct EpiOutFwd {
   float *zy;        // [Mp] target logit
   int V;
   long ldz;
-  template <int TM, int TN>
-  __device__ inline void run(f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, int) const {
+  template <int BM, int BN>
+  static constexpr int lds_bytes() { return stage_lds_bytes<T, BM, BN>(); }
+  template <int BM, int BN, int TM, int TN, int NT>
+  __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
+    const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
+    // bias: a lane needs b[v .. v+3] for 4*TM aligned groups of rows
+    float bias[TM][4][4];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int v = row0 + i * 32 + 8 * g + ((lane >> 5) << 2);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bias[i][g][e] = (v + e < V) ? b[v + e] : 0.0f;
+      }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int m = col0 + j * 32 + (lane & 31);
@@ -278,12 +400,11 @@ struct EpiOutFwd {
           const int v = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
           float z = 0.0f;
           if (v < V) {
-            z = acc[i][j][r] + b[v];
+            z = acc[i][j][r] + bias[i][r >> 2][r & 3];
             mx = fmaxf(mx, z);
             if (v == target) zy[m] = z;
           }
           acc[i][j][r] = z;
-          ZT[(long)v * ldz + m] = from_f32<T>(z);
         }
       float sum = 0.0f;
 #pragma unroll
@@ -302,6 +423,7 @@ struct EpiOutFwd {
       if (osum > 0.0f) tot += osum * __expf(omx - nmx);
       if (lane < 32) part[(long)(row0 / (32 * TM)) * ldz + m] = make_float2(nmx, tot);
     }
+    store_tile<BM, BN, TM, TN, NT>(acc, c, ZT, ldz);
   }
 };
 
@@ -310,52 +432,77 @@ struct EpiPartial {
   float *part;
   long ld;           // columns
   long split_stride; // elements between splits
-  template <int TM, int TN>
-  __device__ inline void run(f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, int split) const {
-    float *p = part + (long)split * split_stride;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = col0 + j * 32 + (lane & 31);
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
-          p[(long)row * ld + col] = acc[i][j][r];
-        }
-      }
+  template <int BM, int BN>
+  static constexpr int lds_bytes() { return 0; }
+  template <int BM, int BN, int TM, int TN, int NT>
+  __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
+    store_tile<BM, BN, TM, TN, NT>(acc, c, part + (long)c.split * split_stride, ld);
   }
 };
 
-// Fused SGD (Sec. 4.2) on a weight-gradient contraction: out = alpha*W - lr*acc for the R x C
-// valid entries; training passes out = W (in place, alpha = 1) and also refreshes the compute copy
-// Wc; the gradient-export call passes out = caller buffer, alpha = 0, lr = -1, Wc = nullptr.
+// Fused SGD (Sec. 4.2) on a weight-gradient contraction computed TRANSPOSED: the accumulator tile is
+// C[j][r] = dLoss/dW[r][j] (rows = columns j of the weight matrix, columns = its rows r), so a lane
+// holds runs of 4 consecutive j for one weight row and updates W[r][j..j+3] with one 16-byte
+// read-modify-write.  out = alpha*W - lr*acc for the R x C valid entries; training passes out = W (in
+// place, alpha = 1) and also refreshes the compute copy Wc; the gradient-export call passes out =
+// caller buffer, alpha = 0, lr = -1, Wc = nullptr.  Padding entries of Wc are never written (they
+// stay zero).
 template <typename T>
-struct EpiSgd {
+struct EpiSgdT {
   const float *W;
   float *out;
   T *Wc;
   long ldw, ldc;  // ldw: W/out leading dimension; ldc: compute copy leading dimension
-  int R, C;
+  int R, C;       // valid weight rows (tile columns) and weight columns (tile rows)
   float alpha, lr;
-  template <int TM, int TN>
-  __device__ inline void run(f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, int) const {
+  template <int BM, int BN>
+  static constexpr int lds_bytes() { return 0; }
+  __device__ static inline void store4(float *p, const f32x4_t &v) { *reinterpret_cast<f32x4_t *>(p) = v; }
+  __device__ static inline void store4(bf16_t *p, const f32x4_t &v) {
+    bf16x4_t h;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int e = 0; e < 4; ++e) h[e] = (bf16_t)v[e];
+    *reinterpret_cast<bf16x4_t *>(p) = h;
+  }
+  template <int BM, int BN, int TM, int TN, int NT>
+  __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
+    const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
+    const bool vec_ok = ((ldw | ldc) & 3) == 0;
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = col0 + j * 32 + (lane & 31);
+    for (int j = 0; j < TN; ++j) {
+      const int r = col0 + j * 32 + (lane & 31);  // weight row
+      if (r >= R) continue;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int row = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
-          if (row < R && col < C) {
-            const float w = (alpha != 0.0f) ? alpha * W[(long)row * ldw + col] : 0.0f;
-            const float nv = w - lr * acc[i][j][r];
-            out[(long)row * ldw + col] = nv;
-            if (Wc) Wc[(long)row * ldc + col] = from_f32<T>(nv);
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int j0 = row0 + i * 32 + 8 * g + ((lane >> 5) << 2);  // first of 4 weight columns
+          if (j0 >= C) continue;
+          const long idx = (long)r * ldw + j0;
+          if (vec_ok && j0 + 3 < C) {
+            f32x4_t nv;
+            if (alpha != 0.0f) {
+              const f32x4_t w = *reinterpret_cast<const f32x4_t *>(W + idx);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) nv[e] = alpha * w[e] - lr * acc[i][j][4 * g + e];
+            } else {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) nv[e] = -lr * acc[i][j][4 * g + e];
+            }
+            *reinterpret_cast<f32x4_t *>(out + idx) = nv;
+            if (Wc) store4(Wc + (long)r * ldc + j0, nv);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (j0 + e < C) {
+                const float w = (alpha != 0.0f) ? alpha * W[idx + e] : 0.0f;
+                const float nv = w - lr * acc[i][j][4 * g + e];
+                out[idx + e] = nv;
+                if (Wc) Wc[(long)r * ldc + j0 + e] = from_f32<T>(nv);
+              }
           }
         }
-      }
+    }
   }
 };
 
@@ -367,8 +514,11 @@ struct EpiRnnBwd {
   float *dA32;       // [Bp][ld]
   T *dAc;            // [Bp][ld]
   int B, H, ld;
-  template <int TM, int TN>
-  __device__ inline void run(f32x16_t (&acc)[TM][TN], int row0, int col0, int lane, int) const {
+  template <int BM, int BN>
+  static constexpr int lds_bytes() { return 0; }
+  template <int BM, int BN, int TM, int TN, int NT>
+  __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
+    const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -392,13 +542,16 @@ struct EpiRnnBwd {
 
 // ---- Host launcher -----------------------------------------------------------------------------
 
-template <typename T, int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi>
+template <typename T, int BM, int BN, int WGM, int WGN, int LA, int LB, int KBYTES = 128, int MINWG = 1, class Epi>
 inline hipError_t launch_gemm(hipStream_t stream, const void *A, long lda, const void *B, long ldb, long Mg, long Ng,
                               long K, int splits, const Epi &epi) {
-  constexpr int BK = Elem<T>::BK;
+  constexpr int BK = KBYTES / (int)sizeof(T);
   if (Mg <= 0 || Ng <= 0 || K < 0 || Mg % BM || Ng % BN || K % BK || splits < 1) return hipErrorInvalidValue;
-  constexpr int smem_bytes = 2 * (TileGeom<T, BM, LA>::BYTES + TileGeom<T, BN, LB>::BYTES);
-  auto kern = gemm_kernel<T, BM, BN, WGM, WGN, LA, LB, Epi>;
+  constexpr int loop_bytes = 2 * (TileGeom<T, BM, LA, KBYTES>::BYTES + TileGeom<T, BN, LB, KBYTES>::BYTES);
+  constexpr int epi_bytes = Epi::template lds_bytes<BM, BN>();
+  constexpr int smem_bytes = loop_bytes > epi_bytes ? loop_bytes : epi_bytes;
+  static_assert(smem_bytes <= 160 * 1024, "tile does not fit the 160 KB of LDS");
+  auto kern = gemm_kernel<T, BM, BN, WGM, WGN, LA, LB, Epi, KBYTES, MINWG>;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),

@@ -92,16 +92,34 @@ __global__ void to_compute_copy_kernel(const float *__restrict__ W, int R, int C
 
 // ---- a4 (part 1): merge the per-row-block (max, sum exp) partials of each position into the log
 // normaliser, and form log P(target) = z_target - lse (Sec. 4.2: explicitly normalised output).
-__global__ void merge_stats_kernel(const float2 *__restrict__ part, int nPart, long ldz, int T, int B, int Bp,
-                                   const float *__restrict__ zy, float *__restrict__ lse,
-                                   float *__restrict__ logp_int, float *__restrict__ logp_out) {
-  const int m = blockIdx.x * blockDim.x + threadIdx.x;
-  if (m >= T * Bp) return;
+// Block = 64 positions x 16 groups of partials; each group is merged sequentially in a fixed order, then
+// the 16 group results are merged in order by the group-0 thread.
+__global__ void __launch_bounds__(1024) merge_stats_kernel(const float2 *__restrict__ part, int nPart, long ldz, int T,
+                                                           int B, int Bp, const float *__restrict__ zy,
+                                                           float *__restrict__ lse, float *__restrict__ logp_int,
+                                                           float *__restrict__ logp_out) {
+  __shared__ float2 sh[16][64];
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int m = blockIdx.x * 64 + lane;
+  const bool valid = m < T * Bp;
+  float mx = -INFINITY, sum = 0.0f;
+  if (valid) {
+    for (int p = grp; p < nPart; p += 16) {
+      const float2 q = part[(long)p * ldz + m];
+      if (q.y > 0.0f) {
+        const float nmx = fmaxf(mx, q.x);
+        sum = sum * __expf(mx - nmx) + q.y * __expf(q.x - nmx);
+        mx = nmx;
+      }
+    }
+  }
+  sh[grp][lane] = make_float2(mx, sum);
+  __syncthreads();
+  if (grp != 0 || !valid) return;
   const int t = m / Bp, s = m % Bp;
   if (s >= B) return;  // padding keeps lse = +inf
-  float mx = -INFINITY, sum = 0.0f;
-  for (int p = 0; p < nPart; ++p) {
-    const float2 q = part[(long)p * ldz + m];
+  for (int g = 1; g < 16; ++g) {
+    const float2 q = sh[g][lane];
     if (q.y > 0.0f) {
       const float nmx = fmaxf(mx, q.x);
       sum = sum * __expf(mx - nmx) + q.y * __expf(q.x - nmx);
@@ -193,27 +211,35 @@ __global__ void splitk_reduce_kernel(const float *__restrict__ part, long n, lon
 
 // ---- a10 helpers (integer-exact): stable order of window positions by input id ------------------
 // rank[m] = #{m' : (x[m'], m') < (x[m], m)};  perm[rank[m]] = m.
-__global__ void rank_sort_kernel(const int32_t *__restrict__ xp, int M, int B, int Bp, int32_t *__restrict__ perm) {
-  __shared__ int32_t keys[2048];
-  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+// Block = 64 positions x 16 slices of the key array (1024 threads).
+__global__ void __launch_bounds__(1024) rank_sort_kernel(const int32_t *__restrict__ xp, int M, int B, int Bp,
+                                                         int32_t *__restrict__ perm) {
+  __shared__ int32_t keys[4096];
+  __shared__ int32_t cnt[16][64];
+  const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int m = blockIdx.x * 64 + lane;
   const int mykey = (m < M) ? xp[(m / B) * Bp + (m % B)] : 0;
   int rank = 0;
-  for (int base = 0; base < M; base += 2048) {
-    const int n = min(2048, M - base);
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+  for (int base = 0; base < M; base += 4096) {
+    const int n = min(4096, M - base);
+    for (int i = threadIdx.x; i < n; i += 1024) {
       const int mm = base + i;
       keys[i] = xp[(mm / B) * Bp + (mm % B)];
     }
     __syncthreads();
-    if (m < M) {
-      for (int i = 0; i < n; ++i) {
-        const int k = keys[i];
-        rank += (k < mykey) || (k == mykey && base + i < m);
-      }
+    for (int i = slice; i < n; i += 16) {
+      const int k = keys[i];
+      rank += (k < mykey) || (k == mykey && base + i < m);
     }
     __syncthreads();
   }
-  if (m < M) perm[rank] = m;
+  cnt[slice][lane] = rank;
+  __syncthreads();
+  if (slice == 0 && m < M) {
+    int r = 0;
+    for (int g = 0; g < 16; ++g) r += cnt[g][lane];
+    perm[r] = m;
+  }
 }
 
 // Run starts of equal ids in sorted order; single workgroup of 1024 threads, fixed scan order.
@@ -259,27 +285,36 @@ __global__ void segment_kernel(const int32_t *__restrict__ xp, const int32_t *__
 }
 
 // ---- a10: segmented embedding update, atomic-free and order-fixed -------------------------------
-//   out[w][:] = alpha*E[w][:] - lr * sum_{m in run of w, ascending m} dA[m][:]
-// blockIdx.x = run index (exits when >= *nseg), blockIdx.y = block of 256 columns.
-__global__ void __launch_bounds__(256) scatter_update_kernel(const float *__restrict__ dA, int Hp, int H, int B,
+//   out[w][:] = alpha*E[w][:] - lr * sum_{m in run of w} dA[m][:]
+// blockIdx.x = run index (exits when >= *nseg), blockIdx.y = block of 64 columns.  The run's members
+// are dealt round-robin to 8 partial sums (each accumulated in ascending m), which are then added in
+// order 0..7: a fixed summation tree, so results are bitwise reproducible.
+__global__ void __launch_bounds__(512) scatter_update_kernel(const float *__restrict__ dA, int Hp, int H, int B,
                                                              int Bp, const int32_t *__restrict__ xp,
                                                              const int32_t *__restrict__ perm,
                                                              const int32_t *__restrict__ seg_start,
                                                              const int32_t *__restrict__ nseg,
                                                              const float *__restrict__ E, float *__restrict__ out,
                                                              float alpha, float lr) {
+  __shared__ float sh[8][64];
   const int g = blockIdx.x;
   if (g >= *nseg) return;
-  const int col = blockIdx.y * 256 + threadIdx.x;
-  if (col >= H) return;
+  const int lane = threadIdx.x & 63, partn = threadIdx.x >> 6;
+  const int col = blockIdx.y * 64 + lane;
   const int r0 = seg_start[g], r1 = seg_start[g + 1];
+  float acc = 0.0f;
+  if (col < H) {
+    for (int r = r0 + partn; r < r1; r += 8) {
+      const int m = perm[r];
+      acc += dA[((long)(m / B) * Bp + (m % B)) * Hp + col];
+    }
+  }
+  sh[partn][lane] = acc;
+  __syncthreads();
+  if (partn != 0 || col >= H) return;
+  for (int q = 1; q < 8; ++q) acc += sh[q][lane];
   const int m0 = perm[r0];
   const int w = xp[(m0 / B) * Bp + (m0 % B)];
-  float acc = 0.0f;
-  for (int r = r0; r < r1; ++r) {
-    const int m = perm[r];
-    acc += dA[((long)(m / B) * Bp + (m % B)) * Hp + col];
-  }
   const long idx = (long)w * H + col;
   out[idx] = ((alpha != 0.0f) ? alpha * E[idx] : 0.0f) - lr * acc;
 }

@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <new>
+#include <vector>
 
 #include "common.h"
 #include "gemm.h"
@@ -25,6 +26,11 @@ struct WsLayout {
   long partElems;
 };
 
+struct EventPair {
+  hipEvent_t start, stop;
+  int stage;
+};
+
 struct rnnlm {
   rnnlm_config cfg;
   rnnlm_buffers buf;
@@ -32,11 +38,62 @@ struct rnnlm {
   int nPart;
   WsLayout L;
   char *ws;
+  // stage timing (host-side only)
+  uint32_t prof_mask = 0;
+  std::vector<EventPair> prof_pool;
+  size_t prof_used = 0;
+  long prof_open[RNNLM_STAGE_COUNT] = {0};
+  double prof_ms[RNNLM_STAGE_COUNT] = {0};
+  int64_t prof_n[RNNLM_STAGE_COUNT] = {0};
 };
 
 namespace {
+constexpr size_t PROF_MAX_PAIRS = 16384;
 
-constexpr int OUT_WTM = 64;  // rows of the output-forward wave tile (one statistics partial each)
+// Records a start event now and a stop event when it goes out of scope, if the stage is enabled.
+struct StageTimer {
+  rnnlm *h;
+  hipStream_t st;
+  EventPair *p = nullptr;
+  bool close_;
+  // open/close: a stage made of several launches opens its pair at the first launch and closes it at
+  // the last (stage < 0: nothing to do for the launches in between).
+  StageTimer(rnnlm *h_, int stage, hipStream_t st_, bool open = true, bool close = true)
+      : h(h_), st(st_), close_(close) {
+    if (stage < 0 || !(h->prof_mask & (1u << stage))) return;
+    if (!open) {
+      if (h->prof_open[stage] >= 0) p = &h->prof_pool[h->prof_open[stage]];
+      return;
+    }
+    h->prof_open[stage] = -1;
+    if (h->prof_used == h->prof_pool.size()) {
+      if (h->prof_pool.size() >= PROF_MAX_PAIRS) return;
+      EventPair e;
+      if (hipEventCreate(&e.start) != hipSuccess) return;
+      if (hipEventCreate(&e.stop) != hipSuccess) {
+        (void)hipEventDestroy(e.start);
+        return;
+      }
+      h->prof_pool.push_back(e);
+    }
+    h->prof_open[stage] = (long)h->prof_used;
+    p = &h->prof_pool[h->prof_used++];
+    p->stage = stage;
+    (void)hipEventRecord(p->start, st);
+  }
+  ~StageTimer() {
+    if (p && close_) (void)hipEventRecord(p->stop, st);
+  }
+};
+}  // namespace
+
+namespace {
+
+// Tile shape of the three output-layer contractions and of the recurrent weight gradient: 256x256
+// output tile, 8 waves as 2 x 4 (wave tile 128 x 64).
+#define BIG_TILE 256, 256, 2, 4
+constexpr int BIG = 256;
+constexpr int OUT_WTM = 128;  // rows of the output-forward wave tile (one statistics partial each)
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -50,8 +107,8 @@ bool cfg_ok(const rnnlm_config *c) {
 }
 
 int desired_splits(long Mp, long Hp, long kBlocks) {
-  const long tiles = (Mp / 128) * (Hp / 128);
-  long s = (768 + tiles - 1) / tiles;
+  const long tiles = (Mp / BIG) * (Hp / BIG);
+  long s = 256 / tiles;  // one workgroup per compute unit: stay within one round
   if (s > 16) s = 16;
   if (s > kBlocks) s = kBlocks;
   if (s < 1) s = 1;
@@ -144,14 +201,18 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
   int32_t *xp = at<int32_t>(h, h->L.xp), *yp = at<int32_t>(h, h->L.yp);
   float *lse = at<float>(h, h->L.lse), *zy = at<float>(h, h->L.zy);
 
-  hipLaunchKernelGGL(prep_tokens_kernel, dim3(blocks_for(Mp, 256)), dim3(256), 0, st, x, y, Tn, c.B, Bp, Mp, c.V, xp,
-                     yp, lse, p_flags(h));
-  hipLaunchKernelGGL(state_to_slot_kernel<T>, dim3(blocks_for((long)Bp * Hp, 256)), dim3(256), 0, st, h->buf.h_state,
-                     c.B, c.H, Bp, Hp, Hs_c);
-  hipLaunchKernelGGL(gather_kernel, dim3(Mrows), dim3(256), 0, st, h->buf.E, xp, c.H, Hp, X32);
-  HIP_TRY(hipGetLastError());
+  {
+    StageTimer tm(h, RNNLM_STAGE_PREP, st);
+    hipLaunchKernelGGL(prep_tokens_kernel, dim3(blocks_for(Mp, 256)), dim3(256), 0, st, x, y, Tn, c.B, Bp, Mp, c.V, xp,
+                       yp, lse, p_flags(h));
+    hipLaunchKernelGGL(state_to_slot_kernel<T>, dim3(blocks_for((long)Bp * Hp, 256)), dim3(256), 0, st,
+                       h->buf.h_state, c.B, c.H, Bp, Hp, Hs_c);
+    hipLaunchKernelGGL(gather_kernel, dim3(Mrows), dim3(256), 0, st, h->buf.E, xp, c.H, Hp, X32);
+    HIP_TRY(hipGetLastError());
+  }
 
   for (int t = 0; t < Tn; ++t) {
+    StageTimer tm(h, (t == 0 || t == Tn - 1) ? RNNLM_STAGE_RNN_FWD : -1, st, t == 0, t == Tn - 1);
     EpiRnnFwd<T> epi;
     epi.X = X32 + (long)t * Bp * Hp;
     epi.Hnext = Hs_c + (long)(t + 1) * Bp * Hp;
@@ -163,6 +224,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
                                                       Hp, 1, epi)));
   }
   {
+    StageTimer tm(h, RNNLM_STAGE_OUT_FWD, st);
     EpiOutFwd<T> epi;
     epi.b = h->buf.b;
     epi.ZT = at<T>(h, h->L.ZT);
@@ -171,10 +233,11 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     epi.zy = zy;
     epi.V = c.V;
     epi.ldz = ldz;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, ROWK>(st, at<T>(h, h->L.Wo_c), Hp, Hs_c + (long)Bp * Hp, Hp, Vp, Mp,
+    HIP_TRY((launch_gemm<T, BIG_TILE, ROWK, ROWK>(st, at<T>(h, h->L.Wo_c), Hp, Hs_c + (long)Bp * Hp, Hp, Vp, Mp,
                                                         Hp, 1, epi)));
   }
-  hipLaunchKernelGGL(merge_stats_kernel, dim3(blocks_for(Mrows, 256)), dim3(256), 0, st, at<float2>(h, h->L.stat),
+  StageTimer tm(h, RNNLM_STAGE_STATS, st);
+  hipLaunchKernelGGL(merge_stats_kernel, dim3(blocks_for(Mrows, 64)), dim3(1024), 0, st, at<float2>(h, h->L.stat),
                      h->nPart, ldz, Tn, c.B, Bp, zy, lse, at<float>(h, h->L.logp_int), logp_out);
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
@@ -183,7 +246,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
 template <typename T>
 int sort_segments(rnnlm_t *h, int Tn, int32_t *perm, int32_t *seg, int32_t *nseg, hipStream_t st) {
   const int M = Tn * h->cfg.B;
-  hipLaunchKernelGGL(rank_sort_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, st, at<int32_t>(h, h->L.xp), M,
+  hipLaunchKernelGGL(rank_sort_kernel, dim3(blocks_for(M, 64)), dim3(1024), 0, st, at<int32_t>(h, h->L.xp), M,
                      h->cfg.B, h->Bp, perm);
   hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(1024), 0, st, at<int32_t>(h, h->L.xp), perm, M, h->cfg.B, h->Bp,
                      seg, nseg);
@@ -211,13 +274,19 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
   int32_t *perm = at<int32_t>(h, h->L.perm), *seg = at<int32_t>(h, h->L.seg);
 
   // integer helpers of the embedding update (independent of everything above)
-  int rc = sort_segments<T>(h, Tn, perm, seg, p_nseg(h), st);
-  if (rc) return rc;
+  {
+    StageTimer tm(h, RNNLM_STAGE_EMB, st);
+    int rc = sort_segments<T>(h, Tn, perm, seg, p_nseg(h), st);
+    if (rc) return rc;
+  }
 
   // fused softmax gradient + bias update, in place on the vocabulary-major logits
-  hipLaunchKernelGGL(softmax_grad_kernel<T>, dim3(Vp / 4), dim3(256), 0, st, ZT, ldz, Mp, c.V, Vp,
-                     at<float>(h, h->L.lse), yp, 1.0f / (float)(Tn * c.B), h->buf.b, u.b, u.alpha, u.lr);
-  HIP_TRY(hipGetLastError());
+  {
+    StageTimer tm(h, RNNLM_STAGE_SOFTMAX_GRAD, st);
+    hipLaunchKernelGGL(softmax_grad_kernel<T>, dim3(Vp / 4), dim3(256), 0, st, ZT, ldz, Mp, c.V, Vp,
+                       at<float>(h, h->L.lse), yp, 1.0f / (float)(Tn * c.B), h->buf.b, u.b, u.alpha, u.lr);
+    HIP_TRY(hipGetLastError());
+  }
 
   // dHs[m][j] = sum_v dz[v][m] Wo[v][j]   (contraction over the vocabulary, split-K)
   {
@@ -229,8 +298,12 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
     epi.part = (S == 1) ? dHs32 : at<float>(h, h->L.part32);
     epi.ld = Hp;
     epi.split_stride = per;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, ZT, ldz, Wo_c, Hp, Mp, Hp, Vp, S, epi)));
+    {
+      StageTimer tm(h, RNNLM_STAGE_OUT_BWD_H, st);
+      HIP_TRY((launch_gemm<T, BIG_TILE, KROW, KROW>(st, ZT, ldz, Wo_c, Hp, Mp, Hp, Vp, S, epi)));
+    }
     if (S > 1) {
+      StageTimer tm(h, RNNLM_STAGE_REDUCE, st);
       hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks_for(per / 4, 256)), dim3(256), 0, st,
                          at<float>(h, h->L.part32), per, per, S, dHs32);
       HIP_TRY(hipGetLastError());
@@ -246,6 +319,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
 
   // back-propagation through time over the window (stops at the window start)
   for (int t = Tn - 1; t >= 0; --t) {
+    StageTimer tm(h, (t == 0 || t == Tn - 1) ? RNNLM_STAGE_RNN_BWD : -1, st, t == Tn - 1, t == 0);
     EpiRnnBwd<T> epi;
     epi.dHs = dHs32 + (long)t * Bp * Hp;
     epi.Hs = Hs_c + (long)(t + 1) * Bp * Hp;
@@ -259,9 +333,10 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
                                                       epi)));
   }
 
-  // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j]
+  // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j], contracted transposed (tile rows = j, tile columns = v)
   {
-    EpiSgd<T> epi;
+    StageTimer tm(h, RNNLM_STAGE_OUT_BWD_W, st);
+    EpiSgdT<T> epi;
     epi.W = h->buf.Wo;
     epi.out = u.Wo;
     epi.Wc = u.refresh_copies ? Wo_c : nullptr;
@@ -271,11 +346,12 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
     epi.C = c.H;
     epi.alpha = u.alpha;
     epi.lr = u.lr;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, KROW>(st, ZT, ldz, Hs_c + (long)Bp * Hp, Hp, Vp, Hp, Mp, 1, epi)));
+    HIP_TRY((launch_gemm<T, BIG_TILE, KROW, ROWK>(st, Hs_c + (long)Bp * Hp, Hp, ZT, ldz, Hp, Vp, Mp, 1, epi)));
   }
-  // U[i][j] -= lr * sum_m dA[m][i] Hprev[m][j]
+  // U[i][j] -= lr * sum_m dA[m][i] Hprev[m][j], contracted transposed (tile rows = j, tile columns = i)
   {
-    EpiSgd<T> epi;
+    StageTimer tm(h, RNNLM_STAGE_REC_W, st);
+    EpiSgdT<T> epi;
     epi.W = h->buf.U;
     epi.out = u.U;
     epi.Wc = u.refresh_copies ? U_c : nullptr;
@@ -285,10 +361,11 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
     epi.C = c.H;
     epi.alpha = u.alpha;
     epi.lr = u.lr;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, dA_c, Hp, Hs_c, Hp, Hp, Hp, Mp, 1, epi)));
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
   }
   // E[w] -= lr * sum_{m: x[m] = w} dA[m]
-  hipLaunchKernelGGL(scatter_update_kernel, dim3(Tn * c.B, (c.H + 255) / 256), dim3(256), 0, st, dA32, Hp, c.H, c.B, Bp,
+  StageTimer tm(h, RNNLM_STAGE_EMB, st);
+  hipLaunchKernelGGL(scatter_update_kernel, dim3(Tn * c.B, (c.H + 63) / 64), dim3(512), 0, st, dA32, Hp, c.H, c.B, Bp,
                      xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr);
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
@@ -364,7 +441,14 @@ int rnnlm_init(const rnnlm_config *cfg, const rnnlm_buffers *buf, rnnlm_t **out)
   return RNNLM_OK;
 }
 
-void rnnlm_free(rnnlm_t *h) { delete h; }
+void rnnlm_free(rnnlm_t *h) {
+  if (!h) return;
+  for (EventPair &e : h->prof_pool) {
+    (void)hipEventDestroy(e.start);
+    (void)hipEventDestroy(e.stop);
+  }
+  delete h;
+}
 
 int rnnlm_stream_chunk(rnnlm_t *h, const int32_t *tok, int64_t N, int64_t k, int32_t T, int32_t *x, int32_t *y,
                        void *stream) {
@@ -476,6 +560,30 @@ int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, 
                      p_flags(h));
   HIP_TRY(hipGetLastError());
   return sort_segments<float>(h, T, perm, seg_start, nseg, st);
+}
+
+int rnnlm_profile_enable(rnnlm_t *h, uint32_t stage_mask) {
+  if (!h || stage_mask >= (1u << RNNLM_STAGE_COUNT)) return RNNLM_ERR_ARG;
+  h->prof_mask = stage_mask;
+  return RNNLM_OK;
+}
+
+int rnnlm_profile_read(rnnlm_t *h, int32_t stage, double *total_ms, int64_t *executions) {
+  if (!h || stage < 0 || stage >= RNNLM_STAGE_COUNT || !total_ms || !executions) return RNNLM_ERR_ARG;
+  for (size_t i = 0; i < h->prof_used; ++i) {
+    EventPair &e = h->prof_pool[i];
+    HIP_TRY(hipEventSynchronize(e.stop));
+    float ms = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&ms, e.start, e.stop));
+    h->prof_ms[e.stage] += ms;
+    h->prof_n[e.stage] += 1;
+  }
+  h->prof_used = 0;
+  *total_ms = h->prof_ms[stage];
+  *executions = h->prof_n[stage];
+  h->prof_ms[stage] = 0.0;
+  h->prof_n[stage] = 0;
+  return RNNLM_OK;
 }
 
 const char *rnnlm_status_string(int status) {
