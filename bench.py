@@ -162,15 +162,19 @@ def cpu_baseline(cfg, E, U, Wo, b, tok):
     import numpy as np
     from oracle import oracle as O
     V, H, B, T = cfg.V, cfg.H, cfg.B, cfg.T
-    flops_word = 6.0 * H * (V + H)
-    est_rate = 4e9 * O.num_threads() / 8  # rough fp64 rate of the plain loops
-    Ts = int(max(1, min(T, (15.0 * est_rate) // (flops_word * B))))
-    m = O.Model.from_weights(E, U, Wo, b, B)
     x, y = O.stream_chunk(tok, B, T, 0)
-    x, y = np.ascontiguousarray(x[:Ts]), np.ascontiguousarray(y[:Ts])
-    t0 = time.perf_counter()
-    O.train_chunk(m, x, y, cfg.lr)
-    dt = time.perf_counter() - t0
+
+    def timed(Ts):
+        m = O.Model.from_weights(E, U, Wo, b, B)
+        xs, ys = np.ascontiguousarray(x[:Ts]), np.ascontiguousarray(y[:Ts])
+        t0 = time.perf_counter()
+        O.train_chunk(m, xs, ys, cfg.lr)
+        return time.perf_counter() - t0
+
+    Ts, dt = 1, timed(1)          # calibration: one timestep of the window
+    if dt < 5.0 and T > 1:        # then as many timesteps as fit about 15 s
+        Ts = int(max(2, min(T, 15.0 // dt)))
+        dt = timed(Ts)
     return {"value": round(B * Ts / dt, 2), "unit": "words/s", "cores": O.num_threads(), "kind": "oracle",
             "sample": f"one training window of {B} streams x {Ts} of {T} timesteps ({B * Ts} words, {dt:.1f} s)"}
 

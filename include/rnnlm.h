@@ -56,7 +56,8 @@ typedef enum {
   RNNLM_ERR_TOKEN_RANGE = -2, /* some token id was outside [0, V) (ids were clamped, results are meaningless) */
   RNNLM_ERR_NONFINITE = -3,   /* a window's sum of log-probabilities was not finite */
   RNNLM_ERR_HIP = -4,         /* a HIP runtime call failed */
-  RNNLM_ERR_NOMEM = -5        /* host allocation failed */
+  RNNLM_ERR_NOMEM = -5,       /* host allocation failed */
+  RNNLM_ERR_TIMEOUT = -6      /* a bounded wait inside a persistent kernel expired (results are meaningless) */
 } rnnlm_status;
 
 typedef struct {
@@ -129,7 +130,8 @@ int rnnlm_reset_state(rnnlm_t *h, void *stream);
 int rnnlm_sync_compute_copies(rnnlm_t *h, void *stream);
 
 /* Waits for the stream and returns RNNLM_ERR_TOKEN_RANGE if any call since the last check saw an
- * out-of-range token id (the flag is cleared), RNNLM_ERR_HIP on a device error, else RNNLM_OK. */
+ * out-of-range token id, RNNLM_ERR_NONFINITE / RNNLM_ERR_TIMEOUT likewise (the flags are cleared),
+ * RNNLM_ERR_HIP on a device error, else RNNLM_OK. */
 int rnnlm_check(rnnlm_t *h, void *stream);
 
 /* Integer intermediates of the embedding-gradient step for the window x: dev int32[T][B]:
@@ -138,6 +140,11 @@ int rnnlm_check(rnnlm_t *h, void *stream);
  * number of runs.  Integer-exact. */
 int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, int32_t *seg_start, int32_t *nseg,
                         void *stream);
+
+/* Number of polls a grid-wide barrier of the persistent recurrent kernels waits before it gives up,
+ * raises the flag that rnnlm_check reports as RNNLM_ERR_TIMEOUT and lets the kernel run to its end
+ * (default 2^18, about a second).  For tests of that error path: polls = 1 makes waits expire at once. */
+int rnnlm_set_barrier_spin_limit(rnnlm_t *h, uint32_t polls);
 
 /* Stage timing with HIP events on the call's stream (for benchmarks; off by default).  Stages of a
  * window, in the order of the kernel sequence: */

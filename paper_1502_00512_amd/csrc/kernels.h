@@ -90,6 +90,17 @@ __global__ void to_compute_copy_kernel(const float *__restrict__ W, int R, int C
   }
 }
 
+// Square transpose of a compute-type matrix (n x n, n a multiple of 32): dst[c][r] = src[r][c].
+template <typename T>
+__global__ void __launch_bounds__(256) transpose_kernel(const T *__restrict__ src, int n, T *__restrict__ dst) {
+  __shared__ T tile[32][33];
+  const int bx = blockIdx.x * 32, by = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  for (int r = ty; r < 32; r += 8) tile[r][tx] = src[(long)(by + r) * n + bx + tx];
+  __syncthreads();
+  for (int r = ty; r < 32; r += 8) dst[(long)(bx + r) * n + by + tx] = tile[tx][r];
+}
+
 // ---- a4 (part 1): merge the per-row-block (max, sum exp) partials of each position into the log
 // normaliser, and form log P(target) = z_target - lse (Sec. 4.2: explicitly normalised output).
 // Block = 64 positions x 16 groups of partials; each group is merged sequentially in a fixed order, then

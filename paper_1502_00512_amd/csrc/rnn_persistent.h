@@ -1,0 +1,230 @@
+// Persistent recurrent kernels: all T dependent timesteps of a window in ONE launch, with the
+// state-to-state matrix held in registers for the whole window (Sec. 4.2 marshals the state-to-state
+// work into one large matrix product; on this hardware the serial chain is latency-bound instead, so
+// the matrix stays on chip and only the B x H state travels between steps).
+//
+// Decomposition: workgroup (sb, ub) owns streams [32 sb, +32) x hidden units [32 ub, +32).  Its four
+// waves split the contraction dimension in quarters; each keeps its 32 x (Hp/4) slice of U (forward:
+// rows of U; backward: rows of U^T) as MFMA operand fragments in registers, loads the matching part
+// of the previous step's state straight from L2 into operand fragments, and the four partial 32x32
+// tiles are summed through LDS.  Steps are separated by a grid-wide barrier (one atomic counter,
+// agent-scope release/acquire); the host guarantees the grid is small enough to be co-resident, and
+// the spin is bounded: on expiry a flag is raised and every workgroup still runs to completion.
+#pragma once
+#include "common.h"
+#include "gemm.h"
+
+namespace rnnlm_dev {
+
+struct RnnPersistArgs {
+  const void *W;      // forward: U_c [Hp][Hp]; backward: UT_c [Hp][Hp] (row n holds the k-contiguous operand)
+  void *Hs;           // hidden-state slots [(T+1)][Bp][Hp] (slot 0 = carried state)
+  const float *X;     // forward: gathered embeddings [T][Bp][Hp]; backward: dHs [T][Bp][Hp]
+  float *dA32;        // backward: [T][Bp][Hp]
+  void *dAc;          // backward: [T][Bp][Hp] compute type
+  float *h_state;     // forward: [B][H] or nullptr
+  unsigned *counter;  // grid barrier counter (zero at launch)
+  int32_t *flags;     // flags[2] raised when a barrier wait expires
+  int T, B, H, Bp, Hp;
+  unsigned spin_limit;
+};
+
+// Coherence between workgroups on different XCDs (each XCD has its own L2): everything one step writes
+// and the next step reads (the state h, the gradient dA) moves with agent-scope relaxed atomic
+// accesses of 64 bits, which carry the agent-scope cache policy on the access itself.  That avoids
+// bulk L2 write-back / invalidate operations at every barrier; ordering comes from waiting for the
+// stores (workgroup-scope fence) before the barrier's arrival atomic, and from the poll loop's
+// control dependency before the loads.
+__device__ inline void grid_barrier(unsigned *counter, unsigned target, unsigned spin_limit, int32_t *flags) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have completed
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned spins = 0;
+    while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      __builtin_amdgcn_s_sleep(1);
+      if (++spins >= spin_limit) {
+        flags[2] = 1;
+        break;
+      }
+    }
+  }
+  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+__device__ inline unsigned long long coherent_load64(const void *p) {
+  return __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void coherent_store64(void *p, unsigned long long v) {
+  __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// MFMA operand fragment (8 consecutive-k elements) straight from global memory.
+template <typename T, bool COHERENT>
+__device__ inline typename FragT<T>::type load_frag_global(const T *p);
+template <>
+__device__ inline bf16x8_t load_frag_global<bf16_t, false>(const bf16_t *p) {
+  return *reinterpret_cast<const bf16x8_t *>(p);
+}
+template <>
+__device__ inline bf16x8_t load_frag_global<bf16_t, true>(const bf16_t *p) {
+  union {
+    unsigned long long q[2];
+    bf16x8_t f;
+  } u;
+  u.q[0] = coherent_load64(p);
+  u.q[1] = coherent_load64(p + 4);
+  return u.f;
+}
+template <>
+__device__ inline F32x8 load_frag_global<float, false>(const float *p) {
+  F32x8 f;
+  const f32x4_t a = *reinterpret_cast<const f32x4_t *>(p);
+  const f32x4_t b = *reinterpret_cast<const f32x4_t *>(p + 4);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    f.v[e] = a[e];
+    f.v[4 + e] = b[e];
+  }
+  return f;
+}
+template <>
+__device__ inline F32x8 load_frag_global<float, true>(const float *p) {
+  union {
+    unsigned long long q[4];
+    F32x8 f;
+  } u;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) u.q[e] = coherent_load64(p + 2 * e);
+  return u.f;
+}
+
+// 4 consecutive values (fp32 in registers) to / from the compute type; COHERENT = agent-scope accesses.
+template <typename T>
+__device__ inline void store4(T *p, const f32x4_t &v);
+template <>
+__device__ inline void store4<float>(float *p, const f32x4_t &v) {
+  union {
+    unsigned long long q[2];
+    f32x4_t f;
+  } u;
+  u.f = v;
+  coherent_store64(p, u.q[0]);
+  coherent_store64(p + 2, u.q[1]);
+}
+template <>
+__device__ inline void store4<bf16_t>(bf16_t *p, const f32x4_t &v) {
+  union {
+    unsigned long long q;
+    bf16x4_t h;
+  } u;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) u.h[e] = (bf16_t)v[e];
+  coherent_store64(p, u.q);
+}
+template <typename T>
+__device__ inline f32x4_t load4(const T *p);
+template <>
+__device__ inline f32x4_t load4<float>(const float *p) {
+  return *reinterpret_cast<const f32x4_t *>(p);
+}
+template <>
+__device__ inline f32x4_t load4<bf16_t>(const bf16_t *p) {
+  const bf16x4_t h = *reinterpret_cast<const bf16x4_t *>(p);
+  f32x4_t v;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) v[e] = (float)h[e];
+  return v;
+}
+
+// KS = 16-wide contraction steps per wave = Hp / 64.  BACKWARD = false: h_t = sigmoid(X_t + h_{t-1} U^T)
+// for t = 0..T-1.  BACKWARD = true: dA_t = (dHs_t + dA_{t+1} U) * h_t * (1 - h_t) for t = T-1..0.
+template <typename T, int KS, bool BACKWARD>
+__global__ void __launch_bounds__(256) rnn_persistent_kernel(const RnnPersistArgs a) {
+  __shared__ __attribute__((aligned(16))) float red[4][16][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nsb = a.Bp / 32;
+  const int sb = blockIdx.x % nsb, ub = blockIdx.x / nsb;
+  const int Hp = a.Hp, Bp = a.Bp;
+  const long slot = (long)Bp * Hp;
+  const int kq = wave * (KS * 16);  // first contraction index of this wave
+  const int lr = lane & 31, lk = (lane >> 5) * 8;
+
+  // this wave's slice of the matrix, resident in registers for all T steps
+  typename FragT<T>::type w[KS];
+  {
+    const T *Wp = static_cast<const T *>(a.W) + (long)(ub * 32 + lr) * Hp + kq + lk;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) w[kk] = load_frag_global<T, false>(Wp + kk * 16);
+  }
+  // epilogue ownership: thread -> accumulator element r = tid/16 of lanes 4*(tid%16) .. +3, i.e. one
+  // stream and 4 consecutive hidden units
+  const int er = tid >> 4, el = (tid & 15) * 4;
+  const int erow = sb * 32 + ((er >> 2) << 3) + ((el >> 5) << 2) + (er & 3);
+  const int ecol = ub * 32 + (el & 31);
+  const bool row_ok = erow < a.B;
+  T *Hs = static_cast<T *>(a.Hs);
+  T *dAc = static_cast<T *>(a.dAc);
+  const unsigned nwg = gridDim.x;
+
+  for (int step = 0; step < a.T; ++step) {
+    const int t = BACKWARD ? a.T - 1 - step : step;
+    const long eidx = (long)t * slot + (long)erow * Hp + ecol;
+    // operands of the epilogue do not depend on the previous step: fetch them early
+    f32x4_t xin = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t hcur = {0.f, 0.f, 0.f, 0.f};
+    if (row_ok) {
+      xin = *reinterpret_cast<const f32x4_t *>(a.X + eidx);
+      if (BACKWARD) hcur = load4<T>(Hs + slot + eidx);
+    }
+    f32x16_t acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    const bool contract = !(BACKWARD && step == 0);  // nothing flows into the window's last position
+    if (contract) {
+      const T *src = BACKWARD ? dAc + (long)(t + 1) * slot : Hs + (long)t * slot;
+      const T *Ap = src + (long)(sb * 32 + lr) * Hp + kq + lk;
+      typename FragT<T>::type f[KS];
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) f[kk] = load_frag_global<T, true>(Ap + kk * 16);
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) mma16(acc, f[kk], w[kk]);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r];
+    __syncthreads();
+    f32x4_t s = *reinterpret_cast<const f32x4_t *>(&red[0][er][el]);
+#pragma unroll
+    for (int q = 1; q < 4; ++q) {
+      const f32x4_t p = *reinterpret_cast<const f32x4_t *>(&red[q][er][el]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[e] += p[e];
+    }
+    f32x4_t o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool ok = row_ok && (ecol + e) < a.H;
+      if (!BACKWARD) {
+        o[e] = ok ? sigmoidf_(s[e] + xin[e]) : 0.0f;
+      } else {
+        o[e] = ok ? (xin[e] + s[e]) * hcur[e] * (1.0f - hcur[e]) : 0.0f;
+      }
+    }
+    if (!BACKWARD) {
+      store4<T>(Hs + slot + eidx, o);
+      if (a.h_state && step == a.T - 1 && row_ok) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (ecol + e < a.H) a.h_state[(long)erow * a.H + ecol + e] = o[e];
+      }
+    } else {
+      *reinterpret_cast<f32x4_t *>(a.dA32 + eidx) = o;
+      store4<T>(dAc + eidx, o);
+    }
+    if (step + 1 < a.T) grid_barrier(a.counter, (unsigned)(step + 1) * nwg, a.spin_limit, a.flags);
+  }
+}
+
+}  // namespace rnnlm_dev

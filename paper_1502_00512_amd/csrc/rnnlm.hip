@@ -11,6 +11,7 @@
 #include "common.h"
 #include "gemm.h"
 #include "kernels.h"
+#include "rnn_persistent.h"
 
 using namespace rnnlm_dev;
 
@@ -21,7 +22,7 @@ using namespace rnnlm_dev;
   } while (0)
 
 struct WsLayout {
-  size_t Wo_c, U_c, Hs_c, ZT, dA_c, X32, dHs32, dA32, part32, stat, lse, zy, logp_int, xp, yp, perm, seg, xtmp, ytmp,
+  size_t Wo_c, U_c, UT_c, Hs_c, ZT, dA_c, X32, dHs32, dA32, part32, stat, lse, zy, logp_int, xp, yp, perm, seg, xtmp, ytmp,
       scalars, total;
   long partElems;
 };
@@ -39,6 +40,7 @@ struct rnnlm {
   WsLayout L;
   char *ws;
   // stage timing (host-side only)
+  unsigned spin_limit = 1u << 18;  // polls of a grid barrier before giving up (about a second)
   uint32_t prof_mask = 0;
   std::vector<EventPair> prof_pool;
   size_t prof_used = 0;
@@ -133,6 +135,7 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
   };
   L.Wo_c = take((size_t)Vp * Hp * es);
   L.U_c = take((size_t)Hp * Hp * es);
+  L.UT_c = take((size_t)Hp * Hp * es);
   L.Hs_c = take((size_t)(MpMax + Bp) * Hp * es);
   L.ZT = take((size_t)Vp * MpMax * es);
   L.dA_c = take((size_t)(MpMax + Bp) * Hp * es);
@@ -150,7 +153,7 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
   L.seg = take((size_t)(MpMax + 1) * 4);
   L.xtmp = take((size_t)c.T_max * c.B * 4);
   L.ytmp = take((size_t)c.T_max * c.B * 4);
-  L.scalars = take(256);  // [0]: int nseg, [8..15]: int flags[2], [32]: double sum, [40]: double running
+  L.scalars = take(256);  // [0]: int nseg, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64]: barrier counter
   L.total = o;
 }
 
@@ -162,6 +165,7 @@ int32_t *p_nseg(rnnlm_t *h) { return at<int32_t>(h, h->L.scalars); }
 int32_t *p_flags(rnnlm_t *h) { return at<int32_t>(h, h->L.scalars + 8); }
 double *p_sum(rnnlm_t *h) { return at<double>(h, h->L.scalars + 32); }
 double *p_running(rnnlm_t *h) { return at<double>(h, h->L.scalars + 40); }
+unsigned *p_counter(rnnlm_t *h) { return at<unsigned>(h, h->L.scalars + 64); }
 
 inline unsigned blocks_for(long n, int per) { return (unsigned)((n + per - 1) / per); }
 
@@ -173,6 +177,46 @@ int sync_copies(rnnlm_t *h, hipStream_t st) {
                      h->buf.Wo, c.V, c.H, h->Hp, nWo, at<T>(h, h->L.Wo_c));
   hipLaunchKernelGGL(to_compute_copy_kernel<T>, dim3(std::min<long>(blocks_for(nU, 256), 65535)), dim3(256), 0, st,
                      h->buf.U, c.H, c.H, h->Hp, nU, at<T>(h, h->L.U_c));
+  hipLaunchKernelGGL(transpose_kernel<T>, dim3(h->Hp / 32, h->Hp / 32), dim3(256), 0, st, at<T>(h, h->L.U_c), h->Hp,
+                     at<T>(h, h->L.UT_c));
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+// The persistent recurrent kernel applies when each wave's quarter of the contraction fits its
+// register file (Hp <= 1024) and the grid is small enough to be co-resident on the chip.
+bool persistent_ok(const rnnlm_t *h) {
+  const int ks = h->Hp / 64;
+  const long grid = (long)(h->Bp / 32) * (h->Hp / 32);
+  return h->Hp % 64 == 0 && (ks == 4 || ks == 8 || ks == 12 || ks == 16) && grid <= 192;
+}
+
+template <typename T, bool BACKWARD>
+int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st) {
+  RnnPersistArgs a;
+  a.W = BACKWARD ? at<T>(h, h->L.UT_c) : at<T>(h, h->L.U_c);
+  a.Hs = at<T>(h, h->L.Hs_c);
+  a.X = BACKWARD ? at<float>(h, h->L.dHs32) : at<float>(h, h->L.X32);
+  a.dA32 = at<float>(h, h->L.dA32);
+  a.dAc = at<T>(h, h->L.dA_c);
+  a.h_state = (!BACKWARD && advance_state) ? h->buf.h_state : nullptr;
+  a.counter = p_counter(h);
+  a.flags = p_flags(h);
+  a.T = Tn;
+  a.B = h->cfg.B;
+  a.H = h->cfg.H;
+  a.Bp = h->Bp;
+  a.Hp = h->Hp;
+  a.spin_limit = h->spin_limit;
+  hipLaunchKernelGGL(fill_kernel<uint32_t>, dim3(1), dim3(64), 0, st, p_counter(h), 1L, 0u);
+  const dim3 grid((unsigned)((h->Bp / 32) * (h->Hp / 32)));
+  switch (h->Hp / 64) {
+    case 4: hipLaunchKernelGGL((rnn_persistent_kernel<T, 4, BACKWARD>), grid, dim3(256), 0, st, a); break;
+    case 8: hipLaunchKernelGGL((rnn_persistent_kernel<T, 8, BACKWARD>), grid, dim3(256), 0, st, a); break;
+    case 12: hipLaunchKernelGGL((rnn_persistent_kernel<T, 12, BACKWARD>), grid, dim3(256), 0, st, a); break;
+    case 16: hipLaunchKernelGGL((rnn_persistent_kernel<T, 16, BACKWARD>), grid, dim3(256), 0, st, a); break;
+    default: return RNNLM_ERR_ARG;
+  }
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }
@@ -211,6 +255,11 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     HIP_TRY(hipGetLastError());
   }
 
+  if (persistent_ok(h)) {
+    StageTimer tm(h, RNNLM_STAGE_RNN_FWD, st);
+    int rc = launch_rnn_persistent<T, false>(h, Tn, advance_state, st);
+    if (rc) return rc;
+  } else
   for (int t = 0; t < Tn; ++t) {
     StageTimer tm(h, (t == 0 || t == Tn - 1) ? RNNLM_STAGE_RNN_FWD : -1, st, t == 0, t == Tn - 1);
     EpiRnnFwd<T> epi;
@@ -318,6 +367,11 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
   }
 
   // back-propagation through time over the window (stops at the window start)
+  if (persistent_ok(h)) {
+    StageTimer tm(h, RNNLM_STAGE_RNN_BWD, st);
+    int rc = launch_rnn_persistent<T, true>(h, Tn, false, st);
+    if (rc) return rc;
+  } else
   for (int t = Tn - 1; t >= 0; --t) {
     StageTimer tm(h, (t == 0 || t == Tn - 1) ? RNNLM_STAGE_RNN_BWD : -1, st, t == Tn - 1, t == 0);
     EpiRnnBwd<T> epi;
@@ -362,6 +416,11 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
     epi.alpha = u.alpha;
     epi.lr = u.lr;
     HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
+    if (u.refresh_copies) {
+      hipLaunchKernelGGL(transpose_kernel<T>, dim3(Hp / 32, Hp / 32), dim3(256), 0, st, U_c, Hp,
+                         at<T>(h, h->L.UT_c));
+      HIP_TRY(hipGetLastError());
+    }
   }
   // E[w] -= lr * sum_{m: x[m] = w} dA[m]
   StageTimer tm(h, RNNLM_STAGE_EMB, st);
@@ -508,10 +567,11 @@ int rnnlm_sync_compute_copies(rnnlm_t *h, void *stream) {
 int rnnlm_check(rnnlm_t *h, void *stream) {
   if (!h) return RNNLM_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
-  int32_t flags[2] = {0, 0};
+  int32_t flags[3] = {0, 0, 0};
   HIP_TRY(hipMemcpyAsync(flags, p_flags(h), sizeof(flags), hipMemcpyDeviceToHost, st));
-  hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(1), dim3(64), 0, st, p_flags(h), 2L, 0);
+  hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(1), dim3(64), 0, st, p_flags(h), 3L, 0);
   HIP_TRY(hipStreamSynchronize(st));
+  if (flags[2]) return RNNLM_ERR_TIMEOUT;
   if (flags[0]) return RNNLM_ERR_TOKEN_RANGE;
   if (flags[1]) return RNNLM_ERR_NONFINITE;
   return RNNLM_OK;
@@ -562,6 +622,12 @@ int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, 
   return sort_segments<float>(h, T, perm, seg_start, nseg, st);
 }
 
+int rnnlm_set_barrier_spin_limit(rnnlm_t *h, uint32_t polls) {
+  if (!h || polls == 0) return RNNLM_ERR_ARG;
+  h->spin_limit = polls;
+  return RNNLM_OK;
+}
+
 int rnnlm_profile_enable(rnnlm_t *h, uint32_t stage_mask) {
   if (!h || stage_mask >= (1u << RNNLM_STAGE_COUNT)) return RNNLM_ERR_ARG;
   h->prof_mask = stage_mask;
@@ -594,6 +660,7 @@ const char *rnnlm_status_string(int status) {
     case RNNLM_ERR_NONFINITE: return "non-finite log-probability sum";
     case RNNLM_ERR_HIP: return "HIP runtime error";
     case RNNLM_ERR_NOMEM: return "host allocation failed";
+    case RNNLM_ERR_TIMEOUT: return "grid barrier wait expired";
     default: return "unknown status";
   }
 }
