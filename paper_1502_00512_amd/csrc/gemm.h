@@ -19,8 +19,34 @@ struct GemmShape {
   long lda, ldb;        // leading dimensions in elements
   int tilesM, tilesN;   // output tiles
   int kBlocks;          // K / BK
-  int kBlocksPerSplit;  // K blocks handled by one blockIdx.y
+  int kBlocksPerSplit;  // K blocks handled by one split
+  int splits;
+  // Workgroup -> (split, tile) mapping.  Workgroups are dealt to the 8 XCDs (each with its own L2)
+  // round-robin by id, so id % 8 picks a contiguous chunk of `perXcd` work items and id / 8 walks it:
+  // neighbours in that walk run on one XCD at about the same time and share operand panels in its
+  // L2.  Inside a split, tiles are walked in bands of `band` tile rows (bandOverN = 0) or tile
+  // columns (bandOverN = 1), the other index running fastest.
+  int perXcd, band, bandOverN;
 };
+
+constexpr int NUM_XCD = 8;
+
+__device__ inline bool map_workgroup(const GemmShape &g, int id, int &split, int &tile_m, int &tile_n) {
+  const int tiles = g.tilesM * g.tilesN;
+  const int lin = (id % NUM_XCD) * g.perXcd + id / NUM_XCD;
+  if (id / NUM_XCD >= g.perXcd || lin >= tiles * g.splits) return false;
+  split = lin / tiles;
+  const int t = lin % tiles;
+  const int major = g.bandOverN ? g.tilesN : g.tilesM;  // banded index
+  const int minor = g.bandOverN ? g.tilesM : g.tilesN;
+  const int perBand = g.band * minor;
+  const int b = t / perBand, r = t % perBand;
+  const int width = min(g.band, major - b * g.band);
+  const int imajor = b * g.band + r % width, iminor = r / width;
+  tile_m = g.bandOverN ? iminor : imajor;
+  tile_n = g.bandOverN ? imajor : iminor;
+  return true;
+}
 
 // KBYTES = bytes of K held by one LDS tile row (128 or 64): BK = KBYTES / sizeof(T) elements.
 template <typename T, int ROWS, int LAYOUT, int KBYTES>
@@ -28,7 +54,7 @@ struct TileGeom {
   static constexpr int ES = sizeof(T);
   static constexpr int BK = KBYTES / ES;
   static constexpr int ROWK_STRIDE = KBYTES + 16;     // +16 B: 16-byte reads of 8 consecutive rows hit distinct banks
-  static constexpr int KROW_STRIDE = ROWS * ES + 32;  // +32 B: the 4 k-rows of a transposing read hit distinct banks
+  static constexpr int KROW_STRIDE = ROWS * ES + 64;  // +64 B: the 4 k rows x 64 B that a transposing read touches per clock hit distinct banks
   static constexpr int BYTES = (LAYOUT == ROWK) ? ROWS * ROWK_STRIDE : BK * KROW_STRIDE;
 };
 
@@ -159,16 +185,26 @@ __device__ inline void mma16(f32x16_t &acc, const F32x8 &a, const F32x8 &b) {
   for (int e = 0; e < 8; ++e) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.v[e], b.v[e], acc, 0, 0, 0);
 }
 
+// Pitch (bytes) of the bf16 staging tile: 144 dwords = 16 (mod 64), so the two rows and two
+// half-waves of one staged write land in distinct banks.
+template <int BN>
+struct StageGeom {
+  static constexpr int PITCH = BN * 2 + 64;
+};
+
 // What an epilogue sees: the workgroup's LDS (reusable: the main loop ends with a barrier), the
 // origin of the workgroup tile in C, the origin of this wave's sub-tile inside it, and ids.
 struct EpiCtx {
-  char *smem;
+  char *smem_lo, *smem_hi;  // LDS for staging the upper / lower half of the tile's rows
   int tile_row0, tile_col0;
   int wrow, wcol;
   int lane, tid, split;
 };
 
-template <typename T, int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi, int KBYTES, int MINWG>
+// PF = tiles of global loads in flight ahead of the tile being multiplied (1 or 2).  With PF = 2 the
+// loads of tile i+2 are issued before tile i is multiplied and land in LDS one iteration later, which
+// covers about two multiply phases of memory latency.
+template <typename T, int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi, int KBYTES, int MINWG, int PF>
 __global__ void __launch_bounds__(WGM *WGN * 64, MINWG) gemm_kernel(const GemmShape g, const Epi epi) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   constexpr int NT = WGM * WGN * 64;
@@ -183,8 +219,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64, MINWG) gemm_kernel(const GemmSh
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WGM, wn = wave / WGM;
-  const int tile_m = blockIdx.x % g.tilesM, tile_n = blockIdx.x / g.tilesM;
-  const int split = blockIdx.y;
+  int tile_m, tile_n, split;
+  if (!map_workgroup(g, blockIdx.x, split, tile_m, tile_n)) return;  // uniform for the workgroup
   const int kb0 = split * g.kBlocksPerSplit;
   const int kb1 = min(kb0 + g.kBlocksPerSplit, g.kBlocks);
   const int nk = kb1 - kb0;
@@ -197,50 +233,85 @@ __global__ void __launch_bounds__(WGM *WGN * 64, MINWG) gemm_kernel(const GemmSh
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  TileLoader<T, BM, LA, NT, KBYTES> la;
-  TileLoader<T, BN, LB, NT, KBYTES> lb;
+  TileLoader<T, BM, LA, NT, KBYTES> la[PF];
+  TileLoader<T, BN, LB, NT, KBYTES> lb[PF];
   const char *Ab = static_cast<const char *>(g.A);
   const char *Bb = static_cast<const char *>(g.B);
   const long lda_b = g.lda * ES, ldb_b = g.ldb * ES;
   const long arow0 = (long)tile_m * BM, brow0 = (long)tile_n * BN;
-
-  if (nk > 0) {
-    la.load(Ab, lda_b, arow0, (long)kb0 * BK, tid);
-    lb.load(Bb, ldb_b, brow0, (long)kb0 * BK, tid);
-    la.store(smem, tid);
-    lb.store(smem + GA::BYTES, tid);
-    __syncthreads();
-  }
   const int lr = lane & 31, lk = (lane >> 5) * 8;
-  for (int it = 0; it < nk; ++it) {
+
+  // one multiply phase on the LDS stage `it & 1`: operand fragments are double buffered so that the
+  // LDS reads of 16-wide step k+1 are in flight while the MFMAs of step k issue
+  auto multiply = [&](int it) {
     const char *sa = smem + (it & 1) * STAGE;
     const char *sb = sa + GA::BYTES;
-    const bool more = it + 1 < nk;
-    if (more) {
-      la.load(Ab, lda_b, arow0, (long)(kb0 + it + 1) * BK, tid);
-      lb.load(Bb, ldb_b, brow0, (long)(kb0 + it + 1) * BK, tid);
-    }
+    constexpr int KSTEPS = BK / 16;
+    typename FragT<T>::type fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int step, int buf) {
 #pragma unroll
-    for (int ks = 0; ks < BK; ks += 16) {
-      typename FragT<T>::type fa[TM], fb[TN];
+      for (int i = 0; i < TM; ++i)
+        fa[buf][i] = FragReader<T, BM, LA, KBYTES>::get(sa, wm * WTM + i * 32 + lr, step * 16 + lk);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = FragReader<T, BM, LA, KBYTES>::get(sa, wm * WTM + i * 32 + lr, ks + lk);
+      for (int j = 0; j < TN; ++j)
+        fb[buf][j] = FragReader<T, BN, LB, KBYTES>::get(sb, wn * WTN + j * 32 + lr, step * 16 + lk);
+    };
+    read_frags(0, 0);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = FragReader<T, BN, LB, KBYTES>::get(sb, wn * WTN + j * 32 + lr, ks + lk);
+    for (int step = 0; step < KSTEPS; ++step) {
+      if (step + 1 < KSTEPS) read_frags(step + 1, (step + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);  // keep the next step's LDS reads ahead of this step's MFMAs
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) mma16(acc[i][j], fa[i], fb[j]);
+        for (int j = 0; j < TN; ++j) mma16(acc[i][j], fa[step & 1][i], fb[step & 1][j]);
     }
-    if (more) {
-      char *da = smem + ((it + 1) & 1) * STAGE;
-      la.store(da, tid);
-      lb.store(da + GA::BYTES, tid);
+  };
+  // tile j travels through register set j % PF and LDS stage j & 1
+  auto fetch = [&](int j, int set) {
+    la[set].load(Ab, lda_b, arow0, (long)(kb0 + j) * BK, tid);
+    lb[set].load(Bb, ldb_b, brow0, (long)(kb0 + j) * BK, tid);
+  };
+  auto land = [&](int j, int set) {
+    char *d = smem + (j & 1) * STAGE;
+    la[set].store(d, tid);
+    lb[set].store(d + GA::BYTES, tid);
+  };
+
+  if (nk > 0) {
+    fetch(0, 0);
+    land(0, 0);
+    if (PF == 2) {
+      if (nk > 1) fetch(1, 1 % PF);
     }
     __syncthreads();
   }
+  if (PF == 1) {
+    for (int it = 0; it < nk; ++it) {
+      const bool more = it + 1 < nk;
+      if (more) fetch(it + 1, 0);
+      multiply(it);
+      if (more) land(it + 1, 0);
+      __syncthreads();
+    }
+  } else {
+    // unrolled by two so that register sets are addressed statically
+    for (int it = 0; it < nk; it += 2) {
+      if (it + 2 < nk) fetch(it + 2, 0);
+      multiply(it);
+      if (it + 1 < nk) land(it + 1, 1 % PF);
+      __syncthreads();
+      if (it + 1 < nk) {
+        if (it + 3 < nk) fetch(it + 3, 1 % PF);
+        multiply(it + 1);
+        if (it + 2 < nk) land(it + 2, 0);
+        __syncthreads();
+      }
+    }
+  }
   EpiCtx ctx;
-  ctx.smem = smem;
+  ctx.smem_lo = smem;
+  ctx.smem_hi = smem + (BM / 2) * StageGeom<BN>::PITCH;
   ctx.tile_row0 = tile_m * BM;
   ctx.tile_col0 = tile_n * BN;
   ctx.wrow = wm * WTM;
@@ -257,12 +328,6 @@ __global__ void __launch_bounds__(WGM *WGN * 64, MINWG) gemm_kernel(const GemmSh
 
 // ---- Tile store helpers --------------------------------------------------------------------------
 
-// Pitch (bytes) of the bf16 staging tile: 144 dwords = 16 (mod 64), so the two rows and two
-// half-waves of one staged write land in distinct banks.
-template <int BN>
-struct StageGeom {
-  static constexpr int PITCH = BN * 2 + 64;
-};
 
 // Writes the workgroup's BM x BN tile of values (already final, in MFMA accumulator layout) to
 // out[row][col] (leading dimension ld, no bounds: the caller's buffer is tile-padded).
@@ -307,7 +372,8 @@ __device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c
         const unsigned theirs = (unsigned)__builtin_amdgcn_mov_dpp((int)mine, 0xB1, 0xF, 0xF, true);  // lane ^ 1
         const unsigned word = odd ? ((theirs >> 16) | (mine & 0xffff0000u)) : ((mine & 0xffffu) | (theirs << 16));
         const int row = c.wrow + i * 32 + RNNLM_ACC_ROW(r0, c.lane) + (odd ? 1 : 0);
-        *reinterpret_cast<unsigned *>(c.smem + row * PITCH + (col & ~1) * 2) = word;
+        char *half = row < BM / 2 ? c.smem_lo : c.smem_hi;
+        *reinterpret_cast<unsigned *>(half + (row % (BM / 2)) * PITCH + (col & ~1) * 2) = word;
       }
     }
   __syncthreads();
@@ -315,7 +381,8 @@ __device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c
 #pragma unroll 4
   for (int idx = c.tid; idx < BM * CPR; idx += NT) {
     const int row = idx / CPR, ch = idx % CPR;
-    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(c.smem + row * PITCH + ch * 16);
+    const char *half = row < BM / 2 ? c.smem_lo : c.smem_hi;
+    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(half + (row % (BM / 2)) * PITCH + ch * 16);
     *reinterpret_cast<u32x4_t *>(out + (long)(c.tile_row0 + row) * ld + c.tile_col0 + ch * 8) = v;
   }
 }
@@ -542,16 +609,18 @@ struct EpiRnnBwd {
 
 // ---- Host launcher -----------------------------------------------------------------------------
 
-template <typename T, int BM, int BN, int WGM, int WGN, int LA, int LB, int KBYTES = 128, int MINWG = 1, class Epi>
+// band > 0: tiles walked in bands of `band` tile rows; band < 0: bands of -band tile columns.
+template <typename T, int BM, int BN, int WGM, int WGN, int LA, int LB, int KBYTES = 128, int MINWG = 1, int PF = 2,
+          class Epi>
 inline hipError_t launch_gemm(hipStream_t stream, const void *A, long lda, const void *B, long ldb, long Mg, long Ng,
-                              long K, int splits, const Epi &epi) {
+                              long K, int splits, const Epi &epi, int band = 4) {
   constexpr int BK = KBYTES / (int)sizeof(T);
   if (Mg <= 0 || Ng <= 0 || K < 0 || Mg % BM || Ng % BN || K % BK || splits < 1) return hipErrorInvalidValue;
   constexpr int loop_bytes = 2 * (TileGeom<T, BM, LA, KBYTES>::BYTES + TileGeom<T, BN, LB, KBYTES>::BYTES);
   constexpr int epi_bytes = Epi::template lds_bytes<BM, BN>();
   constexpr int smem_bytes = loop_bytes > epi_bytes ? loop_bytes : epi_bytes;
   static_assert(smem_bytes <= 160 * 1024, "tile does not fit the 160 KB of LDS");
-  auto kern = gemm_kernel<T, BM, BN, WGM, WGN, LA, LB, Epi, KBYTES, MINWG>;
+  auto kern = gemm_kernel<T, BM, BN, WGM, WGN, LA, LB, Epi, KBYTES, MINWG, PF>;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -568,7 +637,13 @@ inline hipError_t launch_gemm(hipStream_t stream, const void *A, long lda, const
   g.tilesN = (int)(Ng / BN);
   g.kBlocks = (int)(K / BK);
   g.kBlocksPerSplit = (g.kBlocks + splits - 1) / splits;
-  dim3 grid((unsigned)(g.tilesM * g.tilesN), (unsigned)splits);
+  g.splits = splits;
+  const long total = (long)g.tilesM * g.tilesN * splits;
+  if (band == 0 || total > (1L << 30)) return hipErrorInvalidValue;
+  g.perXcd = (int)((total + NUM_XCD - 1) / NUM_XCD);
+  g.bandOverN = band < 0;
+  g.band = band < 0 ? -band : band;
+  dim3 grid((unsigned)(g.perXcd * NUM_XCD));
   hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), smem_bytes, stream, g, epi);
   return hipGetLastError();
 }

@@ -10,6 +10,7 @@
 
 #include "common.h"
 #include "gemm.h"
+#include "gemm_dma.h"
 #include "kernels.h"
 #include "rnn_persistent.h"
 
@@ -93,9 +94,24 @@ namespace {
 
 // Tile shape of the three output-layer contractions and of the recurrent weight gradient: 256x256
 // output tile, 8 waves as 2 x 4 (wave tile 128 x 64).
-#define BIG_TILE 256, 256, 2, 4
 constexpr int BIG = 256;
-constexpr int OUT_WTM = 128;  // rows of the output-forward wave tile (one statistics partial each)
+// rows of the output-forward wave tile (one softmax-statistics partial each): the bf16 path runs that
+// contraction with 4 x 2 waves (64-row wave tiles), the fp32 path with 2 x 4 (128-row wave tiles)
+template <typename T>
+constexpr int out_wtm() {
+  return sizeof(T) == 2 ? 64 : 128;
+}
+
+// The large contractions: bf16 operands take the direct global->LDS kernel, fp32 the register-staged one.
+template <typename T, int WGM, int WGN, int LA, int LB, class Epi>
+hipError_t big_gemm(hipStream_t st, const void *A, long lda, const void *B, long ldb, long Mg, long Ng, long K,
+                    int splits, const Epi &epi, int band = 4) {
+  if constexpr (sizeof(T) == 2) {
+    return launch_gemm_dma<BIG, BIG, WGM, WGN, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
+  } else {
+    return launch_gemm<T, BIG, BIG, 2, 4, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
+  }
+}
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -123,7 +139,7 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
   Vp = (int)round_up(c.V, PAD_V);
   Bp = (int)round_up(c.B, PAD_B);
   MpMax = (int)round_up((long)c.T_max * Bp, PAD_M);
-  nPart = Vp / OUT_WTM;
+  nPart = Vp / 64;  // capacity for the finer of the two wave tilings
   const int BK = (es == 4) ? 32 : 64;
   const int S = desired_splits(MpMax, Hp, Vp / BK);
   L.partElems = (long)S * MpMax * Hp;
@@ -282,12 +298,11 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     epi.zy = zy;
     epi.V = c.V;
     epi.ldz = ldz;
-    HIP_TRY((launch_gemm<T, BIG_TILE, ROWK, ROWK>(st, at<T>(h, h->L.Wo_c), Hp, Hs_c + (long)Bp * Hp, Hp, Vp, Mp,
-                                                        Hp, 1, epi)));
+    HIP_TRY((big_gemm<T, 4, 2, ROWK, ROWK>(st, at<T>(h, h->L.Wo_c), Hp, Hs_c + (long)Bp * Hp, Hp, Vp, Mp, Hp, 1, epi)));
   }
   StageTimer tm(h, RNNLM_STAGE_STATS, st);
   hipLaunchKernelGGL(merge_stats_kernel, dim3(blocks_for(Mrows, 64)), dim3(1024), 0, st, at<float2>(h, h->L.stat),
-                     h->nPart, ldz, Tn, c.B, Bp, zy, lse, at<float>(h, h->L.logp_int), logp_out);
+                     Vp / out_wtm<T>(), ldz, Tn, c.B, Bp, zy, lse, at<float>(h, h->L.logp_int), logp_out);
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }
@@ -349,7 +364,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
     epi.split_stride = per;
     {
       StageTimer tm(h, RNNLM_STAGE_OUT_BWD_H, st);
-      HIP_TRY((launch_gemm<T, BIG_TILE, KROW, KROW>(st, ZT, ldz, Wo_c, Hp, Mp, Hp, Vp, S, epi)));
+      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW>(st, ZT, ldz, Wo_c, Hp, Mp, Hp, Vp, S, epi)));
     }
     if (S > 1) {
       StageTimer tm(h, RNNLM_STAGE_REDUCE, st);
@@ -400,7 +415,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
     epi.C = c.H;
     epi.alpha = u.alpha;
     epi.lr = u.lr;
-    HIP_TRY((launch_gemm<T, BIG_TILE, KROW, ROWK>(st, Hs_c + (long)Bp * Hp, Hp, ZT, ldz, Hp, Vp, Mp, 1, epi)));
+    HIP_TRY((big_gemm<T, 2, 4, KROW, ROWK>(st, Hs_c + (long)Bp * Hp, Hp, ZT, ldz, Hp, Vp, Mp, 1, epi, -2)));
   }
   // U[i][j] -= lr * sum_m dA[m][i] Hprev[m][j], contracted transposed (tile rows = j, tile columns = i)
   {
