@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--stages", action="store_true", help="also time every stage (adds event overhead)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run three 256 MiB device-to-device copies (counter calibration for profiler runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
@@ -115,6 +117,13 @@ def main() -> int:
         g.rnnlm_profile_enable(0)
         log("[bench] per-stage ms per step:", json.dumps(stage_ms))
 
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     words_per_s = args.steps * M / dt
     flops_word = 6.0 * H * (V + H)
     peak = PEAK_BF16_TFLOPS if cfg.precision == "bf16" else PEAK_FP32_TFLOPS
@@ -147,13 +156,24 @@ def main() -> int:
         "gemm_ms": {k: round(v, 4) for k, v in gemm_ms.items()},
         "loss_first_last": [round(first_loss, 4), round(last_loss, 4)],
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
-                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None},
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                     "traffic": measured_traffic(cfg.name, dominant)},
         "cpu_baseline": cpu,
     }
     if stage_ms is not None:
         res["stage_ms"] = stage_ms
     print(json.dumps(res), flush=True)
     return 0
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of the kernel, from the committed counter summary (profiles/hbm_traffic.json:
+    rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a device copy of known size); None if not measured."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            return json.load(f)[workload][kernel]["bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def cpu_baseline(cfg, E, U, Wo, b, tok):
