@@ -17,6 +17,7 @@ enum : int { ROWK = 0, KROW = 1 };
 struct GemmShape {
   const void *A, *B;
   long lda, ldb;        // leading dimensions in elements
+  long bytesA, bytesB;  // extents of the operands (used by the buffer-resource loads)
   int tilesM, tilesN;   // output tiles
   int kBlocks;          // K / BK
   int kBlocksPerSplit;  // K blocks handled by one split
@@ -633,6 +634,7 @@ inline hipError_t launch_gemm(hipStream_t stream, const void *A, long lda, const
   g.B = B;
   g.lda = lda;
   g.ldb = ldb;
+  g.bytesA = g.bytesB = 0;
   g.tilesM = (int)(Mg / BM);
   g.tilesN = (int)(Ng / BN);
   g.kBlocks = (int)(K / BK);

@@ -27,69 +27,102 @@ typedef const __attribute__((address_space(1))) void *global_void_ptr;
 __device__ inline int rowk_swz(int row) { return (row >> 1) & 7; }
 __device__ inline int krow_swz(int k) { return (k & 3) << 2; }
 
+// (Device pass only: the buffer-resource type does not exist for the host target, and a kernel template
+// whose body fails to instantiate there loses its launch stub.)
+#if defined(__HIP_DEVICE_COMPILE__)
+// Loads go through a buffer resource (base + 32-bit per-lane offset + scalar offset): no 64-bit
+// address arithmetic in the loop, one VGPR per load, and reads past the operand return zero instead
+// of faulting.
 template <int ROWS, int LAYOUT, int NT>
 struct DmaLoader {
   static constexpr int BLOCKS = ROWS * 128 / 1024;  // kilobyte blocks per tile
   static constexpr int NW = NT / 64;
   static constexpr int PER = BLOCKS / NW;
   static_assert(BLOCKS % NW == 0, "tile does not divide over the waves");
-  const char *gp[PER];  // this lane's global source of each of its blocks, at k block 0
-  long kstep;           // bytes to advance per k block
+  int off[PER];  // this lane's byte offset inside a k block for each of its kilobyte blocks
+  __amdgpu_buffer_rsrc_t rsrc;
+  int kstep;     // bytes to advance per k block
 
-  __device__ inline void init(const char *base, long ld_bytes, long row0, long k0, int tid) {
+  // op: operand base; op_bytes: its extent; (row0, k0): first tile row and first k of this workgroup
+  __device__ inline void init(const char *op, long op_bytes, long ld_bytes, long row0, long k0, int tid) {
     const int wave = tid >> 6, lane = tid & 63;
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       const int q = (wave + i * NW) * 64 + lane;  // physical chunk index inside the tile
       if (LAYOUT == ROWK) {
         const int r = q >> 3, p = q & 7;
-        gp[i] = base + (row0 + r) * ld_bytes + k0 * 2 + ((p ^ rowk_swz(r)) << 4);
+        off[i] = (int)(r * ld_bytes + ((p ^ rowk_swz(r)) << 4));
       } else {
         constexpr int CPR = ROWS / 8;
         const int k = q / CPR, p = q % CPR;
-        gp[i] = base + (k0 + k) * ld_bytes + row0 * 2 + ((p ^ krow_swz(k)) << 4);
+        off[i] = (int)(k * ld_bytes + ((p ^ krow_swz(k)) << 4));
       }
     }
-    kstep = (LAYOUT == ROWK) ? 128 : 64 * ld_bytes;
+    const long start = (LAYOUT == ROWK) ? row0 * ld_bytes + k0 * 2 : k0 * ld_bytes + row0 * 2;
+    kstep = (LAYOUT == ROWK) ? 128 : (int)(64 * ld_bytes);
+    const long left = op_bytes - start;
+    const unsigned records = left > 0xffffffffL ? 0xffffffffu : (unsigned)left;
+    rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(op + start), 0, (int)records, 0x00020000);
   }
-  // issues the loads of the next k block into `tile` (LDS) and advances
-  __device__ inline void issue(char *tile, int tid) {
+  // issues the loads of k block kb (relative to the first) into `tile` (LDS)
+  __device__ inline void issue(char *tile, int kb, int tid) const {
     const int wave = tid >> 6;
+    const int soff = kb * kstep;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      __builtin_amdgcn_global_load_lds((global_void_ptr)gp[i], (lds_void_ptr)(tile + (wave + i * NW) * 1024), 16, 0, 0);
-      gp[i] += kstep;
-    }
+    for (int i = 0; i < PER; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_void_ptr)(tile + (wave + i * NW) * 1024), 16, off[i], soff, 0, 0);
   }
 };
 
+#endif  // __HIP_DEVICE_COMPILE__
+
+// Fragment addressing.  A lane's byte offsets inside an operand tile are split into a per-lane part
+// computed once (4 registers per operand) and compile-time parts that fold into the instruction's
+// immediate offset, so the loop spends no VALU work on addresses.
+//   ROWK: row r = r0 + 32 i, 16-wide step st: r*128 + ((2 st + h) ^ swz(r)) * 16 with h = lane / 32.
+//         swz(r) does not depend on i (it uses row bits 1..3), so: pre[st] = r0*128 + (((2 st + h) ^ swz) << 4),
+//         immediate = i * 4096.
+//   KROW: transposing reads (see FragReader<bf16_t, ROWS, KROW> in gemm.h): source lane s of a 16-lane
+//         block points at tile[k][n .. n+3], k = 16 st + 8 h + s/4 (+4 for the second read),
+//         n = r0' + 32 i + 4 (s % 4); byte offset k*ROWS*2 + (((n >> 3) ^ swz(k)) << 4) + (n & 7)*2, and
+//         swz(k) = 4 (s/4 & 3) is a per-lane constant: pre[i] = (8 h + s/4)*ROWS*2 + that chunk term,
+//         immediate = st * 16 * ROWS * 2 (+ 4 * ROWS * 2).
 template <int ROWS, int LAYOUT>
-struct DmaFragReader;
+struct DmaFragAddr;
 template <int ROWS>
-struct DmaFragReader<ROWS, ROWK> {
-  // 8 consecutive-k elements of tile row r starting at k offset ks (a multiple of 8)
-  __device__ static inline bf16x8_t get(const char *tile, int r, int ks) {
-    return *reinterpret_cast<const bf16x8_t *>(tile + r * 128 + (((ks >> 3) ^ rowk_swz(r)) << 4));
+struct DmaFragAddr<ROWS, ROWK> {
+  int pre[4];
+  __device__ inline void init(int r0, int lane) {  // r0: the lane's row in the wave's first 32-row block
+    const int h = lane >> 5, sw = rowk_swz(r0);
+#pragma unroll
+    for (int st = 0; st < 4; ++st) pre[st] = r0 * 128 + (((2 * st + h) ^ sw) << 4);
+  }
+  __device__ inline bf16x8_t get(const char *tile, int i, int st) const {
+    return *reinterpret_cast<const bf16x8_t *>(tile + pre[st] + i * 4096);
   }
 };
 template <int ROWS>
-struct DmaFragReader<ROWS, KROW> {
-  // transposing reads, see FragReader<bf16_t, ROWS, KROW>: source lane s of a 16-lane block points at
-  // tile[ks + s/4][r0 + 4*(s%4) .. +3]
-  __device__ static inline bf16x8_t get(const char *tile, int r, int ks) {
+struct DmaFragAddr<ROWS, KROW> {
+  int pre[4];
+  __device__ inline void init(int r0, int lane) {
+    const int h = lane >> 5, s = lane & 15;
+    const int k = 8 * h + (s >> 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = (r0 - s) + 32 * i + 4 * (s & 3);
+      pre[i] = k * (ROWS * 2) + ((((n >> 3) ^ krow_swz(k)) << 4) | ((n & 7) << 1));
+    }
+  }
+  __device__ inline bf16x8_t get(const char *tile, int i, int st) const {
     typedef short s16x4_t __attribute__((ext_vector_type(4)));
     typedef __attribute__((address_space(3))) s16x4_t *lds_ptr_t;
-    const int lane = threadIdx.x & 63;
-    const int s = lane & 15;
-    const int k = ks + (s >> 2);
-    const int n = (r - s) + 4 * (s & 3);
-    const char *p = tile + k * (ROWS * 2) + ((((n >> 3) ^ krow_swz(k)) << 4) | ((n & 7) << 1));
+    const char *p = tile + pre[i] + st * (16 * ROWS * 2);
     union {
-      s16x4_t h[2];
+      s16x4_t hh[2];
       bf16x8_t f;
     } u;
-    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
-    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * ROWS * 2));
+    u.hh[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p));
+    u.hh[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(p + 4 * ROWS * 2));
     return u.f;
   }
 };
@@ -103,6 +136,7 @@ constexpr int dma_stage_bytes() {
 
 template <int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma_kernel(const GemmShape g, const Epi epi) {
+#if defined(__HIP_DEVICE_COMPILE__)
   constexpr int NT = WGM * WGN * 64;
   constexpr int BK = 64;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -129,50 +163,78 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma_kernel(const GemmShape
 
   DmaLoader<BM, LA, NT> la;
   DmaLoader<BN, LB, NT> lb;
-  la.init(static_cast<const char *>(g.A), g.lda * 2, (long)tile_m * BM, (long)kb0 * BK, tid);
-  lb.init(static_cast<const char *>(g.B), g.ldb * 2, (long)tile_n * BN, (long)kb0 * BK, tid);
-  const int lr = lane & 31, lk = (lane >> 5) * 8;
+  la.init(static_cast<const char *>(g.A), g.bytesA, g.lda * 2, (long)tile_m * BM, (long)kb0 * BK, tid);
+  lb.init(static_cast<const char *>(g.B), g.bytesB, g.ldb * 2, (long)tile_n * BN, (long)kb0 * BK, tid);
+  const int lr = lane & 31;
 
-  auto fetch = [&](char *stage) {
-    la.issue(stage, tid);
-    lb.issue(stage + BM * 128, tid);
+  // tile index is clamped to the last one: the final iterations re-fetch it instead of branching
+  auto fetch = [&](char *stage, int kb) {
+    kb = min(kb, nk - 1);
+    la.issue(stage, kb, tid);
+    lb.issue(stage + BM * 128, kb, tid);
   };
-  auto multiply = [&](const char *stage) {
+  // Software pipeline over the four 16-wide steps of a tile, with fragments double buffered in
+  // registers: the reads of step k+1 are issued before the MFMAs of step k.  The barrier that
+  // publishes the next tile sits BEFORE the last step's MFMAs, and the next tile's first fragments
+  // are read right after it, so their LDS latency is covered by those MFMAs instead of stalling the
+  // start of the next iteration.
+  static_assert(TM <= 4 && TN <= 4, "fragment addressing covers up to four 32-row blocks per wave");
+  bf16x8_t fa[2][TM], fb[2][TN];
+  DmaFragAddr<BM, LA> addr_a;
+  DmaFragAddr<BN, LB> addr_b;
+  addr_a.init(wm * WTM + lr, lane);
+  addr_b.init(wn * WTN + lr, lane);
+  auto read_frags = [&](const char *stage, int step, int buf) {
     const char *sa = stage;
     const char *sb = stage + BM * 128;
-    bf16x8_t fa[2][TM], fb[2][TN];
-    auto read_frags = [&](int step, int buf) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[buf][i] = DmaFragReader<BM, LA>::get(sa, wm * WTM + i * 32 + lr, step * 16 + lk);
+    for (int i = 0; i < TM; ++i) fa[buf][i] = addr_a.get(sa, i, step);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[buf][j] = DmaFragReader<BN, LB>::get(sb, wn * WTN + j * 32 + lr, step * 16 + lk);
-    };
-    read_frags(0, 0);
+    for (int j = 0; j < TN; ++j) fb[buf][j] = addr_b.get(sb, j, step);
+  };
+  auto mfmas = [&](int buf) {
 #pragma unroll
-    for (int step = 0; step < BK / 16; ++step) {
-      if (step + 1 < BK / 16) read_frags(step + 1, (step + 1) & 1);
-      __builtin_amdgcn_sched_barrier(0);  // keep the next step's LDS reads ahead of this step's MFMAs
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int j = 0; j < TN; ++j) mma16(acc[i][j], fa[buf][i], fb[buf][j]);
+  };
+  constexpr int KSTEPS = BK / 16;
+  // steps 0 .. KSTEPS-2 of the tile in `stage` (its step-0 fragments are already in buffer 0)
+  auto head_steps = [&](const char *stage) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) mma16(acc[i][j], fa[step & 1][i], fb[step & 1][j]);
+    for (int step = 0; step + 1 < KSTEPS; ++step) {
+      read_frags(stage, step + 1, (step + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      mfmas(step & 1);
     }
+  };
+  // last step of the current tile, overlapped with the first fragment reads of the tile in `next`
+  // (read unconditionally: after the last tile they fetch stale but in-bounds LDS and are unused)
+  auto tail_step = [&](const char *next) {
+    read_frags(next, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas((KSTEPS - 1) & 1);
   };
 
   if (nk > 0) {
-    fetch(stage0);
+    fetch(stage0, 0);
     __syncthreads();  // waits for this wave's loads, then for everyone's
-  }
-  for (int it = 0; it < nk; it += 2) {
-    if (it + 1 < nk) fetch(stage1);
-    multiply(stage0);
-    __syncthreads();
-    if (it + 1 < nk) {
-      if (it + 2 < nk) fetch(stage0);
-      multiply(stage1);
-      __syncthreads();
+    read_frags(stage0, 0, 0);
+#pragma unroll 1
+    for (int it = 0; it < nk; it += 2) {
+      fetch(stage1, it + 1);
+      head_steps(stage0);
+      __syncthreads();  // tile it+1 has landed; every wave has finished reading stage0
+      tail_step(stage1);
+      if (it + 1 < nk) {
+        fetch(stage0, it + 2);
+        head_steps(stage1);
+        __syncthreads();
+        tail_step(stage0);
+      }
     }
   }
+  __syncthreads();  // all loads have landed and all fragment reads are done: the epilogue reuses both stages
   EpiCtx ctx;
   ctx.smem_lo = stage0;
   ctx.smem_hi = stage1;
@@ -184,6 +246,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma_kernel(const GemmShape
   ctx.tid = tid;
   ctx.split = split;
   epi.template run<BM, BN, TM, TN, NT>(acc, ctx);
+#endif  // __HIP_DEVICE_COMPILE__
 }
 
 template <int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi>
@@ -197,6 +260,12 @@ inline hipError_t launch_gemm_dma(hipStream_t stream, const void *A, long lda, c
   g.B = B;
   g.lda = lda;
   g.ldb = ldb;
+  g.bytesA = 2 * lda * (LA == ROWK ? Mg : K);
+  g.bytesB = 2 * ldb * (LB == ROWK ? Ng : K);
+  // one k block of a K-major operand must stay within a 32-bit scalar offset
+  if ((LA == KROW && K * lda * 2 >= (1L << 31)) || (LB == KROW && K * ldb * 2 >= (1L << 31)) ||
+      lda * 2 * BM >= (1L << 31) || ldb * 2 * BN >= (1L << 31))
+    return hipErrorInvalidValue;
   g.tilesM = (int)(Mg / BM);
   g.tilesN = (int)(Ng / BN);
   g.kBlocks = (int)(K / BK);
