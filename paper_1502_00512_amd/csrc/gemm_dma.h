@@ -192,11 +192,15 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma_kernel(const GemmShape
 #pragma unroll
     for (int j = 0; j < TN; ++j) fb[buf][j] = addr_b.get(sb, j, step);
   };
+  // MFMA clusters run at raised wave priority so that, of the two waves sharing a SIMD, the one with
+  // operands ready wins the issue slot over the one still issuing loads.
   auto mfmas = [&](int buf) {
+    __builtin_amdgcn_s_setprio(3);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) mma16(acc[i][j], fa[buf][i], fb[buf][j]);
+    __builtin_amdgcn_s_setprio(0);
   };
   constexpr int KSTEPS = BK / 16;
   // steps 0 .. KSTEPS-2 of the tile in `stage` (its step-0 fragments are already in buffer 0)

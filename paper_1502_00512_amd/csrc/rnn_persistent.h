@@ -3,10 +3,10 @@
 // work into one large matrix product; on this hardware the serial chain is latency-bound instead, so
 // the matrix stays on chip and only the B x H state travels between steps).
 //
-// Decomposition: workgroup (sb, ub) owns streams [32 sb, +32) x hidden units [32 ub, +32).  Its four
-// waves split the contraction dimension in quarters; each keeps its 32 x (Hp/4) slice of U (forward:
+// Decomposition: workgroup (sb, ub) owns streams [32 sb, +32) x hidden units [32 ub, +32).  Its NWAVE
+// (4 or 8) waves split the contraction dimension evenly; each keeps its 32 x (Hp/NWAVE) slice of U (forward:
 // rows of U; backward: rows of U^T) as MFMA operand fragments in registers, loads the matching part
-// of the previous step's state straight from L2 into operand fragments, and the four partial 32x32
+// of the previous step's state straight from L2 into operand fragments, and the NWAVE partial 32x32
 // tiles are summed through LDS.  Steps are separated by a grid-wide barrier (one atomic counter,
 // agent-scope release/acquire); the host guarantees the grid is small enough to be co-resident, and
 // the spin is bounded: on expiry a flag is raised and every workgroup still runs to completion.
@@ -139,11 +139,11 @@ __device__ inline f32x4_t load4<bf16_t>(const bf16_t *p) {
   return v;
 }
 
-// KS = 16-wide contraction steps per wave = Hp / 64.  BACKWARD = false: h_t = sigmoid(X_t + h_{t-1} U^T)
+// KS = 16-wide contraction steps per wave = Hp / (16 NWAVE).  BACKWARD = false: h_t = sigmoid(X_t + h_{t-1} U^T)
 // for t = 0..T-1.  BACKWARD = true: dA_t = (dHs_t + dA_{t+1} U) * h_t * (1 - h_t) for t = T-1..0.
-template <typename T, int KS, bool BACKWARD>
-__global__ void __launch_bounds__(256) rnn_persistent_kernel(const RnnPersistArgs a) {
-  __shared__ __attribute__((aligned(16))) float red[4][16][64];
+template <typename T, int KS, int NWAVE, bool BACKWARD>
+__global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPersistArgs a) {
+  __shared__ __attribute__((aligned(16))) float red[NWAVE][16][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nsb = a.Bp / 32;
   const int sb = blockIdx.x % nsb, ub = blockIdx.x / nsb;
@@ -159,12 +159,13 @@ __global__ void __launch_bounds__(256) rnn_persistent_kernel(const RnnPersistArg
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) w[kk] = load_frag_global<T, false>(Wp + kk * 16);
   }
-  // epilogue ownership: thread -> accumulator element r = tid/16 of lanes 4*(tid%16) .. +3, i.e. one
-  // stream and 4 consecutive hidden units
-  const int er = tid >> 4, el = (tid & 15) * 4;
+  // epilogue ownership (first 256 threads): thread -> accumulator element r = tid/16 of lanes
+  // 4*(tid%16) .. +3, i.e. one stream and 4 consecutive hidden units
+  const bool epi_thread = tid < 256;
+  const int er = (tid >> 4) & 15, el = (tid & 15) * 4;
   const int erow = sb * 32 + ((er >> 2) << 3) + ((el >> 5) << 2) + (er & 3);
   const int ecol = ub * 32 + (el & 31);
-  const bool row_ok = erow < a.B;
+  const bool row_ok = epi_thread && erow < a.B;
   T *Hs = static_cast<T *>(a.Hs);
   T *dAc = static_cast<T *>(a.dAc);
   const unsigned nwg = gridDim.x;
@@ -197,7 +198,7 @@ __global__ void __launch_bounds__(256) rnn_persistent_kernel(const RnnPersistArg
     __syncthreads();
     f32x4_t s = *reinterpret_cast<const f32x4_t *>(&red[0][er][el]);
 #pragma unroll
-    for (int q = 1; q < 4; ++q) {
+    for (int q = 1; q < NWAVE; ++q) {
       const f32x4_t p = *reinterpret_cast<const f32x4_t *>(&red[q][er][el]);
 #pragma unroll
       for (int e = 0; e < 4; ++e) s[e] += p[e];
@@ -212,7 +213,9 @@ __global__ void __launch_bounds__(256) rnn_persistent_kernel(const RnnPersistArg
         o[e] = ok ? (xin[e] + s[e]) * hcur[e] * (1.0f - hcur[e]) : 0.0f;
       }
     }
-    if (!BACKWARD) {
+    if (!epi_thread) {
+      // waves 4..7 only contribute partial sums
+    } else if (!BACKWARD) {
       store4<T>(Hs + slot + eidx, o);
       if (a.h_state && step == a.T - 1 && row_ok) {
 #pragma unroll

@@ -199,12 +199,15 @@ int sync_copies(rnnlm_t *h, hipStream_t st) {
   return RNNLM_OK;
 }
 
-// The persistent recurrent kernel applies when each wave's quarter of the contraction fits its
-// register file (Hp <= 1024) and the grid is small enough to be co-resident on the chip.
+// The persistent recurrent kernel applies when each wave's share of the contraction fits its register
+// file (4 waves up to Hp = 1024, 8 waves up to Hp = 2048) and the grid is small enough to be co-resident
+// with a wide margin (at most half of what the chip can hold at once).
 bool persistent_ok(const rnnlm_t *h) {
-  const int ks = h->Hp / 64;
   const long grid = (long)(h->Bp / 32) * (h->Hp / 32);
-  return h->Hp % 64 == 0 && (ks == 4 || ks == 8 || ks == 12 || ks == 16) && grid <= 192;
+  if (h->Hp <= 1024) return h->Hp % 256 == 0 && grid <= 256;
+  // the 8-wave variant has half the registers per wave: bf16 fragments only
+  if (h->Hp <= 2048) return h->cfg.precision == RNNLM_BF16_FP32MASTER && h->Hp % 256 == 0 && grid <= 256;
+  return false;
 }
 
 template <typename T, bool BACKWARD>
@@ -226,13 +229,20 @@ int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st
   a.spin_limit = h->spin_limit;
   hipLaunchKernelGGL(fill_kernel<uint32_t>, dim3(1), dim3(64), 0, st, p_counter(h), 1L, 0u);
   const dim3 grid((unsigned)((h->Bp / 32) * (h->Hp / 32)));
-  switch (h->Hp / 64) {
-    case 4: hipLaunchKernelGGL((rnn_persistent_kernel<T, 4, BACKWARD>), grid, dim3(256), 0, st, a); break;
-    case 8: hipLaunchKernelGGL((rnn_persistent_kernel<T, 8, BACKWARD>), grid, dim3(256), 0, st, a); break;
-    case 12: hipLaunchKernelGGL((rnn_persistent_kernel<T, 12, BACKWARD>), grid, dim3(256), 0, st, a); break;
-    case 16: hipLaunchKernelGGL((rnn_persistent_kernel<T, 16, BACKWARD>), grid, dim3(256), 0, st, a); break;
+#define RNNLM_LAUNCH_PERSIST(KS, NW) \
+  hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD>), grid, dim3(64 * NW), 0, st, a)
+  switch (h->Hp / 256) {
+    case 1: RNNLM_LAUNCH_PERSIST(4, 4); break;
+    case 2: RNNLM_LAUNCH_PERSIST(8, 4); break;
+    case 3: RNNLM_LAUNCH_PERSIST(12, 4); break;
+    case 4: RNNLM_LAUNCH_PERSIST(16, 4); break;
+    case 5: RNNLM_LAUNCH_PERSIST(10, 8); break;
+    case 6: RNNLM_LAUNCH_PERSIST(12, 8); break;
+    case 7: RNNLM_LAUNCH_PERSIST(14, 8); break;
+    case 8: RNNLM_LAUNCH_PERSIST(16, 8); break;
     default: return RNNLM_ERR_ARG;
   }
+#undef RNNLM_LAUNCH_PERSIST
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }

@@ -56,6 +56,7 @@ SHAPES_FP32 = [
     (300, 130, 3, 1),
     (520, 96, 70, 2),
     (500, 200, 800, 2),   # too many streams for the persistent recurrent kernel: per-step launches
+    (400, 1100, 6, 3),    # H > 1024 in fp32: per-step launches
 ]
 
 
@@ -221,7 +222,8 @@ def test_token_out_of_range_is_reported_not_faulted():
                                 torch.zeros(5, 2, dtype=torch.int32, device="cuda"))  # T > T_max
 
 
-BF16_SHAPES = [(3000, 256, 32, 4), (2049, 130, 5, 9), (5000, 384, 64, 6), (1000, 1100, 8, 3)]  # last: H > 1024, per-step recurrent launches
+# the last two: 1024 < H <= 2048 (8-wave persistent recurrent kernel) and H > 2048 (per-step launches)
+BF16_SHAPES = [(3000, 256, 32, 4), (2049, 130, 5, 9), (5000, 384, 64, 6), (1000, 1100, 8, 3), (700, 2100, 4, 2)]
 
 
 @pytest.mark.parametrize("V,H,B,T", BF16_SHAPES)
