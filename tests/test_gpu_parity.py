@@ -280,3 +280,89 @@ def test_grid_barrier_timeout_is_reported():
     g.rnnlm_reset_state()
     g.rnnlm_forward_logprob(dev(x), dev(y))
     g.rnnlm_check()
+
+
+# ---- full-size checks, in the launch configuration bench.py times -------------------------------------
+
+def _cfg_pair(name, T=None, weights="config"):
+    cfg = synth.CONFIGS[name]
+    T = cfg.T if T is None else T
+    if weights == "config":
+        E, U, Wo, b = synth.make_weights(cfg.V, cfg.H, cfg.init, cfg.init_scale, cfg.weight_seed)
+    else:  # cheaper generator for the largest shapes, same scale
+        E, U, Wo, b = synth.make_weights(cfg.V, cfg.H, "uniform", cfg.init_scale * 1.7, cfg.weight_seed)
+    precision = BF16 if cfg.precision == "bf16" else FP32
+    g = binding.Rnnlm(E, U, Wo, b, cfg.B, cfg.T, precision)
+    return cfg, T, g, (E, U, Wo, b)
+
+
+def test_cfg2_full_size_fp32_window():
+    """cfg2 (V=10,000 H=256 B=32 T=10, fp32): two whole training windows against the oracle."""
+    cfg, T, g, (E, U, Wo, b) = _cfg_pair("cfg2")
+    o = O.Model.from_weights(E, U, Wo, b, cfg.B)
+    tok = synth.make_tokens(cfg, 100_000)
+    dtok = dev(tok)
+    logp = torch.empty(T, cfg.B, device="cuda")
+    for k in range(2):
+        x, y = g.rnnlm_stream_chunk(dtok, k, T)
+        r = g.rnnlm_grad_chunk(x, y)
+        ref = O.grad_chunk(o, *O.stream_chunk(tok, cfg.B, T, k))
+        check_logp(r["logp"], ref["logp"])
+        for kk in ("gE", "gU", "gWo", "gb"):
+            check_grad(kk, r[kk], ref[kk])
+        g.rnnlm_train_chunk(x, y, cfg.lr, logp)
+        O.train_chunk(o, *O.stream_chunk(tok, cfg.B, T, k), cfg.lr)
+    g.rnnlm_check()
+
+
+def test_cfg3_full_size_bf16_window():
+    """cfg3 (V=64,000 H=1024 B=128 T=20, bf16 operands): one whole window, all 2560 positions, against
+    the oracle: window perplexity within 1e-2, every gradient tensor within 2e-2 of its scale, then the
+    SGD step itself (updated masters = old - lr * gradient to fp32 rounding)."""
+    cfg, T, g, (E, U, Wo, b) = _cfg_pair("cfg3")
+    o = O.Model.from_weights(E, U, Wo, b, cfg.B)
+    tok = synth.make_tokens(cfg, 2_000_000)
+    x, y = O.stream_chunk(tok, cfg.B, T, 0)
+    r = g.rnnlm_grad_chunk(dev(x), dev(y))
+    ref = O.grad_chunk(o, x, y)
+    ppl_g = math.exp(-r["logp"].double().mean().item())
+    ppl_r = math.exp(-ref["logp"].mean())
+    assert abs(ppl_g / ppl_r - 1) < 1e-2, (ppl_g, ppl_r)
+    assert np.abs(r["logp"].cpu().numpy() - ref["logp"]).max() < 5e-2
+    for kk in ("gE", "gU", "gWo", "gb"):
+        check_grad(kk, r[kk], ref[kk], rel=2e-2)
+    assert abs(r["gb"].double().sum().item()) < 1e-4          # softmax gradient sums to zero over the vocabulary
+    Wo0 = g.Wo.clone()
+    b0 = g.b.clone()
+    g.rnnlm_train_chunk(dev(x), dev(y), cfg.lr)
+    assert torch.allclose(g.Wo, Wo0 - cfg.lr * r["gWo"], rtol=0, atol=1e-7)
+    assert torch.allclose(g.b, b0 - cfg.lr * r["gb"], rtol=0, atol=1e-7)
+    g.rnnlm_check()
+
+
+@pytest.mark.parametrize("name,streams", [("cfg4", (0, 77, 127)), ("cfg5", (0, 200, 255))])
+def test_large_configs_sampled_streams(name, streams):
+    """cfg4 / cfg5 at full shape: the oracle scores three whole streams of the first window one by one
+    (streams are independent in the forward pass); the GPU's log-probs for those streams must give the
+    same perplexity within 1e-2.  Properties that hold at any size: finite results, bias gradient sums to
+    zero, rows of the embedding gradient for ids not in the window are zero."""
+    cfg, T, g, (E, U, Wo, b) = _cfg_pair(name, weights="uniform")
+    tok = synth.make_tokens(cfg, 4_000_000)
+    x, y = O.stream_chunk(tok, cfg.B, T, 0)
+    r = g.rnnlm_grad_chunk(dev(x), dev(y))
+    got = r["logp"].cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    E64, U64, Wo64, b64 = (np.asarray(a, np.float64) for a in (E, U, Wo, b))
+    for s in streams:
+        o1 = O.Model(E64, U64, Wo64, b64, np.zeros((1, cfg.H)))
+        ref = O.forward_logprob(o1, np.ascontiguousarray(x[:, s:s + 1]), np.ascontiguousarray(y[:, s:s + 1]))[:, 0]
+        assert abs(math.exp(-got[:, s].mean()) / math.exp(-ref.mean()) - 1) < 1e-2
+        assert np.abs(got[:, s] - ref).max() < 5e-2
+    assert abs(r["gb"].double().sum().item()) < 1e-4
+    for kk in ("gE", "gU", "gWo", "gb"):
+        assert torch.isfinite(r[kk]).all()
+    seen = torch.zeros(cfg.V, dtype=torch.bool, device="cuda")
+    seen[dev(x).long().flatten()] = True
+    assert not r["gE"][~seen].any()
+    assert r["gE"][seen].abs().sum() > 0
+    g.rnnlm_check()
