@@ -168,7 +168,9 @@ __global__ void sum_logp_kernel(const float *__restrict__ logp, int n, double *_
 // ---- a4 (part 2) + a5: fused softmax gradient, in place on the vocabulary-major logits ----------
 //   dz[v][m] = (exp(z[v][m] - lse[m]) - [v == y[m]]) / M      (gradient of the mean NLL)
 //   db[v]    = sum_m dz[v][m];   b_out[v] = alpha*b[v] - lr*db[v]
-// One wavefront per vocabulary row; rows v >= V and padded positions (lse = +inf) become zero.
+// One wavefront owns ROWS_PER_WAVE vocabulary rows and walks the window positions once, so the
+// per-position lse / target id loaded for a 16-byte column chunk serve all of its rows and several row
+// loads are in flight per lane.  Rows v >= V and padded positions (lse = +inf) become zero.
 template <typename T>
 __global__ void __launch_bounds__(256) softmax_grad_kernel(T *__restrict__ ZT, long ldz, int Mp, int V, int Vp,
                                                            const float *__restrict__ lse,
@@ -176,32 +178,57 @@ __global__ void __launch_bounds__(256) softmax_grad_kernel(T *__restrict__ ZT, l
                                                            const float *__restrict__ b, float *__restrict__ b_out,
                                                            float alpha, float lr) {
   constexpr int VEC = Elem<T>::VEC;
+  constexpr int R = 4;  // rows per wave
   const int lane = threadIdx.x & 63;
-  const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (v >= Vp) return;
-  T *row = ZT + (long)v * ldz;
-  float db = 0.0f;
+  const int v0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * R;
+  if (v0 >= Vp) return;
+  T *row = ZT + (long)v0 * ldz;
+  float db[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) db[r] = 0.0f;
   for (int c = lane * VEC; c < Mp; c += 64 * VEC) {
-    T vals[VEC];
-    *reinterpret_cast<uint4 *>(vals) = *reinterpret_cast<const uint4 *>(row + c);
-    if (v < V) {
+    u32x4_t raw[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) raw[r] = *reinterpret_cast<const u32x4_t *>(row + (long)r * ldz + c);
+    float l[VEC];
+    int y[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; e += 4) {
+      const f32x4_t lv = *reinterpret_cast<const f32x4_t *>(lse + c + e);
+      const u32x4_t yv = *reinterpret_cast<const u32x4_t *>(yp + c + e);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        l[e + q] = lv[q];
+        y[e + q] = (int)yv[q];
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      union {
+        u32x4_t u;
+        T t[VEC];
+      } in, o;
+      in.u = raw[r];
+      const int v = v0 + r;
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
-        float p = __expf(to_f32(vals[e]) - lse[c + e]);
-        if (yp[c + e] == v) p -= 1.0f;
-        p *= invM;
-        db += p;
-        vals[e] = from_f32<T>(p);
+        float p = __expf(to_f32(in.t[e]) - l[e]);
+        if (y[e] == v) p -= 1.0f;
+        p = (v < V) ? p * invM : 0.0f;
+        db[r] += p;
+        o.t[e] = from_f32<T>(p);
       }
-    } else {
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) vals[e] = from_f32<T>(0.0f);
+      *reinterpret_cast<u32x4_t *>(row + (long)r * ldz + c) = o.u;
     }
-    *reinterpret_cast<uint4 *>(row + c) = *reinterpret_cast<const uint4 *>(vals);
   }
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) db += __shfl_xor(db, o, 64);
-  if (lane == 0 && v < V) b_out[v] = ((alpha != 0.0f) ? alpha * b[v] : 0.0f) - lr * db;
+  for (int r = 0; r < R; ++r) {
+    float d = db[r];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) d += __shfl_xor(d, o, 64);
+    const int v = v0 + r;
+    if (lane == 0 && v < V) b_out[v] = ((alpha != 0.0f) ? alpha * b[v] : 0.0f) - lr * d;
+  }
 }
 
 // ---- a6: fixed-order reduction of the split-K partial sums -------------------------------------
@@ -297,37 +324,74 @@ __global__ void segment_kernel(const int32_t *__restrict__ xp, const int32_t *__
 
 // ---- a10: segmented embedding update, atomic-free and order-fixed -------------------------------
 //   out[w][:] = alpha*E[w][:] - lr * sum_{m in run of w} dA[m][:]
-// blockIdx.x = run index (exits when >= *nseg), blockIdx.y = block of 64 columns.  The run's members
-// are dealt round-robin to 8 partial sums (each accumulated in ascending m), which are then added in
-// order 0..7: a fixed summation tree, so results are bitwise reproducible.
-__global__ void __launch_bounds__(512) scatter_update_kernel(const float *__restrict__ dA, int Hp, int H, int B,
-                                                             int Bp, const int32_t *__restrict__ xp,
-                                                             const int32_t *__restrict__ perm,
-                                                             const int32_t *__restrict__ seg_start,
-                                                             const int32_t *__restrict__ nseg,
-                                                             const float *__restrict__ E, float *__restrict__ out,
-                                                             float alpha, float lr) {
-  __shared__ float sh[8][64];
+// blockIdx.x = run index (exits when >= *nseg), blockIdx.y = block of COLS columns.  The run's members
+// are dealt round-robin to PARTS partial sums (each accumulated in ascending m, position indices
+// fetched four at a time so the row loads are independent), which are then added in order
+// 0..PARTS-1: a fixed summation tree, so results are bitwise reproducible.
+// VEC = 4: a lane owns 4 consecutive columns (H % 4 == 0); VEC = 1: any H.
+template <int VEC>
+__global__ void __launch_bounds__(1024) scatter_update_kernel(const float *__restrict__ dA, int Hp, int H, int B,
+                                                              int Bp, const int32_t *__restrict__ xp,
+                                                              const int32_t *__restrict__ perm,
+                                                              const int32_t *__restrict__ seg_start,
+                                                              const int32_t *__restrict__ nseg,
+                                                              const float *__restrict__ E, float *__restrict__ out,
+                                                              float alpha, float lr) {
+  constexpr int PARTS = 4, LANES = 256;
+  __shared__ float sh[PARTS][LANES * VEC];
   const int g = blockIdx.x;
   if (g >= *nseg) return;
-  const int lane = threadIdx.x & 63, partn = threadIdx.x >> 6;
-  const int col = blockIdx.y * 64 + lane;
+  const int lane = threadIdx.x % LANES, partn = threadIdx.x / LANES;
+  const int col = (blockIdx.y * LANES + lane) * VEC;
   const int r0 = seg_start[g], r1 = seg_start[g + 1];
-  float acc = 0.0f;
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
   if (col < H) {
-    for (int r = r0 + partn; r < r1; r += 8) {
+    int r = r0 + partn;
+    for (; r + 3 * PARTS < r1; r += 4 * PARTS) {
+      long row[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int m = perm[r + q * PARTS];
+        row[q] = ((long)(m / B) * Bp + (m % B)) * Hp + col;
+      }
+      float v[4][VEC];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (VEC == 4) {
+          const f32x4_t t = *reinterpret_cast<const f32x4_t *>(dA + row[q]);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) v[q][e] = t[e];
+        } else {
+          v[q][0] = dA[row[q]];
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += v[q][e];
+    }
+    for (; r < r1; r += PARTS) {
       const int m = perm[r];
-      acc += dA[((long)(m / B) * Bp + (m % B)) * Hp + col];
+      const long rowi = ((long)(m / B) * Bp + (m % B)) * Hp + col;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += dA[rowi + e];
     }
   }
-  sh[partn][lane] = acc;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) sh[partn][lane * VEC + e] = acc[e];
   __syncthreads();
   if (partn != 0 || col >= H) return;
-  for (int q = 1; q < 8; ++q) acc += sh[q][lane];
+#pragma unroll
+  for (int q = 1; q < PARTS; ++q)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] += sh[q][lane * VEC + e];
   const int m0 = perm[r0];
   const int w = xp[(m0 / B) * Bp + (m0 % B)];
   const long idx = (long)w * H + col;
-  out[idx] = ((alpha != 0.0f) ? alpha * E[idx] : 0.0f) - lr * acc;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) out[idx + e] = ((alpha != 0.0f) ? alpha * E[idx + e] : 0.0f) - lr * acc[e];
 }
 
 }  // namespace rnnlm_dev

@@ -357,7 +357,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
   // fused softmax gradient + bias update, in place on the vocabulary-major logits
   {
     StageTimer tm(h, RNNLM_STAGE_SOFTMAX_GRAD, st);
-    hipLaunchKernelGGL(softmax_grad_kernel<T>, dim3(Vp / 4), dim3(256), 0, st, ZT, ldz, Mp, c.V, Vp,
+    hipLaunchKernelGGL(softmax_grad_kernel<T>, dim3(Vp / 16), dim3(256), 0, st, ZT, ldz, Mp, c.V, Vp,
                        at<float>(h, h->L.lse), yp, 1.0f / (float)(Tn * c.B), h->buf.b, u.b, u.alpha, u.lr);
     HIP_TRY(hipGetLastError());
   }
@@ -440,7 +440,11 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
     epi.C = c.H;
     epi.alpha = u.alpha;
     epi.lr = u.lr;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
+    if (sizeof(T) == 2 && (long)(Hp / BIG) * (Hp / BIG) >= 64) {
+      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
+    } else {
+      HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
+    }
     if (u.refresh_copies) {
       hipLaunchKernelGGL(transpose_kernel<T>, dim3(Hp / 32, Hp / 32), dim3(256), 0, st, U_c, Hp,
                          at<T>(h, h->L.UT_c));
@@ -449,8 +453,13 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
   }
   // E[w] -= lr * sum_{m: x[m] = w} dA[m]
   StageTimer tm(h, RNNLM_STAGE_EMB, st);
-  hipLaunchKernelGGL(scatter_update_kernel, dim3(Tn * c.B, (c.H + 63) / 64), dim3(512), 0, st, dA32, Hp, c.H, c.B, Bp,
-                     xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr);
+  if (c.H % 4 == 0) {
+    hipLaunchKernelGGL(scatter_update_kernel<4>, dim3(Tn * c.B, (c.H + 1023) / 1024), dim3(1024), 0, st, dA32, Hp, c.H,
+                       c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr);
+  } else {
+    hipLaunchKernelGGL(scatter_update_kernel<1>, dim3(Tn * c.B, (c.H + 255) / 256), dim3(1024), 0, st, dA32, Hp, c.H,
+                       c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr);
+  }
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }
@@ -564,6 +573,9 @@ int rnnlm_train_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T,
 int rnnlm_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *dE, float *dU, float *dWo,
                      float *db, float *logp, void *stream) {
   if (!window_args_ok(h, x, y, T) || !dE || !dU || !dWo || !db) return RNNLM_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(dE) | reinterpret_cast<uintptr_t>(dU) | reinterpret_cast<uintptr_t>(dWo) |
+       reinterpret_cast<uintptr_t>(db)) & 15)
+    return RNNLM_ERR_ARG;  // the update epilogues use 16-byte accesses
   hipStream_t st = (hipStream_t)stream;
   const long nE = (long)h->cfg.V * h->cfg.H;
   hipLaunchKernelGGL(fill_kernel<float>, dim3(std::min<long>(blocks_for(nE, 256), 65535)), dim3(256), 0, st, dE, nE,
