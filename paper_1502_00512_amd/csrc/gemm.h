@@ -436,16 +436,19 @@ template <typename T>
 struct EpiOutFwd {
   const float *b;   // [V]
   T *ZT;            // [Vp][ldz]
-  float2 *part;     // [Vp / (32*TM)][ldz]
+  float2 *part;     // [Vp / BM][ldz]: one (max, sum exp) per tile row block and position
   const int *yp;    // [Mp] target id per position, -1 on padding
   float *zy;        // [Mp] target logit
   int V;
   long ldz;
   template <int BM, int BN>
-  static constexpr int lds_bytes() { return stage_lds_bytes<T, BM, BN>(); }
+  static constexpr int lds_bytes() {
+    return stage_lds_bytes<T, BM, BN>() > 8 * BN * 8 ? stage_lds_bytes<T, BM, BN>() : 8 * BN * 8;
+  }
   template <int BM, int BN, int TM, int TN, int NT>
   __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
     const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
+    float2 *red = reinterpret_cast<float2 *>(c.smem_lo);  // [waves along rows][BN] statistics exchange
     // bias: a lane needs b[v .. v+3] for 4*TM aligned groups of rows
     float bias[TM][4][4];
 #pragma unroll
@@ -489,8 +492,25 @@ struct EpiOutFwd {
       float tot = 0.0f;
       if (sum > 0.0f) tot += sum * __expf(mx - nmx);
       if (osum > 0.0f) tot += osum * __expf(omx - nmx);
-      if (lane < 32) part[(long)(row0 / (32 * TM)) * ldz + m] = make_float2(nmx, tot);
+      if (lane < 32) red[(c.wrow / (32 * TM)) * BN + c.wcol + j * 32 + lane] = make_float2(nmx, tot);
     }
+    // merge the statistics of the waves stacked along the vocabulary rows of this tile, in fixed order
+    __syncthreads();
+    constexpr int WGM = BM / (32 * TM);
+    if (c.tid < BN) {
+      float2 a = red[c.tid];
+#pragma unroll
+      for (int w = 1; w < WGM; ++w) {
+        const float2 q = red[w * BN + c.tid];
+        const float nm = fmaxf(a.x, q.x);
+        float t = 0.0f;
+        if (a.y > 0.0f) t += a.y * __expf(a.x - nm);
+        if (q.y > 0.0f) t += q.y * __expf(q.x - nm);
+        a = make_float2(nm, t);
+      }
+      part[(long)(c.tile_row0 / BM) * ldz + c.tile_col0 + c.tid] = a;
+    }
+    __syncthreads();
     store_tile<BM, BN, TM, TN, NT>(acc, c, ZT, ldz);
   }
 };

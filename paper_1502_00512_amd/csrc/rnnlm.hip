@@ -95,13 +95,6 @@ namespace {
 // Tile shape of the three output-layer contractions and of the recurrent weight gradient: 256x256
 // output tile, 8 waves as 2 x 4 (wave tile 128 x 64).
 constexpr int BIG = 256;
-// rows of the output-forward wave tile (one softmax-statistics partial each): the bf16 path runs that
-// contraction with 4 x 2 waves (64-row wave tiles), the fp32 path with 2 x 4 (128-row wave tiles)
-template <typename T>
-constexpr int out_wtm() {
-  return sizeof(T) == 2 ? 64 : 128;
-}
-
 // The large contractions: bf16 operands take the direct global->LDS kernel, fp32 the register-staged one.
 template <typename T, int WGM, int WGN, int LA, int LB, class Epi>
 hipError_t big_gemm(hipStream_t st, const void *A, long lda, const void *B, long ldb, long Mg, long Ng, long K,
@@ -139,7 +132,7 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
   Vp = (int)round_up(c.V, PAD_V);
   Bp = (int)round_up(c.B, PAD_B);
   MpMax = (int)round_up((long)c.T_max * Bp, PAD_M);
-  nPart = Vp / 64;  // capacity for the finer of the two wave tilings
+  nPart = Vp / BIG;  // one softmax-statistics partial per tile row block
   const int BK = (es == 4) ? 32 : 64;
   const int S = desired_splits(MpMax, Hp, Vp / BK);
   L.partElems = (long)S * MpMax * Hp;
@@ -312,7 +305,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
   }
   StageTimer tm(h, RNNLM_STAGE_STATS, st);
   hipLaunchKernelGGL(merge_stats_kernel, dim3(blocks_for(Mrows, 64)), dim3(1024), 0, st, at<float2>(h, h->L.stat),
-                     Vp / out_wtm<T>(), ldz, Tn, c.B, Bp, zy, lse, at<float>(h, h->L.logp_int), logp_out);
+                     Vp / BIG, ldz, Tn, c.B, Bp, zy, lse, at<float>(h, h->L.logp_int), logp_out);
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }
