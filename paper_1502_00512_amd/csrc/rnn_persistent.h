@@ -23,7 +23,8 @@ struct RnnPersistArgs {
   float *dA32;        // backward: [T][Bp][Hp]
   void *dAc;          // backward: [T][Bp][Hp] compute type
   float *h_state;     // forward: [B][H] or nullptr
-  unsigned *counter;  // grid barrier counter (zero at launch)
+  unsigned *counter;  // barrier counters, zero at launch: [0] whole grid; [1 + x] the group on XCD x;
+                      // [9 + x] ticket dispenser of XCD x
   int32_t *flags;     // flags[2] raised when a barrier wait expires
   int T, B, H, Bp, Hp;
   unsigned spin_limit;
@@ -35,6 +36,36 @@ struct RnnPersistArgs {
 // bulk L2 write-back / invalidate operations at every barrier; ordering comes from waiting for the
 // stores (workgroup-scope fence) before the barrier's arrival atomic, and from the poll loop's
 // control dependency before the loads.
+// XCD-local mode.  The workgroups that exchange state with one another are exactly those of one block
+// of 32 streams.  When such a group runs on ONE accelerator die (XCD) they share its L2, and the step
+// barrier and the state exchange need nothing beyond that L2: plain stores (the vector L1 is
+// write-through), a counter updated by L2 atomics, and plain loads (a step reads only addresses that no
+// wave of its CU has touched since the kernel started, so the L1 cannot hold a stale copy).  Placement
+// does not rely on the dispatch order: every workgroup reads the id of the XCD it runs on, groups are
+// bound to XCDs (stream block x <-> XCD x), and a per-XCD ticket counter hands out the unit blocks;
+// surplus workgroups and those on XCDs without a group exit at once.  The host enables this mode only
+// after a probe launch has shown that an 8*n grid lands n workgroups on each XCD.
+__device__ inline int xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15; }  // HW_REG_XCC_ID[3:0]
+
+__device__ inline void xcd_barrier(unsigned *counter, unsigned target, unsigned spin_limit, int32_t *flags) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have reached the L2
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned spins = 0;
+    // read-modify-write atomics execute in the L2: an OR with 0 is a coherent read of the counter
+    while (__hip_atomic_fetch_or(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      __builtin_amdgcn_s_sleep(1);
+      if (++spins >= spin_limit) {
+        flags[2] = 1;
+        break;
+      }
+    }
+  }
+  __syncthreads();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 __device__ inline void grid_barrier(unsigned *counter, unsigned target, unsigned spin_limit, int32_t *flags) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have completed
   __syncthreads();
@@ -101,7 +132,15 @@ __device__ inline F32x8 load_frag_global<float, true>(const float *p) {
   return u.f;
 }
 
-// 4 consecutive values (fp32 in registers) to / from the compute type; COHERENT = agent-scope accesses.
+// 4 consecutive values (fp32 in registers) to / from the compute type; store4 uses agent-scope accesses,
+// store4_plain ordinary ones.
+__device__ inline void store4_plain(float *p, const f32x4_t &v) { *reinterpret_cast<f32x4_t *>(p) = v; }
+__device__ inline void store4_plain(bf16_t *p, const f32x4_t &v) {
+  bf16x4_t h;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) h[e] = (bf16_t)v[e];
+  *reinterpret_cast<bf16x4_t *>(p) = h;
+}
 template <typename T>
 __device__ inline void store4(T *p, const f32x4_t &v);
 template <>
@@ -141,12 +180,33 @@ __device__ inline f32x4_t load4<bf16_t>(const bf16_t *p) {
 
 // KS = 16-wide contraction steps per wave = Hp / (16 NWAVE).  BACKWARD = false: h_t = sigmoid(X_t + h_{t-1} U^T)
 // for t = 0..T-1.  BACKWARD = true: dA_t = (dHs_t + dA_{t+1} U) * h_t * (1 - h_t) for t = T-1..0.
-template <typename T, int KS, int NWAVE, bool BACKWARD>
+// XCD = true: XCD-local mode (see above); false: the grid spans the chip and uses agent-scope accesses.
+template <typename T, int KS, int NWAVE, bool BACKWARD, bool XCD>
 __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPersistArgs a) {
   __shared__ __attribute__((aligned(16))) float red[NWAVE][16][64];
+  __shared__ int s_ticket;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nsb = a.Bp / 32;
-  const int sb = blockIdx.x % nsb, ub = blockIdx.x / nsb;
+  int sb, ub;
+  unsigned nwg;
+  unsigned *counter;
+  if (XCD) {
+    const int x = xcc_id();
+    if (x >= nsb) return;  // no group lives on this XCD
+    if (threadIdx.x == 0)
+      s_ticket = (int)__hip_atomic_fetch_add(a.counter + 9 + x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    sb = x;
+    ub = s_ticket;
+    nwg = (unsigned)(a.Hp / 32);
+    if (ub >= (int)nwg) return;  // surplus workgroup
+    counter = a.counter + 1 + x;
+  } else {
+    sb = blockIdx.x % nsb;
+    ub = blockIdx.x / nsb;
+    nwg = gridDim.x;
+    counter = a.counter;
+  }
   const int Hp = a.Hp, Bp = a.Bp;
   const long slot = (long)Bp * Hp;
   const int kq = wave * (KS * 16);  // first contraction index of this wave
@@ -168,7 +228,6 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
   const bool row_ok = epi_thread && erow < a.B;
   T *Hs = static_cast<T *>(a.Hs);
   T *dAc = static_cast<T *>(a.dAc);
-  const unsigned nwg = gridDim.x;
 
   for (int step = 0; step < a.T; ++step) {
     const int t = BACKWARD ? a.T - 1 - step : step;
@@ -189,7 +248,7 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
       const T *Ap = src + (long)(sb * 32 + lr) * Hp + kq + lk;
       typename FragT<T>::type f[KS];
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) f[kk] = load_frag_global<T, true>(Ap + kk * 16);
+      for (int kk = 0; kk < KS; ++kk) f[kk] = load_frag_global<T, !XCD>(Ap + kk * 16);
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) mma16(acc, f[kk], w[kk]);
     }
@@ -216,7 +275,7 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
     if (!epi_thread) {
       // waves 4..7 only contribute partial sums
     } else if (!BACKWARD) {
-      store4<T>(Hs + slot + eidx, o);
+      if (XCD) store4_plain(Hs + slot + eidx, o); else store4<T>(Hs + slot + eidx, o);
       if (a.h_state && step == a.T - 1 && row_ok) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
@@ -224,10 +283,18 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
       }
     } else {
       *reinterpret_cast<f32x4_t *>(a.dA32 + eidx) = o;
-      store4<T>(dAc + eidx, o);
+      if (XCD) store4_plain(dAc + eidx, o); else store4<T>(dAc + eidx, o);
     }
-    if (step + 1 < a.T) grid_barrier(a.counter, (unsigned)(step + 1) * nwg, a.spin_limit, a.flags);
+    if (step + 1 < a.T) {
+      if (XCD) xcd_barrier(counter, (unsigned)(step + 1) * nwg, a.spin_limit, a.flags);
+      else grid_barrier(counter, (unsigned)(step + 1) * nwg, a.spin_limit, a.flags);
+    }
   }
+}
+
+// Records which XCD each workgroup of the launch runs on.
+__global__ void xcd_probe_kernel(int32_t *out) {
+  if (threadIdx.x == 0) out[blockIdx.x] = xcc_id();
 }
 
 }  // namespace rnnlm_dev

@@ -41,6 +41,7 @@ struct rnnlm {
   WsLayout L;
   char *ws;
   // stage timing (host-side only)
+  bool xcd_local = false;        // the probe at init saw round-robin placement over 8 XCDs
   unsigned spin_limit = 1u << 18;  // polls of a grid barrier before giving up (about a second)
   uint32_t prof_mask = 0;
   std::vector<EventPair> prof_pool;
@@ -162,7 +163,7 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
   L.seg = take((size_t)(MpMax + 1) * 4);
   L.xtmp = take((size_t)c.T_max * c.B * 4);
   L.ytmp = take((size_t)c.T_max * c.B * 4);
-  L.scalars = take(256);  // [0]: int nseg, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64]: barrier counter
+  L.scalars = take(256);  // [0]: int nseg, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64..131]: 17 barrier/ticket counters
   L.total = o;
 }
 
@@ -220,10 +221,15 @@ int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st
   a.Bp = h->Bp;
   a.Hp = h->Hp;
   a.spin_limit = h->spin_limit;
-  hipLaunchKernelGGL(fill_kernel<uint32_t>, dim3(1), dim3(64), 0, st, p_counter(h), 1L, 0u);
-  const dim3 grid((unsigned)((h->Bp / 32) * (h->Hp / 32)));
-#define RNNLM_LAUNCH_PERSIST(KS, NW) \
-  hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD>), grid, dim3(64 * NW), 0, st, a)
+  hipLaunchKernelGGL(fill_kernel<uint32_t>, dim3(1), dim3(64), 0, st, p_counter(h), 17L, 0u);
+  // XCD-local mode: one group of Hp/32 workgroups per block of 32 streams, group x on XCD x
+  const bool xcd = h->xcd_local && h->Bp / 32 <= NUM_XCD;
+  const dim3 grid(xcd ? (unsigned)(NUM_XCD * (h->Hp / 32)) : (unsigned)((h->Bp / 32) * (h->Hp / 32)));
+#define RNNLM_LAUNCH_PERSIST(KS, NW)                                                                        \
+  do {                                                                                                      \
+    if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true>), grid, dim3(64 * NW), 0, st, a); \
+    else hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, false>), grid, dim3(64 * NW), 0, st, a);    \
+  } while (0)
   switch (h->Hp / 256) {
     case 1: RNNLM_LAUNCH_PERSIST(4, 4); break;
     case 2: RNNLM_LAUNCH_PERSIST(8, 4); break;
@@ -519,6 +525,21 @@ int rnnlm_init(const rnnlm_config *cfg, const rnnlm_buffers *buf, rnnlm_t **out)
   if (rc == RNNLM_OK)
     rc = (cfg->precision == RNNLM_FP32) ? sync_copies<float>(h, nullptr) : sync_copies<bf16_t>(h, nullptr);
   if (rc == RNNLM_OK && hipDeviceSynchronize() != hipSuccess) rc = RNNLM_ERR_HIP;
+  if (rc == RNNLM_OK) {
+    // where do the workgroups of a grid land?  (uses the start of the not-yet-used logits buffer)
+    constexpr int N = 64 * NUM_XCD;
+    int32_t *dev = at<int32_t>(h, h->L.X32);
+    int32_t host[N];
+    hipLaunchKernelGGL(xcd_probe_kernel, dim3(N), dim3(64), 0, nullptr, dev);
+    if (hipMemcpy(host, dev, sizeof(host), hipMemcpyDeviceToHost) != hipSuccess ||
+        hipMemsetAsync(dev, 0, sizeof(host), nullptr) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+      rc = RNNLM_ERR_HIP;
+    } else {
+      bool rr = true;
+      for (int i = 0; i < N; ++i) rr = rr && host[i] == i % NUM_XCD;
+      h->xcd_local = rr;
+    }
+  }
   if (rc != RNNLM_OK) {
     delete h;
     return rc;

@@ -57,6 +57,7 @@ SHAPES_FP32 = [
     (520, 96, 70, 2),
     (500, 200, 800, 2),   # too many streams for the persistent recurrent kernel: per-step launches
     (400, 1100, 6, 3),    # H > 1024 in fp32: per-step launches
+    (300, 100, 300, 3),   # more than 8 blocks of 32 streams: chip-wide (agent-scope) persistent kernel
 ]
 
 
