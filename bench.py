@@ -124,6 +124,9 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    # what the box sustains (for context next to the published peaks)
+    measured = g.rnnlm_measure_peaks(stream)
+
     words_per_s = args.steps * M / dt
     flops_word = 6.0 * H * (V + H)
     peak = PEAK_BF16_TFLOPS if cfg.precision == "bf16" else PEAK_FP32_TFLOPS
@@ -159,6 +162,7 @@ def main() -> int:
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                      "traffic": measured_traffic(cfg.name, dominant)},
         "cpu_baseline": cpu,
+        "measured_peaks": {k: round(v, 1) for k, v in measured.items()},
     }
     if stage_ms is not None:
         res["stage_ms"] = stage_ms

@@ -146,6 +146,14 @@ int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, 
  * (default 2^18, about a second).  For tests of that error path: polls = 1 makes waits expire at once. */
 int rnnlm_set_barrier_spin_limit(rnnlm_t *h, uint32_t polls);
 
+/* Measures what this machine sustains, for reports next to the published peaks (HOST outputs): a register-
+ * resident bf16 MFMA loop with hash-random operands and with constant operands (TFLOP/s; the two differ
+ * because power management lowers the clock when operand bits toggle), and a plain device copy inside
+ * the workspace (GB/s, read + write).  Uses the logits area of the workspace as scratch; waits for
+ * the stream.  Outputs are 0 when the workspace is too small for a test. */
+int rnnlm_measure_peaks(rnnlm_t *h, double *mfma_bf16_random_tflops, double *mfma_bf16_constant_tflops,
+                        double *copy_gbs, void *stream);
+
 /* Stage timing with HIP events on the call's stream (for benchmarks; off by default).  Stages of a
  * window, in the order of the kernel sequence: */
 typedef enum {

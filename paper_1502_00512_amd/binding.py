@@ -20,7 +20,7 @@ SYMBOLS = [
     "rnnlm_workspace_bytes", "rnnlm_init", "rnnlm_free", "rnnlm_stream_chunk", "rnnlm_forward_logprob",
     "rnnlm_train_chunk", "rnnlm_grad_chunk", "rnnlm_perplexity", "rnnlm_reset_state",
     "rnnlm_sync_compute_copies", "rnnlm_check", "rnnlm_sort_segments", "rnnlm_status_string",
-    "rnnlm_profile_enable", "rnnlm_profile_read", "rnnlm_set_barrier_spin_limit",
+    "rnnlm_profile_enable", "rnnlm_profile_read", "rnnlm_set_barrier_spin_limit", "rnnlm_measure_peaks",
 ]
 
 STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce"]
@@ -69,6 +69,7 @@ def load():
     lib.rnnlm_check.argtypes = [vp, vp]
     lib.rnnlm_sort_segments.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     lib.rnnlm_set_barrier_spin_limit.argtypes = [vp, C.c_uint32]
+    lib.rnnlm_measure_peaks.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     lib.rnnlm_profile_enable.argtypes = [vp, C.c_uint32]
     lib.rnnlm_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.rnnlm_status_string.argtypes = [C.c_int]
@@ -191,6 +192,12 @@ class Rnnlm:
 
     def rnnlm_set_barrier_spin_limit(self, polls: int):
         _ok(self.lib.rnnlm_set_barrier_spin_limit(self.handle, polls), "rnnlm_set_barrier_spin_limit")
+
+    def rnnlm_measure_peaks(self, stream=None):
+        r, c, g = C.c_double(0), C.c_double(0), C.c_double(0)
+        _ok(self.lib.rnnlm_measure_peaks(self.handle, C.byref(r), C.byref(c), C.byref(g), _stream(stream)),
+            "rnnlm_measure_peaks")
+        return dict(mfma_bf16_random_tflops=r.value, mfma_bf16_constant_tflops=c.value, copy_gbs=g.value)
 
     def rnnlm_profile_enable(self, stage_mask: int):
         _ok(self.lib.rnnlm_profile_enable(self.handle, stage_mask), "rnnlm_profile_enable")

@@ -394,4 +394,60 @@ __global__ void __launch_bounds__(1024) scatter_update_kernel(const float *__res
   for (int e = 0; e < VEC; ++e) out[idx + e] = ((alpha != 0.0f) ? alpha * E[idx + e] : 0.0f) - lr * acc[e];
 }
 
+// ---- measured peaks of the box (reported next to the published ones) -----------------------------
+// Register-resident MFMA loop: 8 independent 32x32x16 bf16 accumulations per iteration and wave, operands
+// rotated every iteration.  RANDOM = operand bits drawn from a hash (the sustained rate with realistic
+// data: power management lowers the clock when operands toggle); otherwise constant operands.
+template <bool RANDOM>
+__global__ void __launch_bounds__(512) mfma_rate_kernel(float *out, int iters) {
+  auto hashu = [](unsigned x) {
+    x ^= x >> 16;
+    x *= 0x7feb352dU;
+    x ^= x >> 15;
+    x *= 0x846ca68bU;
+    x ^= x >> 16;
+    return x;
+  };
+  bf16x8_t a[4], b[2];
+  for (int q = 0; q < 4; ++q)
+    for (int e = 0; e < 8; ++e) {
+      const unsigned hsh = hashu(threadIdx.x * 131 + q * 17 + e + blockIdx.x * 7919);
+      a[q][e] = RANDOM ? (bf16_t)(((int)(hsh & 0xffff) - 32768) / 65536.0f) : (bf16_t)0.5f;
+    }
+  for (int q = 0; q < 2; ++q)
+    for (int e = 0; e < 8; ++e) {
+      const unsigned hsh = hashu(threadIdx.x * 733 + q * 29 + e + 1234567);
+      b[q][e] = RANDOM ? (bf16_t)(((int)(hsh & 0xffff) - 32768) / 65536.0f) : (bf16_t)0.25f;
+    }
+  f32x16_t acc[8];
+  for (int i = 0; i < 8; ++i)
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i * 2 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i * 2 + j], 0, 0, 0);
+    bf16x8_t t = a[0];
+    a[0] = a[1];
+    a[1] = a[2];
+    a[2] = a[3];
+    a[3] = t;
+    t = b[0];
+    b[0] = b[1];
+    b[1] = t;
+  }
+  float sum = 0;
+  for (int i = 0; i < 8; ++i)
+    for (int r = 0; r < 16; ++r) sum += acc[i][r];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
+}
+
+// Plain device copy, 16 bytes per lane, grid-stride.
+__global__ void __launch_bounds__(256) copy_kernel(const u32x4_t *__restrict__ src, u32x4_t *__restrict__ dst, long n16) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long stride = (long)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace rnnlm_dev

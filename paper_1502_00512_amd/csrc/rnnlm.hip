@@ -679,6 +679,53 @@ int rnnlm_set_barrier_spin_limit(rnnlm_t *h, uint32_t polls) {
   return RNNLM_OK;
 }
 
+int rnnlm_measure_peaks(rnnlm_t *h, double *mfma_bf16_random_tflops, double *mfma_bf16_constant_tflops,
+                        double *copy_gbs, void *stream) {
+  if (!h || !mfma_bf16_random_tflops || !mfma_bf16_constant_tflops || !copy_gbs) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  hipEvent_t e0, e1;
+  HIP_TRY(hipEventCreate(&e0));
+  HIP_TRY(hipEventCreate(&e1));
+  // scratch: the logits buffer (rewritten by the next window's forward pass before anything reads it)
+  const size_t es = (h->cfg.precision == RNNLM_FP32) ? 4 : 2;
+  char *scratch = h->ws + h->L.ZT;
+  const size_t avail = (size_t)h->Vp * h->MpMax * es;
+  int rc = RNNLM_OK;
+  auto timed = [&](auto launch, double &ms_out) {
+    launch();  // warm-up
+    if (hipEventRecord(e0, st) != hipSuccess) rc = RNNLM_ERR_HIP;
+    launch();
+    if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) rc = RNNLM_ERR_HIP;
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = RNNLM_ERR_HIP;
+    ms_out = ms;
+  };
+  const int iters = 50000;
+  const double mfma_flops = 256.0 * 8 * iters * 8 * 32.0 * 32 * 16 * 2;
+  double ms = 0.0;
+  *mfma_bf16_random_tflops = *mfma_bf16_constant_tflops = *copy_gbs = 0.0;
+  if (avail >= 256 * 512 * sizeof(float)) {
+    float *out = reinterpret_cast<float *>(scratch);
+    timed([&] { hipLaunchKernelGGL(mfma_rate_kernel<true>, dim3(256), dim3(512), 0, st, out, iters); }, ms);
+    if (rc == RNNLM_OK && ms > 0) *mfma_bf16_random_tflops = mfma_flops / ms / 1e9;
+    timed([&] { hipLaunchKernelGGL(mfma_rate_kernel<false>, dim3(256), dim3(512), 0, st, out, iters); }, ms);
+    if (rc == RNNLM_OK && ms > 0) *mfma_bf16_constant_tflops = mfma_flops / ms / 1e9;
+  }
+  const size_t half = (avail / 2) & ~(size_t)255;
+  if (half >= (8u << 20)) {
+    const long n16 = (long)(half / 16);
+    timed([&] {
+      hipLaunchKernelGGL(copy_kernel, dim3(256 * 32), dim3(256), 0, st, reinterpret_cast<const u32x4_t *>(scratch),
+                         reinterpret_cast<u32x4_t *>(scratch + half), n16);
+    }, ms);
+    if (rc == RNNLM_OK && ms > 0) *copy_gbs = 2.0 * half / ms / 1e6;  // read + write
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc == RNNLM_OK && hipGetLastError() != hipSuccess) rc = RNNLM_ERR_HIP;
+  return rc;
+}
+
 int rnnlm_profile_enable(rnnlm_t *h, uint32_t stage_mask) {
   if (!h || stage_mask >= (1u << RNNLM_STAGE_COUNT)) return RNNLM_ERR_ARG;
   h->prof_mask = stage_mask;

@@ -283,6 +283,24 @@ def test_grid_barrier_timeout_is_reported():
     g.rnnlm_check()
 
 
+def test_measure_peaks_is_sane_and_leaves_the_model_alone():
+    """The peak-measurement call borrows the logits area of the workspace: figures are positive and
+    below the published ceilings, and a window evaluated afterwards matches the one before bit for bit."""
+    g, _ = make_pair(3000, 512, 32, 8, BF16, seed=11)
+    tok = tokens(3000, 4000, 7)
+    x, y = O.stream_chunk(tok, 32, 8, 0)
+    before = g.rnnlm_forward_logprob(dev(x), dev(y)).clone()
+    peaks = g.rnnlm_measure_peaks()
+    assert 0 < peaks["mfma_bf16_random_tflops"] <= peaks["mfma_bf16_constant_tflops"] * 1.05
+    assert 100 < peaks["mfma_bf16_constant_tflops"] < 2600
+    # a workspace this small has no room for a meaningful copy: the call then reports 0
+    assert peaks["copy_gbs"] == 0.0 or 100 < peaks["copy_gbs"] < 8000
+    g.rnnlm_reset_state()
+    after = g.rnnlm_forward_logprob(dev(x), dev(y))
+    assert torch.equal(before, after)
+    g.rnnlm_check()
+
+
 # ---- full-size checks, in the launch configuration bench.py times -------------------------------------
 
 def _cfg_pair(name, T=None, weights="config"):
