@@ -26,6 +26,8 @@ def lib():
         _lib.oracle_grad_chunk.restype = C.c_int
         _lib.oracle_train_chunk.restype = C.c_int
         _lib.oracle_perplexity.restype = C.c_int
+        _lib.oracle_nce_grad_chunk.restype = C.c_int
+        _lib.oracle_nce_train_chunk.restype = C.c_int
         _lib.oracle_sort_segments.restype = C.c_int
         _lib.oracle_num_threads.restype = C.c_int
     return _lib
@@ -145,6 +147,48 @@ def train_chunk(m: Model, x, y, lr: float):
                                     _i(np.ascontiguousarray(x, np.int32)), _i(np.ascontiguousarray(y, np.int32)),
                                     C.c_double(lr), _d(logp), C.byref(s)))
     return logp, s.value
+
+
+def nce_grad_chunk(m: Model, x, y, noise, lnq, lnZ=0.0, debug=False):
+    """Gradients of the window's MEAN noise-contrastive loss (Sec. 4.2 criterion; K = len(noise) noise
+    words shared by the window, noise log-probabilities lnq[V], constant normaliser lnZ).
+
+    Returns dict(J[T][B], gE, gU, gWo, gb, h_next[, ct[T][B], dS[T][B][K], dHs, dA]); m is not modified.
+    """
+    T = x.shape[0]
+    V, H, B = m.V, m.H, m.B
+    noise = np.ascontiguousarray(noise, np.int32).reshape(-1)
+    K = noise.size
+    lnq = np.ascontiguousarray(lnq, np.float64)
+    assert lnq.shape == (V,)
+    r = dict(J=np.empty((T, B)), gE=np.empty((V, H)), gU=np.empty((H, H)), gWo=np.empty((V, H)),
+             gb=np.empty(V), h_next=np.empty((B, H)))
+    dbg = dict(ct=np.empty((T, B)), dS=np.empty((T, B, K)), dHs=np.empty((T, B, H)), dA=np.empty((T, B, H))) \
+        if debug else dict(ct=None, dS=None, dHs=None, dA=None)
+    _check(lib().oracle_nce_grad_chunk(V, H, B, T, _d(m.E), _d(m.U), _d(m.Wo), _d(m.b), _d(m.h),
+                                       _i(np.ascontiguousarray(x, np.int32)), _i(np.ascontiguousarray(y, np.int32)),
+                                       K, _i(noise), _d(lnq), C.c_double(lnZ), _d(r["J"]), _d(r["gE"]), _d(r["gU"]),
+                                       _d(r["gWo"]), _d(r["gb"]), _d(r["h_next"]), _d(dbg["ct"]), _d(dbg["dS"]),
+                                       _d(dbg["dHs"]), _d(dbg["dA"])))
+    if debug:
+        r.update(dbg)
+    return r
+
+
+def nce_train_chunk(m: Model, x, y, noise, lnq, lnZ, lr: float):
+    """One SGD step on one window under the noise-contrastive criterion, in place.
+    Returns (J[T][B], sum_J)."""
+    T = x.shape[0]
+    noise = np.ascontiguousarray(noise, np.int32).reshape(-1)
+    lnq = np.ascontiguousarray(lnq, np.float64)
+    assert lnq.shape == (m.V,)
+    J = np.empty((T, m.B), np.float64)
+    s = C.c_double(0.0)
+    _check(lib().oracle_nce_train_chunk(m.V, m.H, m.B, T, _d(m.E), _d(m.U), _d(m.Wo), _d(m.b), _d(m.h),
+                                        _i(np.ascontiguousarray(x, np.int32)), _i(np.ascontiguousarray(y, np.int32)),
+                                        noise.size, _i(noise), _d(lnq), C.c_double(lnZ), C.c_double(lr), _d(J),
+                                        C.byref(s)))
+    return J, s.value
 
 
 def perplexity(m: Model, tok: np.ndarray, T: int):

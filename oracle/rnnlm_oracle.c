@@ -18,7 +18,9 @@
  *     gradient of the mean negative log-likelihood of the B*T tokens of the window,
  *     back-propagated through time to the window start and no further, followed by
  *     one plain SGD step (Sec. 4.2 names stochastic gradient descent);
- *   - perplexity = exp(-mean log P) (Sec. 1 names it the primary metric).
+ *   - perplexity = exp(-mean log P) (Sec. 1 names it the primary metric);
+ *   - the same step with the noise-contrastive criterion Sec. 4.2 trains with (the
+ *     oracle_nce_* functions further down state the estimator and the readings taken).
  *
  * Layouts: row-major; E[V][H], U[H][H] (a_i = sum_j U[i][j] h_j), Wo[V][H], b[V],
  * h[B][H]; token windows are time-major x[T][B], y[T][B].
@@ -127,6 +129,58 @@ int oracle_forward_logprob(int V, int H, int B, int T, const double *E, const do
   return rc;
 }
 
+/* Truncated back-propagation through time over one window (the "minibatch" of Sec. 4.2), given
+ * dHs[T][B][H] = the derivative of the window loss with respect to each hidden state through the
+ * output layer alone.  Per stream, backwards in time:
+ *   dh_j = dHs_j + sum_i U[i][j] da_next_i ;  da = dh * h * (1-h)   (da_next = 0 at the last position)
+ * the carried state h0 is a constant, so the chain stops at the window start.  Fills dA[T][B][H]
+ * (= dLoss/da), gU[H][H] and gE[V][H]. */
+static void backprop_through_time(int V, int H, int B, int T, const double *U, const double *h0, const int32_t *x,
+                                  const double *Hs, const double *dHs, double *dA, double *gU, double *gE) {
+  const size_t M = (size_t)B * T;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int s = 0; s < B; ++s) {
+    for (int t = T - 1; t >= 0; --t) {
+      const size_t m = (size_t)t * B + s;
+      const double *dh = dHs + m * H;
+      double *da = dA + m * H;
+      const double *h = Hs + m * H;
+      if (t == T - 1) {
+        for (int j = 0; j < H; ++j) da[j] = dh[j] * h[j] * (1.0 - h[j]);
+      } else {
+        const double *dan = dA + ((size_t)(t + 1) * B + s) * H;
+        for (int j = 0; j < H; ++j) da[j] = dh[j];
+        for (int i = 0; i < H; ++i) {
+          const double *u = U + (size_t)i * H;
+          const double di = dan[i];
+          for (int j = 0; j < H; ++j) da[j] += u[j] * di;
+        }
+        for (int j = 0; j < H; ++j) da[j] *= h[j] * (1.0 - h[j]);
+      }
+    }
+  }
+  /* gU[i][j] = sum_{t,s} da[t][s][i] * hprev[t][s][j], hprev = h0 at t = 0 */
+#pragma omp parallel for schedule(static)
+  for (int i = 0; i < H; ++i) {
+    double *g = gU + (size_t)i * H;
+    for (int j = 0; j < H; ++j) g[j] = 0.0;
+    for (int t = 0; t < T; ++t)
+      for (int s = 0; s < B; ++s) {
+        const size_t m = (size_t)t * B + s;
+        const double *hp = (t > 0) ? Hs + ((size_t)(t - 1) * B + s) * H : h0 + (size_t)s * H;
+        const double di = dA[m * H + i];
+        for (int j = 0; j < H; ++j) g[j] += di * hp[j];
+      }
+  }
+  /* gE[w] = sum over window positions whose input id is w of da */
+  memset(gE, 0, sizeof(double) * (size_t)V * H);
+  for (size_t m = 0; m < M; ++m) {
+    double *g = gE + (size_t)x[m] * H;
+    const double *da = dA + m * H;
+    for (int j = 0; j < H; ++j) g[j] += da[j];
+  }
+}
+
 /* Gradient of the window's mean negative log-likelihood
  *   Loss = -(1/(B*T)) * sum_{t,s} log P(y[t][s] | ...)
  * with respect to E, U, Wo, b, all evaluated at the given parameters; the carried
@@ -174,56 +228,19 @@ int oracle_grad_chunk(int V, int H, int B, int T, const double *E, const double 
       }
       gb[v] = sb;
     }
-    /* per stream, backwards in time:
-     *   dh_j = sum_v Wo[v][j] dz_v + sum_i U[i][j] da_next_i ; da = dh * h * (1-h) */
-#pragma omp parallel for schedule(dynamic, 1)
-    for (int s = 0; s < B; ++s) {
-      for (int t = T - 1; t >= 0; --t) {
-        const size_t m = (size_t)t * B + s;
-        double *dh = dHs + m * H;
-        for (int j = 0; j < H; ++j) dh[j] = 0.0;
-        const double *d = dZ + m * V;
-        for (int v = 0; v < V; ++v) {
-          const double dv = d[v];
-          const double *w = Wo + (size_t)v * H;
-          for (int j = 0; j < H; ++j) dh[j] += w[j] * dv;
-        }
-        double *da = dA + m * H;
-        const double *h = Hs + m * H;
-        if (t == T - 1) {
-          for (int j = 0; j < H; ++j) da[j] = dh[j] * h[j] * (1.0 - h[j]);
-        } else {
-          const double *dan = dA + ((size_t)(t + 1) * B + s) * H;
-          for (int j = 0; j < H; ++j) da[j] = dh[j];
-          for (int i = 0; i < H; ++i) {
-            const double *u = U + (size_t)i * H;
-            const double di = dan[i];
-            for (int j = 0; j < H; ++j) da[j] += u[j] * di;
-          }
-          for (int j = 0; j < H; ++j) da[j] *= h[j] * (1.0 - h[j]);
-        }
+    /* dHs[m][j] = sum_v Wo[v][j] dz[m][v]: what the output layer sends back to each hidden state */
+#pragma omp parallel for schedule(static)
+    for (long m = 0; m < (long)M; ++m) {
+      double *dh = dHs + (size_t)m * H;
+      for (int j = 0; j < H; ++j) dh[j] = 0.0;
+      const double *d = dZ + (size_t)m * V;
+      for (int v = 0; v < V; ++v) {
+        const double dv = d[v];
+        const double *w = Wo + (size_t)v * H;
+        for (int j = 0; j < H; ++j) dh[j] += w[j] * dv;
       }
     }
-    /* gU[i][j] = sum_{t,s} da[t][s][i] * hprev[t][s][j], hprev = h0 at t = 0 */
-#pragma omp parallel for schedule(static)
-    for (int i = 0; i < H; ++i) {
-      double *g = gU + (size_t)i * H;
-      for (int j = 0; j < H; ++j) g[j] = 0.0;
-      for (int t = 0; t < T; ++t)
-        for (int s = 0; s < B; ++s) {
-          const size_t m = (size_t)t * B + s;
-          const double *hp = (t > 0) ? Hs + ((size_t)(t - 1) * B + s) * H : h0 + (size_t)s * H;
-          const double di = dA[m * H + i];
-          for (int j = 0; j < H; ++j) g[j] += di * hp[j];
-        }
-    }
-    /* gE[w] = sum over window positions whose input id is w of da */
-    memset(gE, 0, sizeof(double) * (size_t)V * H);
-    for (size_t m = 0; m < M; ++m) {
-      double *g = gE + (size_t)x[m] * H;
-      const double *da = dA + m * H;
-      for (int j = 0; j < H; ++j) g[j] += da[j];
-    }
+    backprop_through_time(V, H, B, T, U, h0, x, Hs, dHs, dA, gU, gE);
     if (h_out) memcpy(h_out, Hs + (size_t)(T - 1) * B * H, sizeof(double) * (size_t)B * H);
   }
   if (!Hs_out) free(Hs);
@@ -258,6 +275,142 @@ int oracle_train_chunk(int V, int H, int B, int T, double *E, double *U, double 
       double sacc = 0.0;
       for (size_t m = 0; m < (size_t)B * T; ++m) sacc += logp[m];
       *sum_logp = sacc;
+    }
+  }
+  free(gE); free(gWo); free(gU); free(gb); free(hn);
+  return rc;
+}
+
+/* ---- Noise-contrastive estimation (Sec. 4.2 names it as the training criterion) -------------------
+ *
+ * The paper gives no formula, noise distribution, sample count or normaliser; this follows the
+ * published estimator (Gutmann & Hyvarinen; for language models Mnih & Teh) under these readings:
+ *   - the unnormalised score of word w at window position m is z_m(w) = Wo[w].h_m + b[w], read as
+ *     log P up to the constant lnZ (a parameter; 0 = self-normalised);
+ *   - K noise words n_0..n_{K-1}, drawn by the caller from a noise distribution q (log-probabilities
+ *     lnq[V]) and SHARED by all B*T positions of the window;
+ *   - with D_m(w) = z_m(w) - lnZ - ln(K q(w)) and sigma the logistic function, position m costs
+ *       J_m = -ln sigma(D_m(y_m)) - sum_j ln(1 - sigma(D_m(n_j)))
+ *     (each noise word is its own term, also when it repeats or equals the target);
+ *   - window loss = mean of J_m over the B*T positions; its gradient is back-propagated through time
+ *     exactly as for the normalised criterion.
+ * ln sigma(d) = -softplus(-d), ln(1 - sigma(d)) = -softplus(d), softplus(d) = ln(1 + e^d). */
+static double softplus(double d) { return d > 0.0 ? d + log1p(exp(-d)) : log1p(exp(d)); }
+static double logistic(double d) { return d >= 0.0 ? 1.0 / (1.0 + exp(-d)) : exp(d) / (1.0 + exp(d)); }
+
+/* The recurrence alone: Hs[T][B][H] from state h0 (a_t = E[w_t] + U h_{t-1}, h_t = sigmoid(a_t)). */
+static void hidden_forward(int H, int B, int T, const double *E, const double *U, const double *h0,
+                           const int32_t *x, double *Hs) {
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int s = 0; s < B; ++s) {
+    const double *hprev = h0 + (size_t)s * H;
+    for (int t = 0; t < T; ++t) {
+      const size_t m = (size_t)t * B + s;
+      const double *e = E + (size_t)x[m] * H;
+      double *h = Hs + m * H;
+      for (int i = 0; i < H; ++i) {
+        const double *u = U + (size_t)i * H;
+        double a = 0.0;
+#pragma omp simd reduction(+ : a)
+        for (int j = 0; j < H; ++j) a += u[j] * hprev[j];
+        a += e[i];
+        h[i] = 1.0 / (1.0 + exp(-a));
+      }
+      hprev = h;
+    }
+  }
+}
+
+/* Gradient of the window's mean NCE loss with respect to E, U, Wo, b at the given parameters.
+ * noise[K] ids in [0,V); lnq[V]; J[T][B] receives the per-position losses.  h0 is not modified;
+ * h_out (may be NULL) receives the state after the window.  Optional debug outputs (may be NULL):
+ * ct[T][B] = dLoss/dz_m(y_m), dS[T][B][K] = dLoss/dz_m(n_j) (one entry per noise draw), dHs[T][B][H],
+ * dA[T][B][H]. */
+int oracle_nce_grad_chunk(int V, int H, int B, int T, const double *E, const double *U, const double *Wo,
+                          const double *b, const double *h0, const int32_t *x, const int32_t *y, int K,
+                          const int32_t *noise, const double *lnq, double lnZ, double *J, double *gE, double *gU,
+                          double *gWo, double *gb, double *h_out, double *ct_out, double *dS_out, double *dHs_out,
+                          double *dA_out) {
+  if (V <= 0 || H <= 0 || B <= 0 || T <= 0 || K <= 0 || !E || !U || !Wo || !b || !h0 || !x || !y || !noise ||
+      !lnq || !J || !gE || !gU || !gWo || !gb)
+    return ORACLE_ERR_ARG;
+  const size_t M = (size_t)B * T;
+  if (check_tokens(x, (long)M, V) || check_tokens(y, (long)M, V) || check_tokens(noise, K, V)) return ORACLE_ERR_TOKEN;
+  double *Hs = (double *)malloc(sizeof(double) * M * H);
+  double *dHs = dHs_out ? dHs_out : (double *)malloc(sizeof(double) * M * H);
+  double *dA = dA_out ? dA_out : (double *)malloc(sizeof(double) * M * H);
+  int rc = (Hs && dHs && dA) ? ORACLE_OK : ORACLE_ERR_NOMEM;
+  if (rc == ORACLE_OK) {
+    hidden_forward(H, B, T, E, U, h0, x, Hs);
+    const double lnK = log((double)K), scale = 1.0 / (double)M;
+    memset(gWo, 0, sizeof(double) * (size_t)V * H);
+    memset(gb, 0, sizeof(double) * (size_t)V);
+    memset(dHs, 0, sizeof(double) * M * H);
+    /* positions one after the other: every scored word w with coefficient c = dLoss/dz_m(w) adds
+     * c*h_m to gWo[w], c to gb[w] and c*Wo[w] to dHs[m] */
+    for (size_t m = 0; m < M; ++m) {
+      const double *h = Hs + m * H;
+      double *dh = dHs + m * H;
+      double cost = 0.0;
+      for (int j = -1; j < K; ++j) { /* j = -1: the target word, j >= 0: noise word j */
+        const int w = (j < 0) ? y[m] : noise[j];
+        const double *wo = Wo + (size_t)w * H;
+        double z = b[w];
+        for (int i = 0; i < H; ++i) z += wo[i] * h[i];
+        const double d = z - lnZ - (lnK + lnq[w]);
+        double c;
+        if (j < 0) {
+          cost += softplus(-d);         /* -ln sigma(d) */
+          c = -(1.0 - logistic(d)) * scale;
+          if (ct_out) ct_out[m] = c;
+        } else {
+          cost += softplus(d);          /* -ln(1 - sigma(d)) */
+          c = logistic(d) * scale;
+          if (dS_out) dS_out[m * K + j] = c;
+        }
+        double *g = gWo + (size_t)w * H;
+        for (int i = 0; i < H; ++i) g[i] += c * h[i];
+        gb[w] += c;
+        for (int i = 0; i < H; ++i) dh[i] += c * wo[i];
+      }
+      J[m] = cost;
+    }
+    backprop_through_time(V, H, B, T, U, h0, x, Hs, dHs, dA, gU, gE);
+    if (h_out) memcpy(h_out, Hs + (size_t)(T - 1) * B * H, sizeof(double) * (size_t)B * H);
+  }
+  free(Hs);
+  if (!dHs_out) free(dHs);
+  if (!dA_out) free(dA);
+  return rc;
+}
+
+/* One NCE training step on one window: gradients at the current parameters, then one plain SGD
+ * step on E, U, Wo, b; h <- state after the window (pre-update parameters).  J[T][B]; *sum_J (may
+ * be NULL) = sum of J. */
+int oracle_nce_train_chunk(int V, int H, int B, int T, double *E, double *U, double *Wo, double *b, double *h,
+                           const int32_t *x, const int32_t *y, int K, const int32_t *noise, const double *lnq,
+                           double lnZ, double lr, double *J, double *sum_J) {
+  if (V <= 0 || H <= 0 || B <= 0 || T <= 0) return ORACLE_ERR_ARG;
+  const size_t nVH = (size_t)V * H, nHH = (size_t)H * H;
+  double *gE = (double *)malloc(sizeof(double) * nVH);
+  double *gWo = (double *)malloc(sizeof(double) * nVH);
+  double *gU = (double *)malloc(sizeof(double) * nHH);
+  double *gb = (double *)malloc(sizeof(double) * (size_t)V);
+  double *hn = (double *)malloc(sizeof(double) * (size_t)B * H);
+  int rc = ORACLE_ERR_NOMEM;
+  if (gE && gWo && gU && gb && hn)
+    rc = oracle_nce_grad_chunk(V, H, B, T, E, U, Wo, b, h, x, y, K, noise, lnq, lnZ, J, gE, gU, gWo, gb, hn, NULL,
+                               NULL, NULL, NULL);
+  if (rc == ORACLE_OK) {
+    for (size_t i = 0; i < nVH; ++i) E[i] -= lr * gE[i];
+    for (size_t i = 0; i < nVH; ++i) Wo[i] -= lr * gWo[i];
+    for (size_t i = 0; i < nHH; ++i) U[i] -= lr * gU[i];
+    for (int v = 0; v < V; ++v) b[v] -= lr * gb[v];
+    memcpy(h, hn, sizeof(double) * (size_t)B * H);
+    if (sum_J) {
+      double sacc = 0.0;
+      for (size_t m = 0; m < (size_t)B * T; ++m) sacc += J[m];
+      *sum_J = sacc;
     }
   }
   free(gE); free(gWo); free(gU); free(gb); free(hn);
