@@ -67,6 +67,8 @@ typedef struct {
   int32_t T_max;     /* longest window a call may pass, > 0 */
   int32_t precision; /* rnnlm_precision */
   int32_t device;    /* HIP device ordinal */
+  int32_t K_max;     /* most noise words per window the noise-contrastive calls may pass; 0 = those calls are
+                        not used (no workspace is set aside for them), >= 0, at most 65536 */
 } rnnlm_config;
 
 typedef struct {
@@ -114,6 +116,31 @@ int rnnlm_train_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T,
  * NULL.  Parameters and h_state are left unchanged. */
 int rnnlm_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *dE, float *dU, float *dWo,
                      float *db, float *logp, void *stream);
+
+/* One training step on one window under the noise-contrastive criterion that Sec. 4.2 trains with.
+ * The paper gives neither formula nor constants; this is the published estimator (Gutmann & Hyvarinen;
+ * Mnih & Teh for language models) with these readings: scores z_m(w) = Wo[w].h_m + b[w] are
+ * log-probabilities up to the constant lnZ; K noise words, drawn by the caller from a noise
+ * distribution with log-probabilities lnq, are shared by all B*T positions of the window; with
+ * D_m(w) = z_m(w) - lnZ - ln(K q(w)) position m costs
+ *     J_m = -ln sigmoid(D_m(y_m)) - sum_j ln(1 - sigmoid(D_m(noise[j])))
+ * (every noise word is a term of its own, also when it repeats or equals the target); the window
+ * loss is the mean of J_m; its gradient goes back through time as in rnnlm_train_chunk and is
+ * followed by the same plain SGD step, which here touches only the rows of Wo and entries of b of the
+ * target and noise words (contributions to one row add up in a fixed order, no atomics).
+ * noise: dev int32[K], 1 <= K <= K_max, ids in [0,V) (checked like token ids); lnq: dev float[V];
+ * J: dev float[T][B] or NULL; sum_J: dev double (sum of the window's J) or NULL.  The explicitly
+ * normalised output used for perplexity is unchanged (rnnlm_forward_logprob, rnnlm_perplexity). */
+int rnnlm_nce_train_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, const int32_t *noise, int32_t K,
+                          const float *lnq, float lnZ, float lr, float *J, double *sum_J, void *stream);
+
+/* Same kernels as rnnlm_nce_train_chunk with the updates redirected: gradients of the mean
+ * noise-contrastive loss into dE, dU, dWo: dev float[V][H] / [H][H] / [V][H] and db: dev float[V] (rows
+ * and entries of words that are neither input, target nor noise are zero); J as above or NULL.
+ * Parameters and h_state are left unchanged. */
+int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, const int32_t *noise, int32_t K,
+                         const float *lnq, float lnZ, float *dE, float *dU, float *dWo, float *db, float *J,
+                         void *stream);
 
 /* Perplexity (Sec. 1, Sec. 4.2: normalised output) of tok: dev int32[N]: h_state is reset to zero,
  * the array is split into B streams as in rnnlm_stream_chunk and every full window of T positions
@@ -168,7 +195,13 @@ typedef enum {
   RNNLM_STAGE_REC_W = 8,        /* recurrent weight gradient contraction + SGD */
   RNNLM_STAGE_EMB = 9,          /* sort/segments + segmented embedding update */
   RNNLM_STAGE_REDUCE = 10,      /* fixed-order sum of the split-K partials of stage 5 */
-  RNNLM_STAGE_COUNT = 11
+  /* noise-contrastive calls: stages 2-5 and 7 are replaced by */
+  RNNLM_STAGE_NCE_SCORE = 11,   /* noise-row gather, score contraction, target scores */
+  RNNLM_STAGE_NCE_GRAD = 12,    /* elementwise pass: coefficients, losses, bias-gradient column sums */
+  RNNLM_STAGE_NCE_BWD_H = 13,   /* gradient w.r.t. the hidden states (contraction over the noise words + targets) */
+  RNNLM_STAGE_NCE_BWD_W = 14,   /* noise-row weight gradient contraction */
+  RNNLM_STAGE_NCE_UPDATE = 15,  /* sort/segments of the touched words + row and bias updates */
+  RNNLM_STAGE_COUNT = 16
 } rnnlm_stage;
 
 /* Brackets every later execution of the stages whose bit (1u << stage) is set in stage_mask with a

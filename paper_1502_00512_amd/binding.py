@@ -21,14 +21,16 @@ SYMBOLS = [
     "rnnlm_train_chunk", "rnnlm_grad_chunk", "rnnlm_perplexity", "rnnlm_reset_state",
     "rnnlm_sync_compute_copies", "rnnlm_check", "rnnlm_sort_segments", "rnnlm_status_string",
     "rnnlm_profile_enable", "rnnlm_profile_read", "rnnlm_set_barrier_spin_limit", "rnnlm_measure_peaks",
+    "rnnlm_nce_train_chunk", "rnnlm_nce_grad_chunk",
 ]
 
-STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce"]
+STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce",
+          "nce_score", "nce_grad", "nce_bwd_h", "nce_bwd_w", "nce_update"]
 
 
 class rnnlm_config(C.Structure):
     _fields_ = [("V", C.c_int32), ("H", C.c_int32), ("B", C.c_int32), ("T_max", C.c_int32),
-                ("precision", C.c_int32), ("device", C.c_int32)]
+                ("precision", C.c_int32), ("device", C.c_int32), ("K_max", C.c_int32)]
 
 
 class rnnlm_buffers(C.Structure):
@@ -70,6 +72,9 @@ def load():
     lib.rnnlm_sort_segments.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     lib.rnnlm_set_barrier_spin_limit.argtypes = [vp, C.c_uint32]
     lib.rnnlm_measure_peaks.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
+    f32 = C.c_float
+    lib.rnnlm_nce_train_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, f32, vp, vp, vp]
+    lib.rnnlm_nce_grad_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp]
     lib.rnnlm_profile_enable.argtypes = [vp, C.c_uint32]
     lib.rnnlm_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.rnnlm_status_string.argtypes = [C.c_int]
@@ -100,15 +105,15 @@ def _stream(stream):
     return C.c_void_p(s.cuda_stream)
 
 
-def rnnlm_workspace_bytes(V, H, B, T_max, precision, device=0) -> int:
-    cfg = rnnlm_config(V, H, B, T_max, precision, device)
+def rnnlm_workspace_bytes(V, H, B, T_max, precision, device=0, K_max=0) -> int:
+    cfg = rnnlm_config(V, H, B, T_max, precision, device, K_max)
     return int(load().rnnlm_workspace_bytes(C.byref(cfg)))
 
 
 class Rnnlm:
     """Owns the torch tensors (masters, state, workspace) and the library handle."""
 
-    def __init__(self, E, U, Wo, b, B: int, T_max: int, precision: int, device: int = 0):
+    def __init__(self, E, U, Wo, b, B: int, T_max: int, precision: int, device: int = 0, K_max: int = 0):
         import torch
         self.lib = load()
         dev = torch.device("cuda", device)
@@ -118,7 +123,8 @@ class Rnnlm:
         self.B, self.T_max, self.precision, self.device = int(B), int(T_max), int(precision), dev
         assert self.U.shape == (self.H, self.H) and self.Wo.shape == (self.V, self.H) and self.b.shape == (self.V,)
         self.h_state = torch.zeros(self.B, self.H, dtype=torch.float32, device=dev)
-        cfg = rnnlm_config(self.V, self.H, self.B, self.T_max, self.precision, device)
+        self.K_max = int(K_max)
+        cfg = rnnlm_config(self.V, self.H, self.B, self.T_max, self.precision, device, self.K_max)
         nbytes = int(self.lib.rnnlm_workspace_bytes(C.byref(cfg)))
         if nbytes == 0:
             raise RnnlmError(-1, "rnnlm_workspace_bytes")
@@ -180,6 +186,21 @@ class Rnnlm:
         _ok(self.lib.rnnlm_perplexity(self.handle, _ptr(tok), tok.numel(), T, C.byref(ppl), C.byref(scored),
                                       _stream(stream)), "rnnlm_perplexity")
         return ppl.value, scored.value
+
+    def rnnlm_nce_train_chunk(self, x, y, noise, lnq, lnZ: float, lr: float, J=None, sum_J=None, stream=None):
+        _ok(self.lib.rnnlm_nce_train_chunk(self.handle, _ptr(x), _ptr(y), x.shape[0], _ptr(noise), noise.numel(),
+                                           _ptr(lnq), lnZ, lr, _ptr(J), _ptr(sum_J), _stream(stream)),
+            "rnnlm_nce_train_chunk")
+
+    def rnnlm_nce_grad_chunk(self, x, y, noise, lnq, lnZ: float, want_J=True, stream=None):
+        import torch
+        z = lambda *s: torch.empty(*s, dtype=torch.float32, device=self.device)
+        dE, dU, dWo, db = z(self.V, self.H), z(self.H, self.H), z(self.V, self.H), z(self.V)
+        J = z(x.shape[0], self.B) if want_J else None
+        _ok(self.lib.rnnlm_nce_grad_chunk(self.handle, _ptr(x), _ptr(y), x.shape[0], _ptr(noise), noise.numel(),
+                                          _ptr(lnq), lnZ, _ptr(dE), _ptr(dU), _ptr(dWo), _ptr(db), _ptr(J),
+                                          _stream(stream)), "rnnlm_nce_grad_chunk")
+        return dict(gE=dE, gU=dU, gWo=dWo, gb=db, J=J)
 
     def rnnlm_reset_state(self, stream=None):
         _ok(self.lib.rnnlm_reset_state(self.handle, _stream(stream)), "rnnlm_reset_state")

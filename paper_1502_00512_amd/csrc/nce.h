@@ -1,0 +1,253 @@
+// Kernels of the noise-contrastive training criterion (Sec. 4.2 of the paper names it; the estimator
+// is Gutmann & Hyvarinen's, in the form Mnih & Teh use for language models).
+//
+// For window position m with hidden state h_m and target y_m, and K noise words n_0..n_{K-1} shared by
+// the whole window, with scores z_m(w) = Wo[w].h_m + b[w] and D_m(w) = z_m(w) - lnZ - ln(K q(w)):
+//   J_m = softplus(-D_m(y_m)) + sum_j softplus(D_m(n_j)),        softplus(d) = ln(1 + e^d)
+//   dJ_m/dz_m(y_m) = -(1 - sigmoid(D_m(y_m))),  dJ_m/dz_m(n_j) = sigmoid(D_m(n_j)),
+// window loss = mean of J_m.  The dense parts (all positions x all noise words) run on the contraction
+// kernels over a gathered panel of Wo rows; the kernels here do the gathers, the elementwise pass, the
+// per-target terms and the order-fixed, atomic-free update of the touched rows of Wo and b.
+//
+// Index conventions: "row" = t*Bp + s is a padded window position; "m" = t*B + s the compact one; entry
+// e of the update list is noise word e for e < K and the target of compact position e - K otherwise.
+#pragma once
+#include "common.h"
+
+namespace rnnlm_dev {
+
+__device__ inline float softplusf_(float d) { return fmaxf(d, 0.0f) + log1pf(__expf(-fabsf(d))); }
+__device__ inline float logisticf_(float d) {
+  const float e = __expf(-fabsf(d));
+  return (d >= 0.0f) ? 1.0f / (1.0f + e) : e / (1.0f + e);
+}
+
+// Noise ids checked (flags[0] on an id outside [0,V), clamped), per-noise-word offset
+// off[j] = b[n_j] - lnZ - ln K - lnq[n_j] (0 for the padding j >= K) and the update list ids[K + M].
+__global__ void nce_prep_kernel(const int32_t *__restrict__ noise, int K, int Kp, int V,
+                                const float *__restrict__ lnq, const float *__restrict__ b, float lnZ_lnK,
+                                const int32_t *__restrict__ yp, int M, int B, int Bp, int32_t *__restrict__ noise_c,
+                                float *__restrict__ off, int32_t *__restrict__ ids, int32_t *__restrict__ flags) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < Kp) {
+    int w = 0;
+    float o = 0.0f;
+    if (i < K) {
+      w = noise[i];
+      if (w < 0 || w >= V) {
+        flags[0] = 1;
+        w = min(max(w, 0), V - 1);
+      }
+      o = b[w] - lnZ_lnK - lnq[w];
+      ids[i] = w;
+    }
+    noise_c[i] = w;
+    off[i] = o;
+  } else if (i - Kp < M) {
+    const int m = i - Kp;
+    ids[K + m] = yp[(m / B) * Bp + (m % B)];
+  }
+}
+
+// Wn[j][:] = Wo_c[n_j][:] for j < K, zero rows for K <= j < Kp (Hp is a multiple of 256).
+template <typename T>
+__global__ void __launch_bounds__(256) nce_gather_rows_kernel(const T *__restrict__ Wo_c, int Hp,
+                                                              const int32_t *__restrict__ noise_c, int K,
+                                                              T *__restrict__ Wn) {
+  constexpr int VEC = 16 / (int)sizeof(T);
+  const int j = blockIdx.x;
+  const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Wo_c + (long)noise_c[j] * Hp);
+  u32x4_t *dst = reinterpret_cast<u32x4_t *>(Wn + (long)j * Hp);
+  const u32x4_t zero = {0u, 0u, 0u, 0u};
+  for (int c = threadIdx.x; c < Hp / VEC; c += 256) dst[c] = (j < K) ? src[c] : zero;
+}
+
+// D of the target word of every position: dt[row] = Wo_c[y].Hs[row] + b[y] - lnZ - ln K - lnq[y].
+// One wave per padded position (4 per workgroup); lanes stride the row, then a butterfly sum.
+template <typename T>
+__global__ void __launch_bounds__(256) nce_target_score_kernel(const T *__restrict__ Hs1, const T *__restrict__ Wo_c,
+                                                               int Hp, const int32_t *__restrict__ yp,
+                                                               const float *__restrict__ b,
+                                                               const float *__restrict__ lnq, float lnZ_lnK, int rows,
+                                                               float *__restrict__ dt) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const int y = yp[row];
+  if (y < 0) {
+    if (lane == 0) dt[row] = 0.0f;
+    return;
+  }
+  const T *hrow = Hs1 + (long)row * Hp, *wrow = Wo_c + (long)y * Hp;
+  float acc = 0.0f;
+  for (int c = lane; c < Hp; c += 64) acc = fmaf(to_f32(hrow[c]), to_f32(wrow[c]), acc);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  if (lane == 0) dt[row] = acc + b[y] - lnZ_lnK - lnq[y];
+}
+
+// Elementwise pass over one padded position (one workgroup per row of the score matrix S[Mp][Kp]):
+// dS[row][j] = sigmoid(S + off[j]) * scale in the contraction operand type (0 for padding rows and
+// columns), the position's loss J, and the target coefficient ct[row] = -(1 - sigmoid(dt)) * scale.
+template <typename T>
+__global__ void __launch_bounds__(256) nce_grad_kernel(const float *__restrict__ S, int Kp, int K,
+                                                       const float *__restrict__ off, const float *__restrict__ dt,
+                                                       int Tn, int B, int Bp, float scale, T *__restrict__ dS,
+                                                       float *__restrict__ ct, float *__restrict__ J_int,
+                                                       float *__restrict__ J_out) {
+  __shared__ float red[4];
+  const int row = blockIdx.x, t = row / Bp, s = row % Bp;
+  const bool valid = t < Tn && s < B;
+  const float *srow = S + (long)row * Kp;
+  T *drow = dS + (long)row * Kp;
+  float cost = 0.0f;
+  for (int j = threadIdx.x; j < Kp; j += 256) {
+    float g = 0.0f;
+    if (valid && j < K) {
+      const float d = srow[j] + off[j];
+      g = logisticf_(d) * scale;
+      cost += softplusf_(d);
+    }
+    drow[j] = from_f32<T>(g);
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cost += __shfl_xor(cost, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = cost;
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  if (!valid) {
+    ct[row] = 0.0f;
+    return;
+  }
+  const float d = dt[row];
+  const float total = ((red[0] + red[1]) + (red[2] + red[3])) + softplusf_(-d);
+  ct[row] = -logisticf_(-d) * scale;
+  const int m = t * B + s;
+  J_int[m] = total;
+  if (J_out) J_out[m] = total;
+}
+
+// gcol[j] = sum over valid positions of sigmoid(S[row][j] + off[j]) * scale: the bias gradient of noise
+// word j.  Workgroup = 64 columns x 16 row groups; each group sums its rows in ascending order and the
+// 16 partial sums are added in order.
+__global__ void __launch_bounds__(1024) nce_colsum_kernel(const float *__restrict__ S, int Kp, int K,
+                                                          const float *__restrict__ off, int Tn, int B, int Bp,
+                                                          float scale, float *__restrict__ gcol) {
+  __shared__ float sh[16][64];
+  const int c = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + c;
+  float acc = 0.0f;
+  if (j < K) {
+    const float o = off[j];
+    const int M = Tn * B;
+    for (int m = grp; m < M; m += 16) {
+      const long row = (long)(m / B) * Bp + (m % B);
+      acc += logisticf_(S[row * Kp + j] + o) * scale;
+    }
+  }
+  sh[grp][c] = acc;
+  __syncthreads();
+  if (grp != 0) return;
+  float tot = 0.0f;
+  for (int g = 0; g < 16; ++g) tot += sh[g][c];
+  gcol[j] = tot;
+}
+
+// dHs[row][:] += ct[row] * Wo_c[y_row][:]: the target word's share of what the output layer sends back.
+template <typename T>
+__global__ void __launch_bounds__(256) nce_target_dhs_kernel(const T *__restrict__ Wo_c, int Hp,
+                                                             const int32_t *__restrict__ yp,
+                                                             const float *__restrict__ ct,
+                                                             float *__restrict__ dHs) {
+  const int row = blockIdx.x;
+  const int y = yp[row];
+  if (y < 0) return;
+  const float c = ct[row];
+  const T *w = Wo_c + (long)y * Hp;
+  float *d = dHs + (long)row * Hp;
+  for (int col = threadIdx.x; col < Hp; col += 256) d[col] = fmaf(c, to_f32(w[col]), d[col]);
+}
+
+// Update of the touched rows of Wo, atomic-free and order-fixed:
+//   out[w][:] = alpha*Wo[w][:] - lr * ( sum_{noise entries e of w} G[e][:] + sum_{target entries} ct*Hs[row][:] )
+// blockIdx.x = run of equal ids in the sorted update list (exits when >= *nseg), blockIdx.y = block of
+// 256*VEC columns.  The run's members are dealt round-robin to 4 partial sums (each in ascending list
+// order) which are then added in order.  Also refreshes the compute copy of the row when Wc != nullptr.
+template <typename T, int VEC>
+__global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__restrict__ G, const T *__restrict__ Hs1,
+                                                              int Hp, int H, int K, int B, int Bp,
+                                                              const float *__restrict__ ct,
+                                                              const int32_t *__restrict__ ids,
+                                                              const int32_t *__restrict__ perm,
+                                                              const int32_t *__restrict__ seg_start,
+                                                              const int32_t *__restrict__ nseg,
+                                                              const float *__restrict__ W, float *__restrict__ out,
+                                                              T *__restrict__ Wc, float alpha, float lr) {
+  constexpr int PARTS = 4, LANES = 256;
+  __shared__ float sh[PARTS][LANES * VEC];
+  const int g = blockIdx.x;
+  if (g >= *nseg) return;
+  const int lane = threadIdx.x % LANES, partn = threadIdx.x / LANES;
+  const int col = (blockIdx.y * LANES + lane) * VEC;
+  const int r0 = seg_start[g], r1 = seg_start[g + 1];
+  float acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
+  if (col < H) {
+    for (int r = r0 + partn; r < r1; r += PARTS) {
+      const int ent = perm[r];
+      if (ent < K) {
+        const float *src = G + (long)ent * Hp + col;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += src[e];
+      } else {
+        const int m = ent - K;
+        const long row = (long)(m / B) * Bp + (m % B);
+        const float c = ct[row];
+        const T *src = Hs1 + row * Hp + col;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] = fmaf(c, to_f32(src[e]), acc[e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) sh[partn][lane * VEC + e] = acc[e];
+  __syncthreads();
+  if (partn != 0 || col >= H) return;
+#pragma unroll
+  for (int q = 1; q < PARTS; ++q)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] += sh[q][lane * VEC + e];
+  const int w = ids[perm[r0]];
+  const long idx = (long)w * H + col;
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) {
+    const float v = ((alpha != 0.0f) ? alpha * W[idx + e] : 0.0f) - lr * acc[e];
+    out[idx + e] = v;
+    if (Wc) Wc[(long)w * Hp + col + e] = from_f32<T>(v);
+  }
+}
+
+// b_out[w] = alpha*b[w] - lr * (sum of gcol over w's noise entries + sum of ct over its target entries),
+// one thread per run, members added in list order.
+__global__ void nce_bias_update_kernel(const float *__restrict__ gcol, const float *__restrict__ ct, int K, int B,
+                                       int Bp, const int32_t *__restrict__ ids, const int32_t *__restrict__ perm,
+                                       const int32_t *__restrict__ seg_start, const int32_t *__restrict__ nseg,
+                                       const float *__restrict__ b, float *__restrict__ b_out, float alpha, float lr) {
+  const int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= *nseg) return;
+  const int r0 = seg_start[g], r1 = seg_start[g + 1];
+  float acc = 0.0f;
+  for (int r = r0; r < r1; ++r) {
+    const int ent = perm[r];
+    if (ent < K) {
+      acc += gcol[ent];
+    } else {
+      const int m = ent - K;
+      acc += ct[(long)(m / B) * Bp + (m % B)];
+    }
+  }
+  const int w = ids[perm[r0]];
+  b_out[w] = ((alpha != 0.0f) ? alpha * b[w] : 0.0f) - lr * acc;
+}
+
+}  // namespace rnnlm_dev

@@ -12,6 +12,7 @@
 #include "gemm.h"
 #include "gemm_dma.h"
 #include "kernels.h"
+#include "nce.h"
 #include "rnn_persistent.h"
 
 using namespace rnnlm_dev;
@@ -25,6 +26,8 @@ using namespace rnnlm_dev;
 struct WsLayout {
   size_t Wo_c, U_c, UT_c, Hs_c, ZT, dA_c, X32, dHs32, dA32, part32, stat, lse, zy, logp_int, xp, yp, perm, seg, xtmp, ytmp,
       scalars, total;
+  // noise-contrastive calls (present when K_max > 0)
+  size_t Wn_c, S32, dS_c, G32, noff, ndt, nct, gcol, noise_c, ids, perm2, seg2;
   long partElems;
 };
 
@@ -37,6 +40,7 @@ struct rnnlm {
   rnnlm_config cfg;
   rnnlm_buffers buf;
   int Hp, Vp, Bp, MpMax;
+  int KpMax;  // K_max rounded up to the tile size (0: no noise-contrastive workspace)
   int nPart;
   WsLayout L;
   char *ws;
@@ -114,6 +118,7 @@ bool cfg_ok(const rnnlm_config *c) {
   if (c->V <= 0 || c->H <= 0 || c->B <= 0 || c->T_max <= 0) return false;
   if (c->precision != RNNLM_FP32 && c->precision != RNNLM_BF16_FP32MASTER) return false;
   if (c->device < 0) return false;
+  if (c->K_max < 0 || c->K_max > 65536) return false;
   if ((long)c->B * c->T_max > (1L << 24)) return false;
   return true;
 }
@@ -127,7 +132,7 @@ int desired_splits(long Mp, long Hp, long kBlocks) {
   return (int)s;
 }
 
-void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, int &nPart, WsLayout &L) {
+void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, int &nPart, int &KpMax, WsLayout &L) {
   const size_t es = (c.precision == RNNLM_FP32) ? 4 : 2;
   Hp = (int)round_up(c.H, PAD_H);
   Vp = (int)round_up(c.V, PAD_V);
@@ -163,7 +168,24 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
   L.seg = take((size_t)(MpMax + 1) * 4);
   L.xtmp = take((size_t)c.T_max * c.B * 4);
   L.ytmp = take((size_t)c.T_max * c.B * 4);
-  L.scalars = take(256);  // [0]: int nseg, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64..131]: 17 barrier/ticket counters
+  KpMax = (int)round_up(c.K_max, 256);
+  L.Wn_c = L.S32 = L.dS_c = L.G32 = L.noff = L.ndt = L.nct = L.gcol = L.noise_c = L.ids = L.perm2 = L.seg2 = 0;
+  if (KpMax > 0) {
+    const size_t nent = (size_t)KpMax + (size_t)c.T_max * c.B;
+    L.Wn_c = take((size_t)KpMax * Hp * es);
+    L.S32 = take((size_t)MpMax * KpMax * 4);
+    L.dS_c = take((size_t)MpMax * KpMax * es);
+    L.G32 = take((size_t)KpMax * Hp * 4);
+    L.noff = take((size_t)KpMax * 4);
+    L.ndt = take((size_t)MpMax * 4);
+    L.nct = take((size_t)MpMax * 4);
+    L.gcol = take((size_t)KpMax * 4);
+    L.noise_c = take((size_t)KpMax * 4);
+    L.ids = take(nent * 4);
+    L.perm2 = take(nent * 4);
+    L.seg2 = take((nent + 1) * 4);
+  }
+  L.scalars = take(256);  // [0]: int nseg, [4]: int nseg of the noise-contrastive update list, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64..131]: 17 barrier/ticket counters
   L.total = o;
 }
 
@@ -172,6 +194,7 @@ P *at(rnnlm_t *h, size_t off) {
   return reinterpret_cast<P *>(h->ws + off);
 }
 int32_t *p_nseg(rnnlm_t *h) { return at<int32_t>(h, h->L.scalars); }
+int32_t *p_nseg2(rnnlm_t *h) { return at<int32_t>(h, h->L.scalars + 4); }
 int32_t *p_flags(rnnlm_t *h) { return at<int32_t>(h, h->L.scalars + 8); }
 double *p_sum(rnnlm_t *h) { return at<double>(h, h->L.scalars + 32); }
 double *p_running(rnnlm_t *h) { return at<double>(h, h->L.scalars + 40); }
@@ -259,7 +282,7 @@ struct UpdateTargets {
 // output layer with fused statistics, log-probabilities.
 template <typename T>
 int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *logp_out, bool advance_state,
-                   hipStream_t st) {
+                   bool with_output, hipStream_t st) {
   const rnnlm_config &c = h->cfg;
   const int Hp = h->Hp, Bp = h->Bp, Vp = h->Vp;
   const int Mrows = Tn * Bp;
@@ -297,6 +320,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     HIP_TRY((launch_gemm<T, 32, 64, 1, 2, ROWK, ROWK>(st, Hs_c + (long)t * Bp * Hp, Hp, at<T>(h, h->L.U_c), Hp, Bp, Hp,
                                                       Hp, 1, epi)));
   }
+  if (!with_output) return RNNLM_OK;  // the noise-contrastive calls score the hidden states themselves
   {
     StageTimer tm(h, RNNLM_STAGE_OUT_FWD, st);
     EpiOutFwd<T> epi;
@@ -327,9 +351,128 @@ int sort_segments(rnnlm_t *h, int Tn, int32_t *perm, int32_t *seg, int32_t *nseg
   return RNNLM_OK;
 }
 
+// One call of the noise-contrastive criterion (Sec. 4.2): K noise words shared by the window.
+struct NceCall {
+  const int32_t *noise;
+  int K;
+  const float *lnq;
+  float lnZ;
+  float *J_out;
+};
+
+// Scores of all positions against the gathered noise rows, the targets' own scores, then the
+// elementwise pass: coefficients dS (contraction operand), target coefficients, losses, bias column sums.
+template <typename T>
+int nce_forward(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
+  const rnnlm_config &c = h->cfg;
+  const int Hp = h->Hp, Bp = h->Bp;
+  const int Mrows = Tn * Bp, Mp = (int)round_up(Mrows, PAD_M), M = Tn * c.B;
+  const int K = n.K, Kp = (int)round_up(K, 256);
+  T *Hs1 = at<T>(h, h->L.Hs_c) + (long)Bp * Hp;
+  T *Wn = at<T>(h, h->L.Wn_c);
+  float *S = at<float>(h, h->L.S32);
+  int32_t *yp = at<int32_t>(h, h->L.yp);
+  const float lnZ_lnK = n.lnZ + logf((float)K);
+  const float scale = 1.0f / (float)M;
+  {
+    StageTimer tm(h, RNNLM_STAGE_NCE_SCORE, st);
+    hipLaunchKernelGGL(nce_prep_kernel, dim3(blocks_for((long)Kp + M, 256)), dim3(256), 0, st, n.noise, K, Kp, c.V, n.lnq,
+                       h->buf.b, lnZ_lnK, yp, M, c.B, Bp, at<int32_t>(h, h->L.noise_c), at<float>(h, h->L.noff),
+                       at<int32_t>(h, h->L.ids), p_flags(h));
+    hipLaunchKernelGGL(nce_gather_rows_kernel<T>, dim3(Kp), dim3(256), 0, st, at<T>(h, h->L.Wo_c), Hp,
+                       at<int32_t>(h, h->L.noise_c), K, Wn);
+    hipLaunchKernelGGL(nce_target_score_kernel<T>, dim3(blocks_for(Mrows, 4)), dim3(256), 0, st, Hs1,
+                       at<T>(h, h->L.Wo_c), Hp, yp, h->buf.b, n.lnq, lnZ_lnK, Mrows, at<float>(h, h->L.ndt));
+    HIP_TRY(hipGetLastError());
+    EpiPartial epi;
+    epi.part = S;
+    epi.ld = Kp;
+    epi.split_stride = 0;
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, ROWK>(st, Hs1, Hp, Wn, Hp, Mp, Kp, Hp, 1, epi)));
+  }
+  StageTimer tm(h, RNNLM_STAGE_NCE_GRAD, st);
+  hipLaunchKernelGGL(nce_grad_kernel<T>, dim3(Mp), dim3(256), 0, st, S, Kp, K, at<float>(h, h->L.noff),
+                     at<float>(h, h->L.ndt), Tn, c.B, Bp, scale, at<T>(h, h->L.dS_c), at<float>(h, h->L.nct),
+                     at<float>(h, h->L.logp_int), n.J_out);
+  hipLaunchKernelGGL(nce_colsum_kernel, dim3(Kp / 64), dim3(1024), 0, st, S, Kp, K, at<float>(h, h->L.noff), Tn, c.B,
+                     Bp, scale, at<float>(h, h->L.gcol));
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+// dHs = dS . Wn + ct * Wo[target]  (what the output layer sends back to the hidden states)
+template <typename T>
+int nce_backward_h(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
+  const int Hp = h->Hp, Bp = h->Bp;
+  const int Mrows = Tn * Bp, Mp = (int)round_up(Mrows, PAD_M);
+  const int Kp = (int)round_up(n.K, 256);
+  float *dHs32 = at<float>(h, h->L.dHs32);
+  StageTimer tm(h, RNNLM_STAGE_NCE_BWD_H, st);
+  EpiPartial epi;
+  epi.part = dHs32;
+  epi.ld = Hp;
+  epi.split_stride = 0;
+  HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, KROW>(st, at<T>(h, h->L.dS_c), Kp, at<T>(h, h->L.Wn_c), Hp, Mp, Hp, Kp,
+                                                      1, epi)));
+  hipLaunchKernelGGL(nce_target_dhs_kernel<T>, dim3(Mrows), dim3(256), 0, st, at<T>(h, h->L.Wo_c), Hp,
+                     at<int32_t>(h, h->L.yp), at<float>(h, h->L.nct), dHs32);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+// Gradient rows of the noise words (G = dS^T . Hs), then the order-fixed update of every touched row of
+// Wo and entry of b (noise words and targets together).
+template <typename T>
+int nce_update(rnnlm_t *h, int Tn, const NceCall &n, const UpdateTargets &u, hipStream_t st) {
+  const rnnlm_config &c = h->cfg;
+  const int Hp = h->Hp, Bp = h->Bp;
+  const int Mrows = Tn * Bp, Mp = (int)round_up(Mrows, PAD_M), M = Tn * c.B;
+  const int K = n.K, Kp = (int)round_up(K, 256);
+  T *Hs1 = at<T>(h, h->L.Hs_c) + (long)Bp * Hp;
+  float *G = at<float>(h, h->L.G32);
+  {
+    StageTimer tm(h, RNNLM_STAGE_NCE_BWD_W, st);
+    const long per = (long)Kp * Hp;
+    constexpr int BK = Elem<T>::BK;
+    long S = 256 / ((long)(Kp / 128) * (Hp / 128));  // aim at one round of workgroups
+    S = std::min<long>(std::min<long>(S, 8), std::min<long>(Mp / BK, h->L.partElems / per));
+    if (S < 1) S = 1;
+    EpiPartial epi;
+    epi.part = (S == 1) ? G : at<float>(h, h->L.part32);
+    epi.ld = Hp;
+    epi.split_stride = per;
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, at<T>(h, h->L.dS_c), Kp, Hs1, Hp, Kp, Hp, Mp, (int)S, epi)));
+    if (S > 1) {
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks_for(per / 4, 256)), dim3(256), 0, st,
+                         at<float>(h, h->L.part32), per, per, (int)S, G);
+      HIP_TRY(hipGetLastError());
+    }
+  }
+  StageTimer tm(h, RNNLM_STAGE_NCE_UPDATE, st);
+  const int nent = K + M;
+  int32_t *ids = at<int32_t>(h, h->L.ids), *perm = at<int32_t>(h, h->L.perm2), *seg = at<int32_t>(h, h->L.seg2);
+  // the sort helpers index keys as key[(i / B) * Bp + i % B]: B = Bp = 1 reads the compact list
+  hipLaunchKernelGGL(rank_sort_kernel, dim3(blocks_for(nent, 64)), dim3(1024), 0, st, ids, nent, 1, 1, perm);
+  hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(1024), 0, st, ids, perm, nent, 1, 1, seg, p_nseg2(h));
+  T *Wc = u.refresh_copies ? at<T>(h, h->L.Wo_c) : nullptr;
+  if (c.H % 4 == 0) {
+    hipLaunchKernelGGL((nce_row_update_kernel<T, 4>), dim3(nent, (c.H + 1023) / 1024), dim3(1024), 0, st, G, Hs1, Hp,
+                       c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
+                       u.alpha, u.lr);
+  } else {
+    hipLaunchKernelGGL((nce_row_update_kernel<T, 1>), dim3(nent, (c.H + 255) / 256), dim3(1024), 0, st, G, Hs1, Hp,
+                       c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
+                       u.alpha, u.lr);
+  }
+  hipLaunchKernelGGL(nce_bias_update_kernel, dim3(blocks_for(nent, 256)), dim3(256), 0, st, at<float>(h, h->L.gcol),
+                     at<float>(h, h->L.nct), K, c.B, Bp, ids, perm, seg, p_nseg2(h), h->buf.b, u.b, u.alpha, u.lr);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
 // Backward half of a window + fused updates.
 template <typename T>
-int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) {
+int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *nce, hipStream_t st) {
   const rnnlm_config &c = h->cfg;
   const int Hp = h->Hp, Bp = h->Bp, Vp = h->Vp;
   const int Mrows = Tn * Bp;
@@ -353,6 +496,10 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
     if (rc) return rc;
   }
 
+  if (nce) {
+    int rc = nce_backward_h<T>(h, Tn, *nce, st);
+    if (rc) return rc;
+  } else {
   // fused softmax gradient + bias update, in place on the vocabulary-major logits
   {
     StageTimer tm(h, RNNLM_STAGE_SOFTMAX_GRAD, st);
@@ -381,6 +528,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
                          at<float>(h, h->L.part32), per, per, S, dHs32);
       HIP_TRY(hipGetLastError());
     }
+  }
   }
 
   // rows [Mrows, Mp) of dA take part in the dU contraction: keep them zero
@@ -411,8 +559,11 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
                                                       epi)));
   }
 
-  // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j], contracted transposed (tile rows = j, tile columns = v)
-  {
+  if (nce) {
+    int rc = nce_update<T>(h, Tn, *nce, u, st);
+    if (rc) return rc;
+  } else {
+    // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j], contracted transposed (tile rows = j, tile columns = v)
     StageTimer tm(h, RNNLM_STAGE_OUT_BWD_W, st);
     EpiSgdT<T> epi;
     epi.W = h->buf.Wo;
@@ -465,15 +616,19 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, hipStream_t st) 
 
 template <typename T>
 int window_call(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *logp, double *sum_logp,
-                const UpdateTargets *u, bool advance_state, hipStream_t st) {
-  int rc = forward_window<T>(h, x, y, Tn, logp, advance_state, st);
+                const UpdateTargets *u, bool advance_state, hipStream_t st, const NceCall *nce = nullptr) {
+  int rc = forward_window<T>(h, x, y, Tn, logp, advance_state, nce == nullptr, st);
   if (rc) return rc;
+  if (nce) {  // per-position losses take the place of the log-probabilities
+    rc = nce_forward<T>(h, Tn, *nce, st);
+    if (rc) return rc;
+  }
   if (sum_logp || u) {
     hipLaunchKernelGGL(sum_logp_kernel, dim3(1), dim3(1024), 0, st, at<float>(h, h->L.logp_int), Tn * h->cfg.B,
                        sum_logp ? sum_logp : p_sum(h), (double *)nullptr, p_flags(h));
     HIP_TRY(hipGetLastError());
   }
-  if (u) rc = backward_window<T>(h, Tn, *u, st);
+  if (u) rc = backward_window<T>(h, Tn, *u, nce, st);
   return rc;
 }
 
@@ -487,9 +642,9 @@ extern "C" {
 
 size_t rnnlm_workspace_bytes(const rnnlm_config *cfg) {
   if (!cfg_ok(cfg)) return 0;
-  int Hp, Vp, Bp, MpMax, nPart;
+  int Hp, Vp, Bp, MpMax, nPart, KpMax;
   WsLayout L;
-  make_layout(*cfg, Hp, Vp, Bp, MpMax, nPart, L);
+  make_layout(*cfg, Hp, Vp, Bp, MpMax, nPart, KpMax, L);
   return L.total;
 }
 
@@ -507,7 +662,7 @@ int rnnlm_init(const rnnlm_config *cfg, const rnnlm_buffers *buf, rnnlm_t **out)
   if (!h) return RNNLM_ERR_NOMEM;
   h->cfg = *cfg;
   h->buf = *buf;
-  make_layout(*cfg, h->Hp, h->Vp, h->Bp, h->MpMax, h->nPart, h->L);
+  make_layout(*cfg, h->Hp, h->Vp, h->Bp, h->MpMax, h->nPart, h->KpMax, h->L);
   if (buf->workspace_bytes < h->L.total) {
     delete h;
     return RNNLM_ERR_ARG;
@@ -600,6 +755,43 @@ int rnnlm_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, 
                                           : window_call<bf16_t>(h, x, y, T, logp, nullptr, &u, false, st);
 }
 
+namespace {
+bool nce_args_ok(rnnlm_t *h, const int32_t *noise, int32_t K, const float *lnq, float lnZ) {
+  return h && noise && lnq && K >= 1 && K <= h->cfg.K_max && (lnZ == lnZ);
+}
+}  // namespace
+
+int rnnlm_nce_train_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, const int32_t *noise, int32_t K,
+                          const float *lnq, float lnZ, float lr, float *J, double *sum_J, void *stream) {
+  if (!window_args_ok(h, x, y, T) || !nce_args_ok(h, noise, K, lnq, lnZ) || !(lr == lr)) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  UpdateTargets u{h->buf.E, h->buf.U, h->buf.Wo, h->buf.b, 1.0f, lr, true, true};
+  NceCall n{noise, K, lnq, lnZ, J};
+  return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, nullptr, sum_J, &u, true, st, &n)
+                                          : window_call<bf16_t>(h, x, y, T, nullptr, sum_J, &u, true, st, &n);
+}
+
+int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, const int32_t *noise, int32_t K,
+                         const float *lnq, float lnZ, float *dE, float *dU, float *dWo, float *db, float *J,
+                         void *stream) {
+  if (!window_args_ok(h, x, y, T) || !nce_args_ok(h, noise, K, lnq, lnZ) || !dE || !dU || !dWo || !db)
+    return RNNLM_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(dE) | reinterpret_cast<uintptr_t>(dU) | reinterpret_cast<uintptr_t>(dWo) |
+       reinterpret_cast<uintptr_t>(db)) & 15)
+    return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const long nE = (long)h->cfg.V * h->cfg.H;
+  const unsigned fb = (unsigned)std::min<long>(blocks_for(nE, 256), 65535);
+  hipLaunchKernelGGL(fill_kernel<float>, dim3(fb), dim3(256), 0, st, dE, nE, 0.0f);
+  hipLaunchKernelGGL(fill_kernel<float>, dim3(fb), dim3(256), 0, st, dWo, nE, 0.0f);
+  hipLaunchKernelGGL(fill_kernel<float>, dim3(blocks_for(h->cfg.V, 256)), dim3(256), 0, st, db, (long)h->cfg.V, 0.0f);
+  HIP_TRY(hipGetLastError());
+  UpdateTargets u{dE, dU, dWo, db, 0.0f, -1.0f, false, false};
+  NceCall n{noise, K, lnq, lnZ, J};
+  return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, nullptr, nullptr, &u, false, st, &n)
+                                          : window_call<bf16_t>(h, x, y, T, nullptr, nullptr, &u, false, st, &n);
+}
+
 int rnnlm_reset_state(rnnlm_t *h, void *stream) {
   if (!h) return RNNLM_ERR_ARG;
   const long n = (long)h->cfg.B * h->cfg.H;
@@ -643,8 +835,8 @@ int rnnlm_perplexity(rnnlm_t *h, const int32_t *tok, int64_t N, int32_t T, doubl
   for (long k = 0; k < nchunks; ++k) {
     hipLaunchKernelGGL(stream_chunk_kernel, dim3(blocks_for((long)T * B, 256)), dim3(256), 0, st, tok, L, k, T, B, xt,
                        yt);
-    rc = (h->cfg.precision == RNNLM_FP32) ? forward_window<float>(h, xt, yt, T, nullptr, true, st)
-                                          : forward_window<bf16_t>(h, xt, yt, T, nullptr, true, st);
+    rc = (h->cfg.precision == RNNLM_FP32) ? forward_window<float>(h, xt, yt, T, nullptr, true, true, st)
+                                          : forward_window<bf16_t>(h, xt, yt, T, nullptr, true, true, st);
     if (rc) return rc;
     hipLaunchKernelGGL(sum_logp_kernel, dim3(1), dim3(1024), 0, st, at<float>(h, h->L.logp_int), T * B,
                        (double *)nullptr, p_running(h), p_flags(h));

@@ -186,5 +186,22 @@ def make_weights(V: int, H: int, init: str, scale: float, seed: int):
     return E, U, Wo, b
 
 
+def unigram_noise(tok: np.ndarray, V: int):
+    """Noise distribution for a contrastive criterion: the add-one-smoothed unigram of a token array.
+
+    Returns (lnq[V] float32, thr[V] uint64): log-probabilities as both sides consume them, and the
+    integer thresholds noise words are drawn with."""
+    counts = np.bincount(tok, minlength=V).astype(np.float64) + 1.0
+    q = counts / counts.sum()
+    return np.log(q).astype(np.float32), _thresholds(q)
+
+
+def noise_words(thr: np.ndarray, K: int, seed: int, window: int) -> np.ndarray:
+    """K noise ids for window number `window`, drawn i.i.d. from the thresholds' distribution: draw j
+    of window k is a pure function of (seed, k*K + j)."""
+    u = counter_u64(seed, window * K, K)
+    return sample_from_thresholds(thr, u).astype(np.int32)
+
+
 def sha256_of(a: np.ndarray) -> str:
     return hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()

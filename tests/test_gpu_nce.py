@@ -1,0 +1,175 @@
+"""GPU parity of the noise-contrastive training calls (Sec. 4.2 criterion) against the fp64 oracle,
+through the C ABI, on the same seeded inputs.  Tolerances as for the normalised criterion: fp32 path
+per-position losses |d| <= 1e-4*|ref| + 1e-6 and gradients per tensor 1e-3 (max and l2); bf16 path mean
+loss within 1e-2 relative and gradients within 2e-2 of each tensor's scale."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_1502_00512_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+FP32, BF16 = binding.RNNLM_FP32, binding.RNNLM_BF16_FP32MASTER
+
+
+def dev(a):
+    return torch.as_tensor(np.ascontiguousarray(a)).cuda()
+
+
+def setup(V, H, B, T, K, precision, seed, scale=0.3, bias_scale=0.5, K_max=None, init="uniform"):
+    E, U, Wo, b = synth.make_weights(V, H, init, scale, seed)
+    if bias_scale:
+        b = synth.uniform_weights((V,), -bias_scale, bias_scale, seed + 99)
+    g = binding.Rnnlm(E, U, Wo, b, B, T, precision, K_max=K if K_max is None else K_max)
+    o = O.Model.from_weights(E, U, Wo, b, B)
+    tok = synth.zipf_tokens(3 * B * T + B + 1, V, 1.1, seed + 5)
+    lnq, thr = synth.unigram_noise(tok, V)
+    return g, o, tok, lnq, thr
+
+
+def check_rel(got, ref, rel=1e-4, abs_=1e-6):
+    got = got.detach().cpu().numpy().astype(np.float64)
+    bad = np.abs(got - ref) > rel * np.abs(ref) + abs_
+    assert not bad.any(), f"max |d| = {np.abs(got - ref).max():.3e}"
+
+
+def check_grad(name, got, ref, rel=1e-3):
+    got = got.detach().cpu().numpy().astype(np.float64)
+    d = got - ref
+    assert np.isfinite(got).all(), name
+    assert np.abs(d).max() <= rel * np.abs(ref).max(), f"{name}: max {np.abs(d).max():.3e} vs {np.abs(ref).max():.3e}"
+    assert np.linalg.norm(d) <= rel * np.linalg.norm(ref), f"{name}: l2 {np.linalg.norm(d):.3e} vs {np.linalg.norm(ref):.3e}"
+
+
+SHAPES = [
+    # V, H, B, T, K   (cfg1 shape; ragged everything; several tiles + ragged tails; K = 1; K > 256; T = 1)
+    (1000, 64, 4, 8, 16),
+    (777, 50, 5, 7, 13),
+    (3001, 200, 33, 3, 300),
+    (10000, 256, 32, 10, 128),
+    (300, 130, 3, 1, 1),
+    (520, 96, 70, 2, 257),
+]
+
+
+@pytest.mark.parametrize("V,H,B,T,K", SHAPES)
+def test_nce_grad_chunk_fp32(V, H, B, T, K):
+    g, o, tok, lnq, thr = setup(V, H, B, T, K, FP32, seed=3 * V + H)
+    lnZ = 0.4
+    x, y = O.stream_chunk(tok, B, T, 0)
+    g.rnnlm_forward_logprob(dev(x), dev(y))      # non-zero carried state on both sides
+    O.forward_logprob(o, x, y)
+    x, y = O.stream_chunk(tok, B, T, 1)
+    noise = synth.noise_words(thr, K, 77, 1)
+    noise[0] = y[0, 0]                           # a noise word equal to a target
+    if K > 2:
+        noise[-1] = noise[1]                     # a repeated noise word
+    before = [t.clone() for t in (g.E, g.U, g.Wo, g.b, g.h_state)]
+    r = g.rnnlm_nce_grad_chunk(dev(x), dev(y), dev(noise), dev(lnq), lnZ)
+    ref = O.nce_grad_chunk(o, x, y, noise, lnq.astype(np.float64), lnZ)
+    check_rel(r["J"], ref["J"])
+    for k in ("gE", "gU", "gWo", "gb"):
+        check_grad(k, r[k], ref[k])
+    for a, c in zip(before, (g.E, g.U, g.Wo, g.b, g.h_state)):
+        assert torch.equal(a, c)
+    untouched = np.setdiff1d(np.arange(V), np.concatenate([y.ravel(), noise]))
+    assert not r["gWo"].cpu().numpy()[untouched].any() and not r["gb"].cpu().numpy()[untouched].any()
+    g.rnnlm_check()
+
+
+@pytest.mark.parametrize("V,H,B,T,K,W", [(1000, 64, 4, 8, 16, 10), (2500, 160, 20, 5, 100, 6)])
+def test_nce_train_chunks_fp32(V, H, B, T, K, W):
+    lr, lnZ = 0.1, math.log(V) * 0.5
+    g, o, tok, lnq, thr = setup(V, H, B, T, K, FP32, seed=17, scale=0.1, bias_scale=0.0)
+    tok = synth.zipf_tokens(W * B * T + B + 1, V, 1.1, 18)
+    dtok, dlnq = dev(tok), dev(lnq)
+    J = torch.empty(T, B, device="cuda")
+    s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for k in range(W):
+        x, y = g.rnnlm_stream_chunk(dtok, k, T)
+        noise = synth.noise_words(thr, K, 19, k)
+        g.rnnlm_nce_train_chunk(x, y, dev(noise), dlnq, lnZ, lr, J, s)
+        xr, yr = O.stream_chunk(tok, B, T, k)
+        ref, sref = O.nce_train_chunk(o, xr, yr, noise, lnq.astype(np.float64), lnZ, lr)
+        check_rel(J, ref, rel=2e-4)
+        assert abs(s.item() - sref) <= 2e-4 * abs(sref)
+    for name, a, c in (("E", g.E, o.E), ("U", g.U, o.U), ("Wo", g.Wo, o.Wo), ("b", g.b, o.b), ("h", g.h_state, o.h)):
+        d = np.abs(a.cpu().numpy() - c).max()
+        assert d <= 1e-4 * max(1.0, np.abs(c).max()), (name, d)
+    # the normalised evaluation path sees the trained weights (compute copies were refreshed)
+    xe, ye = O.stream_chunk(tok, B, T, 0)
+    lp = g.rnnlm_forward_logprob(dev(xe), dev(ye))
+    check_rel(lp, O.forward_logprob(o, xe, ye), rel=2e-4)
+    g.rnnlm_check()
+
+
+@pytest.mark.parametrize("precision", [FP32, BF16])
+def test_nce_bitwise_determinism(precision):
+    V, H, B, T, K = 2000, 128, 16, 6, 200
+    outs = []
+    for _ in range(2):
+        g, o, tok, lnq, thr = setup(V, H, B, T, K, precision, seed=23, scale=0.1)
+        dtok, dlnq = dev(tok), dev(lnq)
+        for k in range(3):
+            x, y = g.rnnlm_stream_chunk(dtok, k, T)
+            g.rnnlm_nce_train_chunk(x, y, dev(synth.noise_words(thr, K, 29, k)), dlnq, 1.0, 0.1)
+        g.rnnlm_check()
+        outs.append([t.clone() for t in (g.E, g.U, g.Wo, g.b, g.h_state)])
+    for a, c in zip(*outs):
+        assert torch.equal(a, c)
+
+
+BF16_SHAPES = [(3000, 256, 32, 8, 256), (1000, 1100, 8, 3, 100), (5000, 512, 64, 10, 1000)]
+
+
+@pytest.mark.parametrize("V,H,B,T,K", BF16_SHAPES)
+def test_nce_bf16_loss_and_gradients(V, H, B, T, K):
+    g, o, tok, lnq, thr = setup(V, H, B, T, K, BF16, seed=V + K, scale=0.1, bias_scale=0.2)
+    lnZ = 2.0
+    x, y = O.stream_chunk(tok, B, T, 0)
+    noise = synth.noise_words(thr, K, 31, 0)
+    r = g.rnnlm_nce_grad_chunk(dev(x), dev(y), dev(noise), dev(lnq), lnZ)
+    ref = O.nce_grad_chunk(o, x, y, noise, lnq.astype(np.float64), lnZ)
+    assert abs(r["J"].double().mean().item() / ref["J"].mean() - 1) < 1e-2
+    for k in ("gE", "gU", "gWo", "gb"):
+        check_grad(k, r[k], ref[k], rel=2e-2)
+    g.rnnlm_check()
+
+
+def test_nce_bf16_training_tracks_oracle():
+    V, H, B, T, K, W, lr = 4000, 256, 32, 10, 256, 30, 0.2
+    g, o, tok, lnq, thr = setup(V, H, B, T, K, BF16, seed=41, scale=0.1, bias_scale=0.0)
+    tok = synth.zipf_tokens(W * B * T + B + 1, V, 1.1, 42)
+    dtok, dlnq = dev(tok), dev(lnq)
+    lnZ = math.log(V) * 0.5
+    s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ratios = []
+    for k in range(W):
+        x, y = g.rnnlm_stream_chunk(dtok, k, T)
+        noise = synth.noise_words(thr, K, 43, k)
+        g.rnnlm_nce_train_chunk(x, y, dev(noise), dlnq, lnZ, lr, None, s)
+        _, sref = O.nce_train_chunk(o, *O.stream_chunk(tok, B, T, k), noise, lnq.astype(np.float64), lnZ, lr)
+        ratios.append(s.item() / sref)
+    assert max(abs(r - 1) for r in ratios) < 1e-2, (ratios[0], ratios[-1])
+    g.rnnlm_check()
+
+
+def test_nce_arguments_are_validated():
+    g, o, tok, lnq, thr = setup(500, 32, 4, 4, 8, FP32, seed=51)
+    x, y = O.stream_chunk(tok, 4, 4, 0)
+    noise = synth.noise_words(thr, 8, 1, 0)
+    with pytest.raises(binding.RnnlmError):   # more noise words than the handle was configured for
+        g.rnnlm_nce_train_chunk(dev(x), dev(y), dev(np.concatenate([noise, noise])), dev(lnq), 0.0, 0.1)
+    g0 = binding.Rnnlm(*synth.make_weights(500, 32, "uniform", 0.1, 3), 4, 4, FP32)   # K_max = 0
+    with pytest.raises(binding.RnnlmError):
+        g0.rnnlm_nce_train_chunk(dev(x), dev(y), dev(noise), dev(lnq), 0.0, 0.1)
+    bad = noise.copy()
+    bad[3] = 500                               # out-of-range noise id: clamped, reported, never a fault
+    g.rnnlm_nce_train_chunk(dev(x), dev(y), dev(bad), dev(lnq), 0.0, 0.1)
+    with pytest.raises(binding.RnnlmError) as e:
+        g.rnnlm_check()
+    assert e.value.status == -2
