@@ -11,6 +11,10 @@ streams that are already resident in HBM.  Prints ONE JSON line:
   cpu_baseline     the fp64 oracle timed on a bounded sample of the same workload on the host cores
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3] [--stages]
+                       [--criterion softmax|nce] [--noise K]
+
+--criterion nce times the same window with the noise-contrastive output layer (the "next" row after the
+headline path): K shared noise words per window drawn from the smoothed unigram of the token array.
 """
 from __future__ import annotations
 
@@ -26,6 +30,7 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6   # MI355X published dense bf16 MFMA peak
 PEAK_FP32_TFLOPS = 157.3    # MI355X published fp32 matrix peak
+PEAK_HBM_GBS = 8000.0       # MI355X published HBM3E bandwidth
 
 
 def log(*a):
@@ -40,6 +45,9 @@ def main() -> int:
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--stages", action="store_true", help="also time every stage (adds event overhead)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--criterion", choices=["softmax", "nce"], default="softmax",
+                    help="output criterion: full normalised softmax (headline metric) or noise-contrastive estimation")
+    ap.add_argument("--noise", type=int, default=1024, help="noise words per window for --criterion nce")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (counter calibration for profiler runs)")
     args = ap.parse_args()
@@ -67,8 +75,16 @@ def main() -> int:
     log(f"[bench] {cfg.name}: V={V} H={H} B={B} T={T} N={N} inputs generated in {time.time() - t0:.1f}s "
         f"tokens sha256 {synth.sha256_of(tok)[:16]}")
 
-    g = binding.Rnnlm(E, U, Wo, b, B, T, precision)
+    nce = args.criterion == "nce"
+    g = binding.Rnnlm(E, U, Wo, b, B, T, precision, K_max=args.noise if nce else 0)
     dtok = torch.as_tensor(tok).cuda()
+    if nce:
+        # noise distribution = smoothed unigram of the corpus; the draws of every window, generated up front
+        lnq, thr = synth.unigram_noise(tok, V)
+        dlnq = torch.as_tensor(lnq).cuda()
+        dnoise = torch.as_tensor(np.stack([synth.noise_words(thr, args.noise, cfg.data_seed + 7, k)
+                                           for k in range(total_steps)])).cuda()
+        lnZ = float(np.log(V))  # scores start near 0: a constant normaliser of ln V makes them near-normalised
     x = torch.empty(T, B, dtype=torch.int32, device="cuda")
     y = torch.empty(T, B, dtype=torch.int32, device="cuda")
     sum_logp = torch.zeros(1, dtype=torch.float64, device="cuda")
@@ -76,15 +92,19 @@ def main() -> int:
 
     def step(k):
         g.rnnlm_stream_chunk(dtok, k, T, x, y, stream)
-        g.rnnlm_train_chunk(x, y, cfg.lr, None, sum_logp, stream)
+        if nce:
+            g.rnnlm_nce_train_chunk(x, y, dnoise[k % total_steps], dlnq, lnZ, cfg.lr, None, sum_logp, stream)
+        else:
+            g.rnnlm_train_chunk(x, y, cfg.lr, None, sum_logp, stream)
 
     stage_ids = {n: i for i, n in enumerate(binding.STAGES)}
-    gemm_stages = ["out_fwd", "out_bwd_h", "out_bwd_w"]
+    gemm_stages = ["rnn_fwd", "rnn_bwd", "nce_update"] if nce else ["out_fwd", "out_bwd_h", "out_bwd_w"]
 
     for k in range(args.warmup):
         step(k)
     torch.cuda.synchronize()
-    first_loss = -sum_logp.item() / M if args.warmup else float("nan")
+    sign = 1.0 if nce else -1.0  # noise-contrastive calls return the loss itself, the others log-probabilities
+    first_loss = sign * sum_logp.item() / M if args.warmup else float("nan")
 
     # timed region: K steps, the three output-layer contractions bracketed by HIP events
     mask = sum(1 << stage_ids[n] for n in gemm_stages)
@@ -96,7 +116,7 @@ def main() -> int:
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     g.rnnlm_check()
-    last_loss = -sum_logp.item() / M
+    last_loss = sign * sum_logp.item() / M
     gemm_ms = {}
     for n in gemm_stages:
         ms, cnt = g.rnnlm_profile_read(stage_ids[n])
@@ -128,19 +148,51 @@ def main() -> int:
     measured = g.rnnlm_measure_peaks(stream)
 
     words_per_s = args.steps * M / dt
-    flops_word = 6.0 * H * (V + H)
     peak = PEAK_BF16_TFLOPS if cfg.precision == "bf16" else PEAK_FP32_TFLOPS
-    gemm_flops = 2.0 * H * V * M  # algorithmic flops of each output-layer contraction per window
     dominant = max(gemm_ms, key=gemm_ms.get)
-    achieved = gemm_flops / (gemm_ms[dominant] * 1e-3) / 1e12
-    out_gemm_frac = 3 * gemm_flops / (sum(gemm_ms.values()) * 1e-3) / 1e12 / peak
+    extra = {}
+    if nce:
+        Kn = args.noise
+        flops_word = 6.0 * H * (Kn + 1 + H)  # K+1 scored words per position instead of V
+        # algorithmic work per launch of the three longest stages: the recurrent kernels are contractions
+        # (2 H^2 per position and direction), the row update moves the touched rows (4 B per element read from
+        # the gradient panel or hidden states, 10 B per element for the fp32 master read-modify-write and the
+        # bf16 copy, one row per list entry)
+        work = {"rnn_fwd": ("mfma", 2.0 * H * H * M), "rnn_bwd": ("mfma", 2.0 * H * H * (M - B)),
+                "nce_update": ("hbm", (Kn + M) * H * 14.0)}
+        bound, amount = work[dominant]
+        if bound == "mfma":
+            achieved = amount / (gemm_ms[dominant] * 1e-3) / 1e12
+            roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
+                        "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None}
+        else:
+            achieved = amount / (gemm_ms[dominant] * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                        "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None}
+        extra["stage_ms_timed"] = {k: round(v, 4) for k, v in gemm_ms.items()}
+        extra["noise_words"] = Kn
+        criterion = f"noise-contrastive output ({Kn} shared noise words per window, lnZ = ln V)"
+        metric = "training words/sec (fwd+BPTT+SGD, noise-contrastive criterion) at 1 MI355X"
+    else:
+        flops_word = 6.0 * H * (V + H)
+        gemm_flops = 2.0 * H * V * M  # algorithmic flops of each output-layer contraction per window
+        achieved = gemm_flops / (gemm_ms[dominant] * 1e-3) / 1e12
+        out_gemm_frac = 3 * gemm_flops / (sum(gemm_ms.values()) * 1e-3) / 1e12 / peak
+        roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                    "traffic": measured_traffic(cfg.name, dominant)}
+        extra["output_gemms_mfma_frac"] = round(out_gemm_frac, 4)
+        extra["gemm_ms"] = {k: round(v, 4) for k, v in gemm_ms.items()}
+        criterion = "full softmax"
+        metric = "training words/sec (fwd+BPTT+SGD) at 1 MI355X"
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(cfg, E, U, Wo, b, tok)
+        cpu = cpu_baseline(cfg, E, U, Wo, b, tok,
+                           (synth.noise_words(thr, args.noise, cfg.data_seed + 7, 0), lnq, lnZ) if nce else None)
 
     res = {
-        "metric": "training words/sec (fwd+BPTT+SGD) at 1 MI355X",
+        "metric": metric,
         "value": round(words_per_s, 1),
         "unit": "words/s",
         "n_gpus": 1,
@@ -153,17 +205,14 @@ def main() -> int:
         "dtype": cfg.precision if cfg.precision == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: Elman RNNLM V={V} H={H}, {B} streams x BPTT {T}, Zipf({cfg.zipf_s}) tokens, "
-                               f"full softmax + SGD lr={cfg.lr}", "V": V, "H": H, "B": B, "T": T, "tokens": int(N)},
+                               f"{criterion} + SGD lr={cfg.lr}", "V": V, "H": H, "B": B, "T": T, "tokens": int(N)},
         "whole_path_mfma_frac": round(words_per_s * flops_word / (peak * 1e12), 4),
-        "output_gemms_mfma_frac": round(out_gemm_frac, 4),
-        "gemm_ms": {k: round(v, 4) for k, v in gemm_ms.items()},
         "loss_first_last": [round(first_loss, 4), round(last_loss, 4)],
-        "roofline": {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
-                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "traffic": measured_traffic(cfg.name, dominant)},
+        "roofline": roofline,
         "cpu_baseline": cpu,
         "measured_peaks": {k: round(v, 1) for k, v in measured.items()},
     }
+    res.update(extra)
     if stage_ms is not None:
         res["stage_ms"] = stage_ms
     print(json.dumps(res), flush=True)
@@ -180,9 +229,10 @@ def measured_traffic(workload, kernel):
         return None
 
 
-def cpu_baseline(cfg, E, U, Wo, b, tok):
+def cpu_baseline(cfg, E, U, Wo, b, tok, nce=None):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload: the first window cut
-    to as many leading timesteps as fit about 10-30 s of CPU work."""
+    to as many leading timesteps as fit about 10-30 s of CPU work.  nce = (noise, lnq, lnZ) times the
+    noise-contrastive step instead of the normalised one."""
     import numpy as np
     from oracle import oracle as O
     V, H, B, T = cfg.V, cfg.H, cfg.B, cfg.T
@@ -192,7 +242,10 @@ def cpu_baseline(cfg, E, U, Wo, b, tok):
         m = O.Model.from_weights(E, U, Wo, b, B)
         xs, ys = np.ascontiguousarray(x[:Ts]), np.ascontiguousarray(y[:Ts])
         t0 = time.perf_counter()
-        O.train_chunk(m, xs, ys, cfg.lr)
+        if nce is None:
+            O.train_chunk(m, xs, ys, cfg.lr)
+        else:
+            O.nce_train_chunk(m, xs, ys, nce[0], nce[1].astype(np.float64), nce[2], cfg.lr)
         return time.perf_counter() - t0
 
     Ts, dt = 1, timed(1)          # calibration: one timestep of the window

@@ -126,12 +126,13 @@ __global__ void __launch_bounds__(256) nce_grad_kernel(const float *__restrict__
   if (J_out) J_out[m] = total;
 }
 
-// gcol[j] = sum over valid positions of sigmoid(S[row][j] + off[j]) * scale: the bias gradient of noise
-// word j.  Workgroup = 64 columns x 16 row groups; each group sums its rows in ascending order and the
-// 16 partial sums are added in order.
+// Bias gradient of noise word j: gcol[j] = sum over valid positions of sigmoid(S[row][j] + off[j]) * scale,
+// in two fixed-order levels.  Level 1: workgroup (column block x, row block y) = 64 columns x 16 row
+// groups over the positions m = y, y + gridDim.y, ...; each group sums its positions in ascending order,
+// the 16 group sums are added in order into part[y][j].  Level 2 adds the row blocks in order.
 __global__ void __launch_bounds__(1024) nce_colsum_kernel(const float *__restrict__ S, int Kp, int K,
                                                           const float *__restrict__ off, int Tn, int B, int Bp,
-                                                          float scale, float *__restrict__ gcol) {
+                                                          float scale, float *__restrict__ part) {
   __shared__ float sh[16][64];
   const int c = threadIdx.x & 63, grp = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + c;
@@ -139,7 +140,7 @@ __global__ void __launch_bounds__(1024) nce_colsum_kernel(const float *__restric
   if (j < K) {
     const float o = off[j];
     const int M = Tn * B;
-    for (int m = grp; m < M; m += 16) {
+    for (int m = blockIdx.y * 16 + grp; m < M; m += 16 * gridDim.y) {
       const long row = (long)(m / B) * Bp + (m % B);
       acc += logisticf_(S[row * Kp + j] + o) * scale;
     }
@@ -149,6 +150,14 @@ __global__ void __launch_bounds__(1024) nce_colsum_kernel(const float *__restric
   if (grp != 0) return;
   float tot = 0.0f;
   for (int g = 0; g < 16; ++g) tot += sh[g][c];
+  part[(long)blockIdx.y * Kp + j] = tot;
+}
+
+__global__ void nce_colsum_merge_kernel(const float *__restrict__ part, int Kp, int nblk, float *__restrict__ gcol) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= Kp) return;
+  float tot = 0.0f;
+  for (int y = 0; y < nblk; ++y) tot += part[(long)y * Kp + j];
   gcol[j] = tot;
 }
 
@@ -170,8 +179,10 @@ __global__ void __launch_bounds__(256) nce_target_dhs_kernel(const T *__restrict
 // Update of the touched rows of Wo, atomic-free and order-fixed:
 //   out[w][:] = alpha*Wo[w][:] - lr * ( sum_{noise entries e of w} G[e][:] + sum_{target entries} ct*Hs[row][:] )
 // blockIdx.x = run of equal ids in the sorted update list (exits when >= *nseg), blockIdx.y = block of
-// 256*VEC columns.  The run's members are dealt round-robin to 4 partial sums (each in ascending list
+// 64*VEC columns.  The run's members are dealt round-robin to 16 partial sums (each in ascending list
 // order) which are then added in order.  Also refreshes the compute copy of the row when Wc != nullptr.
+// The first column block also updates the word's bias the same way:
+//   b_out[w] = alpha*b[w] - lr * (sum of gcol over w's noise entries + sum of ct over its target entries).
 template <typename T, int VEC>
 __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__restrict__ G, const T *__restrict__ Hs1,
                                                               int Hp, int H, int K, int B, int Bp,
@@ -181,9 +192,12 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
                                                               const int32_t *__restrict__ seg_start,
                                                               const int32_t *__restrict__ nseg,
                                                               const float *__restrict__ W, float *__restrict__ out,
-                                                              T *__restrict__ Wc, float alpha, float lr) {
-  constexpr int PARTS = 4, LANES = 256;
+                                                              T *__restrict__ Wc, const float *__restrict__ gcol,
+                                                              const float *__restrict__ b, float *__restrict__ b_out,
+                                                              float alpha, float lr) {
+  constexpr int PARTS = 16, LANES = 64;
   __shared__ float sh[PARTS][LANES * VEC];
+  __shared__ float shb[PARTS];
   const int g = blockIdx.x;
   if (g >= *nseg) return;
   const int lane = threadIdx.x % LANES, partn = threadIdx.x / LANES;
@@ -192,62 +206,96 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
   float acc[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
-  if (col < H) {
-    for (int r = r0 + partn; r < r1; r += PARTS) {
-      const int ent = perm[r];
-      if (ent < K) {
+  float bacc = 0.0f;  // every lane of a part walks the same entries, so each holds the part's bias sum
+  const bool live = col < H;
+  // one member: its row (times its coefficient) and its bias term
+  auto fetch = [&](int r, float (&v)[VEC], float &bv) {
+    const int ent = perm[r];
+    if (ent < K) {
+      bv = gcol[ent];
+      if (live) {
         const float *src = G + (long)ent * Hp + col;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] += src[e];
-      } else {
-        const int m = ent - K;
-        const long row = (long)(m / B) * Bp + (m % B);
-        const float c = ct[row];
+        for (int e = 0; e < VEC; ++e) v[e] = src[e];
+      }
+    } else {
+      const int m = ent - K;
+      const long row = (long)(m / B) * Bp + (m % B);
+      const float c = ct[row];
+      bv = c;
+      if (live) {
         const T *src = Hs1 + row * Hp + col;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] = fmaf(c, to_f32(src[e]), acc[e]);
+        for (int e = 0; e < VEC; ++e) v[e] = c * to_f32(src[e]);
       }
     }
+  };
+  int r = r0 + partn;
+  for (; r + 3 * PARTS < r1; r += 4 * PARTS) {  // four members at a time: their loads are independent
+    float v[4][VEC], bv[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[q][e] = 0.0f;
+      fetch(r + q * PARTS, v[q], bv[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      bacc += bv[q];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[e] += v[q][e];
+    }
+  }
+  for (; r < r1; r += PARTS) {
+    float v[VEC], bv;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) v[e] = 0.0f;
+    fetch(r, v, bv);
+    bacc += bv;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] += v[e];
   }
 #pragma unroll
   for (int e = 0; e < VEC; ++e) sh[partn][lane * VEC + e] = acc[e];
+  if (lane == 0) shb[partn] = bacc;
   __syncthreads();
-  if (partn != 0 || col >= H) return;
+  if (blockIdx.y == 0 && threadIdx.x == 0) {
+    const int wb = ids[perm[r0]];
+    float tot = shb[0];
+    for (int q = 1; q < PARTS; ++q) tot += shb[q];
+    b_out[wb] = ((alpha != 0.0f) ? alpha * b[wb] : 0.0f) - lr * tot;
+  }
+  if (partn != 0 || !live) return;
 #pragma unroll
   for (int q = 1; q < PARTS; ++q)
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[e] += sh[q][lane * VEC + e];
   const int w = ids[perm[r0]];
   const long idx = (long)w * H + col;
+  if constexpr (VEC == 4) {  // H % 4 == 0: 16-byte accesses to the master row
+    f32x4_t v = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (alpha != 0.0f) v = *reinterpret_cast<const f32x4_t *>(W + idx) * alpha;
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) {
-    const float v = ((alpha != 0.0f) ? alpha * W[idx + e] : 0.0f) - lr * acc[e];
-    out[idx + e] = v;
-    if (Wc) Wc[(long)w * Hp + col + e] = from_f32<T>(v);
-  }
-}
-
-// b_out[w] = alpha*b[w] - lr * (sum of gcol over w's noise entries + sum of ct over its target entries),
-// one thread per run, members added in list order.
-__global__ void nce_bias_update_kernel(const float *__restrict__ gcol, const float *__restrict__ ct, int K, int B,
-                                       int Bp, const int32_t *__restrict__ ids, const int32_t *__restrict__ perm,
-                                       const int32_t *__restrict__ seg_start, const int32_t *__restrict__ nseg,
-                                       const float *__restrict__ b, float *__restrict__ b_out, float alpha, float lr) {
-  const int g = blockIdx.x * blockDim.x + threadIdx.x;
-  if (g >= *nseg) return;
-  const int r0 = seg_start[g], r1 = seg_start[g + 1];
-  float acc = 0.0f;
-  for (int r = r0; r < r1; ++r) {
-    const int ent = perm[r];
-    if (ent < K) {
-      acc += gcol[ent];
-    } else {
-      const int m = ent - K;
-      acc += ct[(long)(m / B) * Bp + (m % B)];
+    for (int e = 0; e < 4; ++e) v[e] -= lr * acc[e];
+    *reinterpret_cast<f32x4_t *>(out + idx) = v;
+    if (Wc) {
+      if constexpr (sizeof(T) == 2) {
+        bf16x4_t hv;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) hv[e] = (bf16_t)v[e];
+        *reinterpret_cast<bf16x4_t *>(Wc + (long)w * Hp + col) = hv;
+      } else {
+        *reinterpret_cast<f32x4_t *>(Wc + (long)w * Hp + col) = v;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float v = ((alpha != 0.0f) ? alpha * W[idx + e] : 0.0f) - lr * acc[e];
+      out[idx + e] = v;
+      if (Wc) Wc[(long)w * Hp + col + e] = from_f32<T>(v);
     }
   }
-  const int w = ids[perm[r0]];
-  b_out[w] = ((alpha != 0.0f) ? alpha * b[w] : 0.0f) - lr * acc;
 }
 
 }  // namespace rnnlm_dev

@@ -394,8 +394,13 @@ int nce_forward(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
   hipLaunchKernelGGL(nce_grad_kernel<T>, dim3(Mp), dim3(256), 0, st, S, Kp, K, at<float>(h, h->L.noff),
                      at<float>(h, h->L.ndt), Tn, c.B, Bp, scale, at<T>(h, h->L.dS_c), at<float>(h, h->L.nct),
                      at<float>(h, h->L.logp_int), n.J_out);
-  hipLaunchKernelGGL(nce_colsum_kernel, dim3(Kp / 64), dim3(1024), 0, st, S, Kp, K, at<float>(h, h->L.noff), Tn, c.B,
-                     Bp, scale, at<float>(h, h->L.gcol));
+  // bias-gradient column sums in two levels; the 16 x Kp level-1 partials borrow the gradient panel
+  // (Kp x Hp floats, Hp >= 256), which is written only later in the window
+  const int rowBlocks = 16;
+  hipLaunchKernelGGL(nce_colsum_kernel, dim3(Kp / 64, rowBlocks), dim3(1024), 0, st, S, Kp, K,
+                     at<float>(h, h->L.noff), Tn, c.B, Bp, scale, at<float>(h, h->L.G32));
+  hipLaunchKernelGGL(nce_colsum_merge_kernel, dim3(blocks_for(Kp, 256)), dim3(256), 0, st, at<float>(h, h->L.G32), Kp,
+                     rowBlocks, at<float>(h, h->L.gcol));
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }
@@ -456,16 +461,14 @@ int nce_update(rnnlm_t *h, int Tn, const NceCall &n, const UpdateTargets &u, hip
   hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(1024), 0, st, ids, perm, nent, 1, 1, seg, p_nseg2(h));
   T *Wc = u.refresh_copies ? at<T>(h, h->L.Wo_c) : nullptr;
   if (c.H % 4 == 0) {
-    hipLaunchKernelGGL((nce_row_update_kernel<T, 4>), dim3(nent, (c.H + 1023) / 1024), dim3(1024), 0, st, G, Hs1, Hp,
+    hipLaunchKernelGGL((nce_row_update_kernel<T, 4>), dim3(nent, (c.H + 255) / 256), dim3(1024), 0, st, G, Hs1, Hp,
                        c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
-                       u.alpha, u.lr);
+                       at<float>(h, h->L.gcol), h->buf.b, u.b, u.alpha, u.lr);
   } else {
-    hipLaunchKernelGGL((nce_row_update_kernel<T, 1>), dim3(nent, (c.H + 255) / 256), dim3(1024), 0, st, G, Hs1, Hp,
+    hipLaunchKernelGGL((nce_row_update_kernel<T, 1>), dim3(nent, (c.H + 63) / 64), dim3(1024), 0, st, G, Hs1, Hp,
                        c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
-                       u.alpha, u.lr);
+                       at<float>(h, h->L.gcol), h->buf.b, u.b, u.alpha, u.lr);
   }
-  hipLaunchKernelGGL(nce_bias_update_kernel, dim3(blocks_for(nent, 256)), dim3(256), 0, st, at<float>(h, h->L.gcol),
-                     at<float>(h, h->L.nct), K, c.B, Bp, ids, perm, seg, p_nseg2(h), h->buf.b, u.b, u.alpha, u.lr);
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }
@@ -592,6 +595,8 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     epi.lr = u.lr;
     if (sizeof(T) == 2 && (long)(Hp / BIG) * (Hp / BIG) >= 64) {
       HIP_TRY((big_gemm<T, 2, 4, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
+    } else if (Hp <= 1024) {  // small matrix: 64x64 tiles give up to 256 workgroups
+      HIP_TRY((launch_gemm<T, 64, 64, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
     } else {
       HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
     }

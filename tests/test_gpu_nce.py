@@ -173,3 +173,76 @@ def test_nce_arguments_are_validated():
     with pytest.raises(binding.RnnlmError) as e:
         g.rnnlm_check()
     assert e.value.status == -2
+
+
+# ---- full-size checks, in the launch configuration bench.py --criterion nce times -----------------------
+
+def _cfg_setup(name, K, weights="config"):
+    cfg = synth.CONFIGS[name]
+    if weights == "config":
+        E, U, Wo, b = synth.make_weights(cfg.V, cfg.H, cfg.init, cfg.init_scale, cfg.weight_seed)
+    else:  # cheaper generator for the largest shapes, same scale
+        E, U, Wo, b = synth.make_weights(cfg.V, cfg.H, "uniform", cfg.init_scale * 1.7, cfg.weight_seed)
+    g = binding.Rnnlm(E, U, Wo, b, cfg.B, cfg.T, BF16 if cfg.precision == "bf16" else FP32, K_max=K)
+    return cfg, g, (E, U, Wo, b)
+
+
+def test_cfg3_full_size_nce_window():
+    """cfg3 (V=64,000 H=1024 B=128 T=20, bf16 operands, 1024 noise words): one whole window against the
+    oracle: mean loss within 1e-2, every position's loss within 2e-2 relative, every gradient tensor within
+    2e-2 of its scale, then the SGD step itself on the touched rows and the untouched rows left alone."""
+    K = 1024
+    cfg, g, (E, U, Wo, b) = _cfg_setup("cfg3", K)
+    o = O.Model.from_weights(E, U, Wo, b, cfg.B)
+    tok = synth.make_tokens(cfg, 2_000_000)
+    lnq, thr = synth.unigram_noise(tok, cfg.V)
+    noise = synth.noise_words(thr, K, cfg.data_seed + 7, 0)
+    lnZ = math.log(cfg.V)
+    x, y = O.stream_chunk(tok, cfg.B, cfg.T, 0)
+    r = g.rnnlm_nce_grad_chunk(dev(x), dev(y), dev(noise), dev(lnq), lnZ)
+    ref = O.nce_grad_chunk(o, x, y, noise, lnq.astype(np.float64), lnZ)
+    J = r["J"].cpu().numpy().astype(np.float64)
+    assert abs(J.mean() / ref["J"].mean() - 1) < 1e-2
+    assert (np.abs(J - ref["J"]) <= 2e-2 * np.abs(ref["J"])).all()
+    for kk in ("gE", "gU", "gWo", "gb"):
+        check_grad(kk, r[kk], ref[kk], rel=2e-2)
+    Wo0, b0 = g.Wo.clone(), g.b.clone()
+    g.rnnlm_nce_train_chunk(dev(x), dev(y), dev(noise), dev(lnq), lnZ, cfg.lr)
+    assert torch.allclose(g.Wo, Wo0 - cfg.lr * r["gWo"], rtol=0, atol=1e-7)
+    assert torch.allclose(g.b, b0 - cfg.lr * r["gb"], rtol=0, atol=1e-7)
+    touched = torch.zeros(cfg.V, dtype=torch.bool, device="cuda")
+    touched[dev(np.concatenate([y.ravel(), noise])).long()] = True
+    assert torch.equal(g.Wo[~touched], Wo0[~touched]) and torch.equal(g.b[~touched], b0[~touched])
+    g.rnnlm_check()
+
+
+def test_cfg5_nce_sampled_streams():
+    """cfg5 at full shape (V=100,000 H=4096 B=256 T=32, 1024 noise words): the oracle runs three whole
+    streams of the first window one by one (the forward pass and the per-position losses of a stream do not
+    depend on the other streams); the GPU's losses for those streams must agree within 2e-2 per position
+    and 1e-2 in the mean.  Size-independent properties: finite results, rows of dWo and entries of db of
+    words that are neither target nor noise are exactly zero."""
+    K = 1024
+    cfg, g, (E, U, Wo, b) = _cfg_setup("cfg5", K, weights="uniform")
+    tok = synth.make_tokens(cfg, 4_000_000)
+    lnq, thr = synth.unigram_noise(tok, cfg.V)
+    noise = synth.noise_words(thr, K, cfg.data_seed + 7, 0)
+    lnZ = math.log(cfg.V)
+    x, y = O.stream_chunk(tok, cfg.B, cfg.T, 0)
+    r = g.rnnlm_nce_grad_chunk(dev(x), dev(y), dev(noise), dev(lnq), lnZ)
+    J = r["J"].cpu().numpy().astype(np.float64)
+    assert np.isfinite(J).all()
+    E64, U64, Wo64, b64 = (np.asarray(a, np.float64) for a in (E, U, Wo, b))
+    for s in (0, 200, 255):
+        o1 = O.Model(E64, U64, Wo64, b64, np.zeros((1, cfg.H)))
+        ref = O.nce_grad_chunk(o1, np.ascontiguousarray(x[:, s:s + 1]), np.ascontiguousarray(y[:, s:s + 1]), noise,
+                               lnq.astype(np.float64), lnZ)["J"][:, 0]
+        assert abs(J[:, s].mean() / ref.mean() - 1) < 1e-2
+        assert (np.abs(J[:, s] - ref) <= 2e-2 * np.abs(ref)).all()
+    for kk in ("gE", "gU", "gWo", "gb"):
+        assert torch.isfinite(r[kk]).all()
+    touched = torch.zeros(cfg.V, dtype=torch.bool, device="cuda")
+    touched[dev(np.concatenate([y.ravel(), noise])).long()] = True
+    assert not r["gWo"][~touched].any() and not r["gb"][~touched].any()
+    assert r["gWo"][touched].abs().sum() > 0
+    g.rnnlm_check()
