@@ -45,8 +45,10 @@ def main() -> int:
     ap.add_argument("--config", default="cfg3")
     ap.add_argument("--stages", action="store_true", help="also time every stage (adds event overhead)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--criterion", choices=["softmax", "nce"], default="softmax",
-                    help="output criterion: full normalised softmax (headline metric) or noise-contrastive estimation")
+    ap.add_argument("--criterion", choices=["softmax", "nce", "score"], default="softmax",
+                    help="softmax: training with the full normalised output (headline metric); nce: training with "
+                         "noise-contrastive estimation; score: forward-only unnormalised scoring of given next words")
+    ap.add_argument("--streams", type=int, default=0, help="override the number of parallel streams B (scoring)")
     ap.add_argument("--noise", type=int, default=1024, help="noise words per window for --criterion nce")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (counter calibration for profiler runs)")
@@ -61,7 +63,7 @@ def main() -> int:
     from paper_1502_00512_amd import binding, synth
 
     cfg = synth.CONFIGS[args.config]
-    V, H, B, T = cfg.V, cfg.H, cfg.B, cfg.T
+    V, H, B, T = cfg.V, cfg.H, (args.streams or cfg.B), cfg.T
     M = B * T
     precision = binding.RNNLM_BF16_FP32MASTER if cfg.precision == "bf16" else binding.RNNLM_FP32
     total_steps = args.steps + args.warmup
@@ -76,6 +78,7 @@ def main() -> int:
         f"tokens sha256 {synth.sha256_of(tok)[:16]}")
 
     nce = args.criterion == "nce"
+    score = args.criterion == "score"
     g = binding.Rnnlm(E, U, Wo, b, B, T, precision, K_max=args.noise if nce else 0)
     dtok = torch.as_tensor(tok).cuda()
     if nce:
@@ -88,17 +91,22 @@ def main() -> int:
     x = torch.empty(T, B, dtype=torch.int32, device="cuda")
     y = torch.empty(T, B, dtype=torch.int32, device="cuda")
     sum_logp = torch.zeros(1, dtype=torch.float64, device="cuda")
+    scores = torch.empty(T, B, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
     def step(k):
         g.rnnlm_stream_chunk(dtok, k, T, x, y, stream)
         if nce:
             g.rnnlm_nce_train_chunk(x, y, dnoise[k % total_steps], dlnq, lnZ, cfg.lr, None, sum_logp, stream)
+        elif score:
+            g.rnnlm_forward_score(x, y, float(np.log(V)), scores, stream)
         else:
             g.rnnlm_train_chunk(x, y, cfg.lr, None, sum_logp, stream)
 
     stage_ids = {n: i for i, n in enumerate(binding.STAGES)}
     gemm_stages = ["rnn_fwd", "rnn_bwd", "nce_update"] if nce else ["out_fwd", "out_bwd_h", "out_bwd_w"]
+    if score:
+        gemm_stages = ["prep", "rnn_fwd", "nce_score"]
 
     for k in range(args.warmup):
         step(k)
@@ -151,7 +159,16 @@ def main() -> int:
     peak = PEAK_BF16_TFLOPS if cfg.precision == "bf16" else PEAK_FP32_TFLOPS
     dominant = max(gemm_ms, key=gemm_ms.get)
     extra = {}
-    if nce:
+    if score:
+        flops_word = 2.0 * H * (H + 1)
+        achieved = 2.0 * H * H * M / (gemm_ms["rnn_fwd"] * 1e-3) / 1e12
+        dominant = "rnn_fwd"
+        roofline = {"bound": "mfma", "kernel": "rnn_fwd", "achieved": round(achieved, 2), "peak": peak,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None}
+        extra["stage_ms_timed"] = {k: round(v, 4) for k, v in gemm_ms.items()}
+        criterion = "forward-only unnormalised scoring of the given next words"
+        metric = "scored words/sec (forward only, unnormalised output) at 1 MI355X"
+    elif nce:
         Kn = args.noise
         flops_word = 6.0 * H * (Kn + 1 + H)  # K+1 scored words per position instead of V
         # algorithmic work per launch of the three longest stages: the recurrent kernels are contractions
@@ -187,7 +204,7 @@ def main() -> int:
         metric = "training words/sec (fwd+BPTT+SGD) at 1 MI355X"
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not score:
         cpu = cpu_baseline(cfg, E, U, Wo, b, tok,
                            (synth.noise_words(thr, args.noise, cfg.data_seed + 7, 0), lnq, lnZ) if nce else None)
 
@@ -205,7 +222,7 @@ def main() -> int:
         "dtype": cfg.precision if cfg.precision == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: Elman RNNLM V={V} H={H}, {B} streams x BPTT {T}, Zipf({cfg.zipf_s}) tokens, "
-                               f"{criterion} + SGD lr={cfg.lr}", "V": V, "H": H, "B": B, "T": T, "tokens": int(N)},
+                               f"{criterion}" + ("" if score else f" + SGD lr={cfg.lr}"), "V": V, "H": H, "B": B, "T": T, "tokens": int(N)},
         "whole_path_mfma_frac": round(words_per_s * flops_word / (peak * 1e12), 4),
         "loss_first_last": [round(first_loss, 4), round(last_loss, 4)],
         "roofline": roofline,

@@ -142,6 +142,14 @@ int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t
                          const float *lnq, float lnZ, float *dE, float *dU, float *dWo, float *db, float *J,
                          void *stream);
 
+/* Forward-only unnormalised scoring (Sec. 4.2: for rescoring the output is used without the explicit
+ * normalisation, which is what makes it fast): score[t][s] = Wo[y[t][s]].h_t + b[y[t][s]] - lnZ for the
+ * given next words only, no pass over the vocabulary; lnZ is the constant a self-normalised
+ * (noise-contrastively trained) model is read against.  Starts from h_state and advances it, so calls
+ * chain along a stream of text.  x, y: dev int32[T][B]; score: dev float[T][B]. */
+int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lnZ, float *score,
+                        void *stream);
+
 /* Perplexity (Sec. 1, Sec. 4.2: normalised output) of tok: dev int32[N]: h_state is reset to zero,
  * the array is split into B streams as in rnnlm_stream_chunk and every full window of T positions
  * is scored; *ppl (HOST) = exp(-sum logp / scored), *scored (HOST, may be NULL) = windows*B*T.

@@ -28,6 +28,7 @@ def lib():
         _lib.oracle_perplexity.restype = C.c_int
         _lib.oracle_nce_grad_chunk.restype = C.c_int
         _lib.oracle_nce_train_chunk.restype = C.c_int
+        _lib.oracle_forward_score.restype = C.c_int
         _lib.oracle_sort_segments.restype = C.c_int
         _lib.oracle_num_threads.restype = C.c_int
     return _lib
@@ -189,6 +190,17 @@ def nce_train_chunk(m: Model, x, y, noise, lnq, lnZ, lr: float):
                                         noise.size, _i(noise), _d(lnq), C.c_double(lnZ), C.c_double(lr), _d(J),
                                         C.byref(s)))
     return J, s.value
+
+
+def forward_score(m: Model, x, y, lnZ=0.0):
+    """Unnormalised scores z[y] - lnZ of the given next words, score[T][B]; advances m.h (Sec. 4.2: the
+    output as used for rescoring, without the explicit normalisation)."""
+    T = x.shape[0]
+    score = np.empty((T, m.B), np.float64)
+    _check(lib().oracle_forward_score(m.V, m.H, m.B, T, _d(m.E), _d(m.U), _d(m.Wo), _d(m.b), _d(m.h),
+                                      _i(np.ascontiguousarray(x, np.int32)), _i(np.ascontiguousarray(y, np.int32)),
+                                      C.c_double(lnZ), _d(score)))
+    return score
 
 
 def perplexity(m: Model, tok: np.ndarray, T: int):

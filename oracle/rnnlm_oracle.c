@@ -417,6 +417,29 @@ int oracle_nce_train_chunk(int V, int H, int B, int T, double *E, double *U, dou
   return rc;
 }
 
+/* Unnormalised scoring, forward only (Sec. 4.2: for rescoring the output is used without the explicit
+ * normalisation): score[t][s] = Wo[y].h_t + b[y] - lnZ for the given next words y only, with lnZ the
+ * constant a self-normalised (NCE-trained) model is read against.  Advances h in place. */
+int oracle_forward_score(int V, int H, int B, int T, const double *E, const double *U, const double *Wo,
+                         const double *b, double *h, const int32_t *x, const int32_t *y, double lnZ,
+                         double *score) {
+  if (V <= 0 || H <= 0 || B <= 0 || T <= 0 || !E || !U || !Wo || !b || !h || !x || !y || !score) return ORACLE_ERR_ARG;
+  const size_t M = (size_t)B * T;
+  if (check_tokens(x, (long)M, V) || check_tokens(y, (long)M, V)) return ORACLE_ERR_TOKEN;
+  double *Hs = (double *)malloc(sizeof(double) * M * H);
+  if (!Hs) return ORACLE_ERR_NOMEM;
+  hidden_forward(H, B, T, E, U, h, x, Hs);
+  for (size_t m = 0; m < M; ++m) {
+    const double *wo = Wo + (size_t)y[m] * H, *hm = Hs + m * H;
+    double z = b[y[m]];
+    for (int i = 0; i < H; ++i) z += wo[i] * hm[i];
+    score[m] = z - lnZ;
+  }
+  memcpy(h, Hs + (size_t)(T - 1) * B * H, sizeof(double) * (size_t)B * H);
+  free(Hs);
+  return ORACLE_OK;
+}
+
 /* Perplexity of a token array: B streams from a zero state, every full window of T
  * positions scored, PPL = exp(-sum logp / #scored).  The result does not depend on
  * T except through which tail positions are dropped. */

@@ -21,7 +21,7 @@ SYMBOLS = [
     "rnnlm_train_chunk", "rnnlm_grad_chunk", "rnnlm_perplexity", "rnnlm_reset_state",
     "rnnlm_sync_compute_copies", "rnnlm_check", "rnnlm_sort_segments", "rnnlm_status_string",
     "rnnlm_profile_enable", "rnnlm_profile_read", "rnnlm_set_barrier_spin_limit", "rnnlm_measure_peaks",
-    "rnnlm_nce_train_chunk", "rnnlm_nce_grad_chunk",
+    "rnnlm_nce_train_chunk", "rnnlm_nce_grad_chunk", "rnnlm_forward_score",
 ]
 
 STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce",
@@ -75,6 +75,7 @@ def load():
     f32 = C.c_float
     lib.rnnlm_nce_train_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, f32, vp, vp, vp]
     lib.rnnlm_nce_grad_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp]
+    lib.rnnlm_forward_score.argtypes = [vp, vp, vp, i32, f32, vp, vp]
     lib.rnnlm_profile_enable.argtypes = [vp, C.c_uint32]
     lib.rnnlm_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.rnnlm_status_string.argtypes = [C.c_int]
@@ -186,6 +187,15 @@ class Rnnlm:
         _ok(self.lib.rnnlm_perplexity(self.handle, _ptr(tok), tok.numel(), T, C.byref(ppl), C.byref(scored),
                                       _stream(stream)), "rnnlm_perplexity")
         return ppl.value, scored.value
+
+    def rnnlm_forward_score(self, x, y, lnZ: float = 0.0, score=None, stream=None):
+        import torch
+        T = x.shape[0]
+        if score is None:
+            score = torch.empty(T, self.B, dtype=torch.float32, device=self.device)
+        _ok(self.lib.rnnlm_forward_score(self.handle, _ptr(x), _ptr(y), T, lnZ, _ptr(score), _stream(stream)),
+            "rnnlm_forward_score")
+        return score
 
     def rnnlm_nce_train_chunk(self, x, y, noise, lnq, lnZ: float, lr: float, J=None, sum_J=None, stream=None):
         _ok(self.lib.rnnlm_nce_train_chunk(self.handle, _ptr(x), _ptr(y), x.shape[0], _ptr(noise), noise.numel(),

@@ -62,14 +62,16 @@ __global__ void __launch_bounds__(256) nce_gather_rows_kernel(const T *__restric
   for (int c = threadIdx.x; c < Hp / VEC; c += 256) dst[c] = (j < K) ? src[c] : zero;
 }
 
-// D of the target word of every position: dt[row] = Wo_c[y].Hs[row] + b[y] - lnZ - ln K - lnq[y].
-// One wave per padded position (4 per workgroup); lanes stride the row, then a butterfly sum.
+// Score of the target word of every position: dt[row] = Wo_c[y].Hs[row] + b[y] - shift - lnq[y]
+// (lnq == nullptr: no noise term).  One wave per padded position (4 per workgroup); lanes stride the
+// row, then a butterfly sum.  out (may be nullptr) receives the valid positions in compact order t*B + s.
 template <typename T>
 __global__ void __launch_bounds__(256) nce_target_score_kernel(const T *__restrict__ Hs1, const T *__restrict__ Wo_c,
                                                                int Hp, const int32_t *__restrict__ yp,
                                                                const float *__restrict__ b,
-                                                               const float *__restrict__ lnq, float lnZ_lnK, int rows,
-                                                               float *__restrict__ dt) {
+                                                               const float *__restrict__ lnq, float shift, int rows,
+                                                               int B, int Bp, float *__restrict__ dt,
+                                                               float *__restrict__ out) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= rows) return;
   const int y = yp[row];
@@ -82,7 +84,11 @@ __global__ void __launch_bounds__(256) nce_target_score_kernel(const T *__restri
   for (int c = lane; c < Hp; c += 64) acc = fmaf(to_f32(hrow[c]), to_f32(wrow[c]), acc);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
-  if (lane == 0) dt[row] = acc + b[y] - lnZ_lnK - lnq[y];
+  if (lane == 0) {
+    const float v = acc + b[y] - shift - (lnq ? lnq[y] : 0.0f);
+    dt[row] = v;
+    if (out) out[(row / Bp) * B + (row % Bp)] = v;
+  }
 }
 
 // Elementwise pass over one padded position (one workgroup per row of the score matrix S[Mp][Kp]):

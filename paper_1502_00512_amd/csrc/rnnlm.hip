@@ -382,7 +382,8 @@ int nce_forward(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
     hipLaunchKernelGGL(nce_gather_rows_kernel<T>, dim3(Kp), dim3(256), 0, st, at<T>(h, h->L.Wo_c), Hp,
                        at<int32_t>(h, h->L.noise_c), K, Wn);
     hipLaunchKernelGGL(nce_target_score_kernel<T>, dim3(blocks_for(Mrows, 4)), dim3(256), 0, st, Hs1,
-                       at<T>(h, h->L.Wo_c), Hp, yp, h->buf.b, n.lnq, lnZ_lnK, Mrows, at<float>(h, h->L.ndt));
+                       at<T>(h, h->L.Wo_c), Hp, yp, h->buf.b, n.lnq, lnZ_lnK, Mrows, c.B, Bp, at<float>(h, h->L.ndt),
+                       (float *)nullptr);
     HIP_TRY(hipGetLastError());
     EpiPartial epi;
     epi.part = S;
@@ -637,6 +638,20 @@ int window_call(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *l
   return rc;
 }
 
+template <typename T>
+int score_call(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float lnZ, float *score, hipStream_t st) {
+  int rc = forward_window<T>(h, x, y, Tn, nullptr, true, false, st);
+  if (rc) return rc;
+  const int Mrows = Tn * h->Bp;
+  StageTimer tm(h, RNNLM_STAGE_NCE_SCORE, st);
+  // the per-position scratch of the log-probability path holds the padded result
+  hipLaunchKernelGGL(nce_target_score_kernel<T>, dim3(blocks_for(Mrows, 4)), dim3(256), 0, st,
+                     at<T>(h, h->L.Hs_c) + (long)h->Bp * h->Hp, at<T>(h, h->L.Wo_c), h->Hp, at<int32_t>(h, h->L.yp),
+                     h->buf.b, (const float *)nullptr, lnZ, Mrows, h->cfg.B, h->Bp, at<float>(h, h->L.zy), score);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
 bool window_args_ok(rnnlm_t *h, const int32_t *x, const int32_t *y, int T) {
   return h && x && y && T >= 1 && T <= h->cfg.T_max;
 }
@@ -795,6 +810,14 @@ int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t
   NceCall n{noise, K, lnq, lnZ, J};
   return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, nullptr, nullptr, &u, false, st, &n)
                                           : window_call<bf16_t>(h, x, y, T, nullptr, nullptr, &u, false, st, &n);
+}
+
+int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lnZ, float *score,
+                        void *stream) {
+  if (!window_args_ok(h, x, y, T) || !score || !(lnZ == lnZ)) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  return (h->cfg.precision == RNNLM_FP32) ? score_call<float>(h, x, y, T, lnZ, score, st)
+                                          : score_call<bf16_t>(h, x, y, T, lnZ, score, st);
 }
 
 int rnnlm_reset_state(rnnlm_t *h, void *stream) {

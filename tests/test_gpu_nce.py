@@ -246,3 +246,45 @@ def test_cfg5_nce_sampled_streams():
     assert not r["gWo"][~touched].any() and not r["gb"][~touched].any()
     assert r["gWo"][touched].abs().sum() > 0
     g.rnnlm_check()
+
+
+# ---- forward-only unnormalised scoring (Sec. 4.2: the output as used for rescoring) ----------------------
+
+@pytest.mark.parametrize("V,H,B,T,precision,tol", [(1000, 64, 1, 8, FP32, 1e-4), (3001, 200, 5, 7, FP32, 1e-4),
+                                                   (10000, 256, 16, 10, FP32, 1e-4), (520, 96, 70, 2, FP32, 1e-4),
+                                                   (5000, 512, 8, 12, BF16, 2e-2), (4000, 1100, 3, 4, BF16, 2e-2)])
+def test_forward_score(V, H, B, T, precision, tol):
+    """Small-batch scoring of given next words against the oracle, two chained windows (carried state)."""
+    E, U, Wo, b = synth.make_weights(V, H, "uniform", 0.3, V + H)
+    b = synth.uniform_weights((V,), -0.5, 0.5, 7)
+    g = binding.Rnnlm(E, U, Wo, b, B, T, precision)
+    o = O.Model.from_weights(E, U, Wo, b, B)
+    tok = synth.zipf_tokens(2 * B * T + B + 1, V, 1.1, 3)
+    lnZ = 1.25
+    for k in range(2):
+        x, y = O.stream_chunk(tok, B, T, k)
+        got = g.rnnlm_forward_score(dev(x), dev(y), lnZ).cpu().numpy().astype(np.float64)
+        ref = O.forward_score(o, x, y, lnZ)
+        scale = max(1.0, np.abs(ref).max())
+        assert np.abs(got - ref).max() <= tol * scale, (k, np.abs(got - ref).max())
+    assert np.abs(g.h_state.cpu().numpy() - o.h).max() < (1e-5 if precision == FP32 else 2e-2)
+    g.rnnlm_check()
+
+
+def test_forward_score_matches_the_normalised_path_up_to_the_log_partition():
+    """score + lnZ - logp is the same for every next word asked for at a position (it is the position's
+    log-partition): two calls with different targets from the same state."""
+    V, H, B, T = 2000, 128, 4, 6
+    E, U, Wo, b = synth.make_weights(V, H, "uniform", 0.3, 5)
+    g = binding.Rnnlm(E, U, Wo, b, B, T, FP32)
+    tok = synth.zipf_tokens(4 * B * T + 1, V, 1.1, 6)
+    x, y1 = O.stream_chunk(tok, B, T, 0)
+    _, y2 = O.stream_chunk(tok, B, T, 1)
+    parts = []
+    for y in (y1, y2):
+        g.rnnlm_reset_state()
+        s = g.rnnlm_forward_score(dev(x), dev(y), 0.0)
+        g.rnnlm_reset_state()
+        lp = g.rnnlm_forward_logprob(dev(x), dev(y))
+        parts.append((s - lp).cpu().numpy())
+    assert np.abs(parts[0] - parts[1]).max() < 1e-4

@@ -277,3 +277,50 @@ def test_out_of_range_noise_is_rejected():
     x, y = rand_tokens(5, 2, 1, 72)
     with pytest.raises(ValueError):
         O.nce_grad_chunk(m, x, y, np.array([0, 5], np.int32), np.log(rand_q(5, 73)))
+
+
+# ---- unnormalised forward scoring (Sec. 4.2: the output as used for rescoring) -------------------------
+
+def test_score_worked_example():
+    """On the hand-computed model the scores are logs of small integers: z0 = [ln4, ln27, ln2],
+    z1 = [ln8, ln3, ln2]."""
+    x = np.array([[0], [1]], np.int32)
+    for y, want in (([1, 2], [math.log(27), math.log(2)]), ([0, 0], [math.log(4), math.log(8)]),
+                    ([2, 1], [math.log(2), math.log(3)])):
+        m = worked_model()
+        s = O.forward_score(m, x, np.array(y, np.int32).reshape(2, 1), lnZ=0.5)
+        assert s.ravel() == pytest.approx([w - 0.5 for w in want], abs=1e-12)
+        assert m.h.ravel() == pytest.approx([0.75, 0.25], abs=1e-13)
+
+
+def test_score_differs_from_log_probability_by_the_log_partition():
+    """score + lnZ - logp is the position's log-partition, the same whatever next word is asked for; it
+    equals logsumexp of the scores of all words."""
+    V, H, B, T = 13, 5, 3, 4
+    m = rand_model(V, H, B, 81, h_scale=1.0)
+    x, _ = rand_tokens(V, T, B, 82)
+    allz = np.empty((V, T, B))
+    lses = []
+    for w in range(V):
+        y = np.full((T, B), w, np.int32)
+        s = O.forward_score(m.copy(), x, y, lnZ=0.0)
+        lp = O.forward_logprob(m.copy(), x, y)
+        allz[w] = s
+        lses.append(s - lp)
+    for w in range(1, V):
+        assert lses[w] == pytest.approx(lses[0], rel=1e-12, abs=1e-12)
+    from scipy.special import logsumexp
+    assert lses[0] == pytest.approx(logsumexp(allz, axis=0), rel=1e-12)
+
+
+def test_score_advances_state_like_the_normalised_pass_and_chains():
+    V, H, B, T = 9, 4, 2, 6
+    m = rand_model(V, H, B, 91, h_scale=1.0)
+    x, y = rand_tokens(V, T, B, 92)
+    a, b_ = m.copy(), m.copy()
+    whole = O.forward_score(a, x, y, 0.3)
+    O.forward_logprob(b_, x, y)
+    assert np.array_equal(a.h, b_.h)
+    c = m.copy()
+    parts = np.concatenate([O.forward_score(c, x[t:t + 1], y[t:t + 1], 0.3) for t in range(T)])
+    assert parts == pytest.approx(whole, rel=1e-13)
