@@ -29,6 +29,7 @@ def lib():
         _lib.oracle_nce_grad_chunk.restype = C.c_int
         _lib.oracle_nce_train_chunk.restype = C.c_int
         _lib.oracle_forward_score.restype = C.c_int
+        _lib.oracle_train_chunk_rmsprop.restype = C.c_int
         _lib.oracle_sort_segments.restype = C.c_int
         _lib.oracle_num_threads.restype = C.c_int
     return _lib
@@ -147,6 +148,38 @@ def train_chunk(m: Model, x, y, lr: float):
     _check(lib().oracle_train_chunk(m.V, m.H, m.B, T, _d(m.E), _d(m.U), _d(m.Wo), _d(m.b), _d(m.h),
                                     _i(np.ascontiguousarray(x, np.int32)), _i(np.ascontiguousarray(y, np.int32)),
                                     C.c_double(lr), _d(logp), C.byref(s)))
+    return logp, s.value
+
+
+@dataclass
+class RmspropState:
+    """Running means of squared gradients (Sec. 4.2 rmsprop): one value per word for E and Wo
+    (rE[V], rWo[V]), one per element for U and b (rU[H][H], rb[V])."""
+    rE: np.ndarray
+    rU: np.ndarray
+    rWo: np.ndarray
+    rb: np.ndarray
+
+    @classmethod
+    def filled(cls, V, H, value):
+        return cls(np.full(V, value, np.float64), np.full((H, H), value, np.float64), np.full(V, value, np.float64),
+                   np.full(V, value, np.float64))
+
+    def copy(self):
+        return RmspropState(self.rE.copy(), self.rU.copy(), self.rWo.copy(), self.rb.copy())
+
+
+def train_chunk_rmsprop(m: Model, st: RmspropState, x, y, lr: float, rho: float, eps: float):
+    """One rmsprop-scaled SGD step on one window, in place (model and statistics).
+    Returns (logp[T][B], sum_logp)."""
+    T = x.shape[0]
+    logp = np.empty((T, m.B), np.float64)
+    s = C.c_double(0.0)
+    _check(lib().oracle_train_chunk_rmsprop(m.V, m.H, m.B, T, _d(m.E), _d(m.U), _d(m.Wo), _d(m.b), _d(m.h),
+                                            _i(np.ascontiguousarray(x, np.int32)),
+                                            _i(np.ascontiguousarray(y, np.int32)), C.c_double(lr), C.c_double(rho),
+                                            C.c_double(eps), _d(st.rE), _d(st.rU), _d(st.rWo), _d(st.rb), _d(logp),
+                                            C.byref(s)))
     return logp, s.value
 
 

@@ -281,6 +281,66 @@ int oracle_train_chunk(int V, int H, int B, int T, double *E, double *U, double 
   return rc;
 }
 
+/* ---- rmsprop (Sec. 4.2: the paper trains with SGD and rmsprop, smoothing constant 0.9995) -----------
+ *
+ * One training step on one window with the rmsprop scaling of the SGD step.  Readings where the paper
+ * is silent: a running mean of squared gradients  r <- rho*r + (1-rho)*s  is updated first and the step
+ * is  theta <- theta - lr * g / (sqrt(r) + eps);  for the state-to-state matrix U and the output bias
+ * b, s = g^2 element by element (rU[H][H], rb[V]); for the input-to-state and state-to-output matrices
+ * E and Wo each WORD has a single value, s = the mean over the H units of the squared gradient of that
+ * word's row (rE[V], rWo[V]: Sec. 4.2 averages over the nstate units so that each word has one value).
+ * Rows whose gradient is zero (words not in the window) keep their weights and their value decays by
+ * rho like any other.  The statistics are caller-initialised state, updated in place. */
+int oracle_train_chunk_rmsprop(int V, int H, int B, int T, double *E, double *U, double *Wo, double *b, double *h,
+                               const int32_t *x, const int32_t *y, double lr, double rho, double eps, double *rE,
+                               double *rU, double *rWo, double *rb, double *logp, double *sum_logp) {
+  if (V <= 0 || H <= 0 || B <= 0 || T <= 0 || !rE || !rU || !rWo || !rb) return ORACLE_ERR_ARG;
+  const size_t nVH = (size_t)V * H, nHH = (size_t)H * H;
+  double *gE = (double *)malloc(sizeof(double) * nVH);
+  double *gWo = (double *)malloc(sizeof(double) * nVH);
+  double *gU = (double *)malloc(sizeof(double) * nHH);
+  double *gb = (double *)malloc(sizeof(double) * (size_t)V);
+  double *hn = (double *)malloc(sizeof(double) * (size_t)B * H);
+  int rc = ORACLE_ERR_NOMEM;
+  if (gE && gWo && gU && gb && hn)
+    rc = oracle_grad_chunk(V, H, B, T, E, U, Wo, b, h, x, y, logp, gE, gU, gWo, gb, hn, NULL, NULL, NULL, NULL);
+  if (rc == ORACLE_OK) {
+    /* one value per word for E and Wo */
+    for (int w = 0; w < V; ++w) {
+      double sE = 0.0, sW = 0.0;
+      for (int j = 0; j < H; ++j) {
+        sE += gE[(size_t)w * H + j] * gE[(size_t)w * H + j];
+        sW += gWo[(size_t)w * H + j] * gWo[(size_t)w * H + j];
+      }
+      rE[w] = rho * rE[w] + (1.0 - rho) * (sE / H);
+      rWo[w] = rho * rWo[w] + (1.0 - rho) * (sW / H);
+      const double dE = sqrt(rE[w]) + eps, dW = sqrt(rWo[w]) + eps;
+      for (int j = 0; j < H; ++j) {
+        /* a zero gradient moves nothing (also when the denominator is zero) */
+        if (gE[(size_t)w * H + j] != 0.0) E[(size_t)w * H + j] -= lr * gE[(size_t)w * H + j] / dE;
+        if (gWo[(size_t)w * H + j] != 0.0) Wo[(size_t)w * H + j] -= lr * gWo[(size_t)w * H + j] / dW;
+      }
+    }
+    /* one value per element for U and b */
+    for (size_t i = 0; i < nHH; ++i) {
+      rU[i] = rho * rU[i] + (1.0 - rho) * gU[i] * gU[i];
+      if (gU[i] != 0.0) U[i] -= lr * gU[i] / (sqrt(rU[i]) + eps);
+    }
+    for (int v = 0; v < V; ++v) {
+      rb[v] = rho * rb[v] + (1.0 - rho) * gb[v] * gb[v];
+      if (gb[v] != 0.0) b[v] -= lr * gb[v] / (sqrt(rb[v]) + eps);
+    }
+    memcpy(h, hn, sizeof(double) * (size_t)B * H);
+    if (sum_logp) {
+      double sacc = 0.0;
+      for (size_t m = 0; m < (size_t)B * T; ++m) sacc += logp[m];
+      *sum_logp = sacc;
+    }
+  }
+  free(gE); free(gWo); free(gU); free(gb); free(hn);
+  return rc;
+}
+
 /* ---- Noise-contrastive estimation (Sec. 4.2 names it as the training criterion) -------------------
  *
  * The paper gives no formula, noise distribution, sample count or normaliser; this follows the
