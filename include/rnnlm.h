@@ -69,6 +69,8 @@ typedef struct {
   int32_t device;    /* HIP device ordinal */
   int32_t K_max;     /* most noise words per window the noise-contrastive calls may pass; 0 = those calls are
                         not used (no workspace is set aside for them), >= 0, at most 65536 */
+  int32_t rmsprop;   /* 1: rnnlm_train_chunk_rmsprop may be called (adds gradient buffers of the size of Wo, U
+                        and b to the workspace); 0: it may not */
 } rnnlm_config;
 
 typedef struct {
@@ -109,6 +111,27 @@ int rnnlm_forward_logprob(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_
  * logp: dev float[T][B] or NULL; sum_logp: dev double (sum of the window's log-probs) or NULL. */
 int rnnlm_train_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lr, float *logp,
                       double *sum_logp, void *stream);
+
+/* Running means of squared gradients for rnnlm_train_chunk_rmsprop, caller-owned and caller-initialised
+ * device arrays, updated in place: one value per WORD for the input-to-state and state-to-output matrices
+ * (Sec. 4.2 averages over the nstate units so that each word has a single value), one per element for U
+ * and b. */
+typedef struct {
+  float *rE;  /* dev [V]    */
+  float *rU;  /* dev [H][H] */
+  float *rWo; /* dev [V]    */
+  float *rb;  /* dev [V]    */
+} rnnlm_rmsprop_state;
+
+/* rnnlm_train_chunk with the rmsprop scaling of Sec. 4.2 (the paper trains with SGD and rmsprop, smoothing
+ * constant 0.9995).  Readings where the paper is silent: the statistic is updated first,
+ * r <- rho*r + (1-rho)*s, then theta <- theta - lr * g / (sqrt(r) + eps); s = g^2 element by element for
+ * U and b, and the mean over the H units of the squared gradient of the word's row for E and Wo; words
+ * whose row has a zero gradient keep their weights while their statistic decays by rho; a zero gradient
+ * moves nothing.  Requires cfg.rmsprop = 1; 0 <= rho <= 1, eps >= 0.  Other arguments as rnnlm_train_chunk. */
+int rnnlm_train_chunk_rmsprop(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lr, float rho,
+                              float eps, const rnnlm_rmsprop_state *state, float *logp, double *sum_logp,
+                              void *stream);
 
 /* Same kernels as rnnlm_train_chunk but the update epilogues write the gradients (of the mean
  * negative log-likelihood) into caller buffers instead of updating: dE: dev float[V][H] (rows of ids
@@ -209,7 +232,8 @@ typedef enum {
   RNNLM_STAGE_NCE_BWD_H = 13,   /* gradient w.r.t. the hidden states (contraction over the noise words + targets) */
   RNNLM_STAGE_NCE_BWD_W = 14,   /* noise-row weight gradient contraction */
   RNNLM_STAGE_NCE_UPDATE = 15,  /* sort/segments of the touched words + row and bias updates */
-  RNNLM_STAGE_COUNT = 16
+  RNNLM_STAGE_RMSPROP = 16,     /* rmsprop calls: statistics + scaled updates from the gradient buffers */
+  RNNLM_STAGE_COUNT = 17
 } rnnlm_stage;
 
 /* Brackets every later execution of the stages whose bit (1u << stage) is set in stage_mask with a

@@ -22,15 +22,20 @@ SYMBOLS = [
     "rnnlm_sync_compute_copies", "rnnlm_check", "rnnlm_sort_segments", "rnnlm_status_string",
     "rnnlm_profile_enable", "rnnlm_profile_read", "rnnlm_set_barrier_spin_limit", "rnnlm_measure_peaks",
     "rnnlm_nce_train_chunk", "rnnlm_nce_grad_chunk", "rnnlm_forward_score",
+    "rnnlm_train_chunk_rmsprop",
 ]
 
 STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce",
-          "nce_score", "nce_grad", "nce_bwd_h", "nce_bwd_w", "nce_update"]
+          "nce_score", "nce_grad", "nce_bwd_h", "nce_bwd_w", "nce_update", "rmsprop"]
 
 
 class rnnlm_config(C.Structure):
     _fields_ = [("V", C.c_int32), ("H", C.c_int32), ("B", C.c_int32), ("T_max", C.c_int32),
-                ("precision", C.c_int32), ("device", C.c_int32), ("K_max", C.c_int32)]
+                ("precision", C.c_int32), ("device", C.c_int32), ("K_max", C.c_int32), ("rmsprop", C.c_int32)]
+
+
+class rnnlm_rmsprop_state(C.Structure):
+    _fields_ = [("rE", C.c_void_p), ("rU", C.c_void_p), ("rWo", C.c_void_p), ("rb", C.c_void_p)]
 
 
 class rnnlm_buffers(C.Structure):
@@ -75,6 +80,7 @@ def load():
     f32 = C.c_float
     lib.rnnlm_nce_train_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, f32, vp, vp, vp]
     lib.rnnlm_nce_grad_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp]
+    lib.rnnlm_train_chunk_rmsprop.argtypes = [vp, vp, vp, i32, f32, f32, f32, C.POINTER(rnnlm_rmsprop_state), vp, vp, vp]
     lib.rnnlm_forward_score.argtypes = [vp, vp, vp, i32, f32, vp, vp]
     lib.rnnlm_profile_enable.argtypes = [vp, C.c_uint32]
     lib.rnnlm_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -106,15 +112,16 @@ def _stream(stream):
     return C.c_void_p(s.cuda_stream)
 
 
-def rnnlm_workspace_bytes(V, H, B, T_max, precision, device=0, K_max=0) -> int:
-    cfg = rnnlm_config(V, H, B, T_max, precision, device, K_max)
+def rnnlm_workspace_bytes(V, H, B, T_max, precision, device=0, K_max=0, rmsprop=0) -> int:
+    cfg = rnnlm_config(V, H, B, T_max, precision, device, K_max, rmsprop)
     return int(load().rnnlm_workspace_bytes(C.byref(cfg)))
 
 
 class Rnnlm:
     """Owns the torch tensors (masters, state, workspace) and the library handle."""
 
-    def __init__(self, E, U, Wo, b, B: int, T_max: int, precision: int, device: int = 0, K_max: int = 0):
+    def __init__(self, E, U, Wo, b, B: int, T_max: int, precision: int, device: int = 0, K_max: int = 0,
+                 rmsprop: bool = False, r_init: float = 1.0):
         import torch
         self.lib = load()
         dev = torch.device("cuda", device)
@@ -125,7 +132,12 @@ class Rnnlm:
         assert self.U.shape == (self.H, self.H) and self.Wo.shape == (self.V, self.H) and self.b.shape == (self.V,)
         self.h_state = torch.zeros(self.B, self.H, dtype=torch.float32, device=dev)
         self.K_max = int(K_max)
-        cfg = rnnlm_config(self.V, self.H, self.B, self.T_max, self.precision, device, self.K_max)
+        cfg = rnnlm_config(self.V, self.H, self.B, self.T_max, self.precision, device, self.K_max, int(bool(rmsprop)))
+        if rmsprop:  # the caller-owned statistics, all starting at r_init
+            fill = lambda *shp: torch.full(shp, float(r_init), dtype=torch.float32, device=dev)
+            self.rE, self.rU, self.rWo, self.rb = fill(self.V), fill(self.H, self.H), fill(self.V), fill(self.V)
+            self.rms_state = rnnlm_rmsprop_state(self.rE.data_ptr(), self.rU.data_ptr(), self.rWo.data_ptr(),
+                                                 self.rb.data_ptr())
         nbytes = int(self.lib.rnnlm_workspace_bytes(C.byref(cfg)))
         if nbytes == 0:
             raise RnnlmError(-1, "rnnlm_workspace_bytes")
@@ -187,6 +199,13 @@ class Rnnlm:
         _ok(self.lib.rnnlm_perplexity(self.handle, _ptr(tok), tok.numel(), T, C.byref(ppl), C.byref(scored),
                                       _stream(stream)), "rnnlm_perplexity")
         return ppl.value, scored.value
+
+    def rnnlm_train_chunk_rmsprop(self, x, y, lr: float, rho: float, eps: float, logp=None, sum_logp=None,
+                                  stream=None):
+        state = getattr(self, "rms_state", None)
+        _ok(self.lib.rnnlm_train_chunk_rmsprop(self.handle, _ptr(x), _ptr(y), x.shape[0], lr, rho, eps,
+                                               C.byref(state) if state is not None else None, _ptr(logp),
+                                               _ptr(sum_logp), _stream(stream)), "rnnlm_train_chunk_rmsprop")
 
     def rnnlm_forward_score(self, x, y, lnZ: float = 0.0, score=None, stream=None):
         import torch

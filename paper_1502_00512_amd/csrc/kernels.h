@@ -336,7 +336,7 @@ __global__ void __launch_bounds__(1024) scatter_update_kernel(const float *__res
                                                               const int32_t *__restrict__ seg_start,
                                                               const int32_t *__restrict__ nseg,
                                                               const float *__restrict__ E, float *__restrict__ out,
-                                                              float alpha, float lr) {
+                                                              float alpha, float lr, int compact_ld) {
   constexpr int PARTS = 4, LANES = 256;
   __shared__ float sh[PARTS][LANES * VEC];
   const int g = blockIdx.x;
@@ -390,8 +390,10 @@ __global__ void __launch_bounds__(1024) scatter_update_kernel(const float *__res
   const int m0 = perm[r0];
   const int w = xp[(m0 / B) * Bp + (m0 % B)];
   const long idx = (long)w * H + col;
+  // compact_ld > 0: the run's result goes to row g of a compact [runs][compact_ld] buffer instead of row w
+  const long oidx = compact_ld > 0 ? (long)g * compact_ld + col : idx;
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) out[idx + e] = ((alpha != 0.0f) ? alpha * E[idx + e] : 0.0f) - lr * acc[e];
+  for (int e = 0; e < VEC; ++e) out[oidx + e] = ((alpha != 0.0f) ? alpha * E[idx + e] : 0.0f) - lr * acc[e];
 }
 
 // ---- measured peaks of the box (reported next to the published ones) -----------------------------

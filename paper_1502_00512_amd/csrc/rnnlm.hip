@@ -13,6 +13,7 @@
 #include "gemm_dma.h"
 #include "kernels.h"
 #include "nce.h"
+#include "rmsprop.h"
 #include "rnn_persistent.h"
 
 using namespace rnnlm_dev;
@@ -28,6 +29,8 @@ struct WsLayout {
       scalars, total;
   // noise-contrastive calls (present when K_max > 0)
   size_t Wn_c, S32, dS_c, G32, noff, ndt, nct, gcol, noise_c, ids, perm2, seg2;
+  // rmsprop calls (present when cfg.rmsprop != 0): gradient buffers the redirected update epilogues fill
+  size_t gWo, gU, gb;
   long partElems;
 };
 
@@ -119,6 +122,7 @@ bool cfg_ok(const rnnlm_config *c) {
   if (c->precision != RNNLM_FP32 && c->precision != RNNLM_BF16_FP32MASTER) return false;
   if (c->device < 0) return false;
   if (c->K_max < 0 || c->K_max > 65536) return false;
+  if (c->rmsprop != 0 && c->rmsprop != 1) return false;
   if ((long)c->B * c->T_max > (1L << 24)) return false;
   return true;
 }
@@ -184,6 +188,12 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
     L.ids = take(nent * 4);
     L.perm2 = take(nent * 4);
     L.seg2 = take((nent + 1) * 4);
+  }
+  L.gWo = L.gU = L.gb = 0;
+  if (c.rmsprop) {
+    L.gWo = take((size_t)c.V * c.H * 4);
+    L.gU = take((size_t)c.H * c.H * 4);
+    L.gb = take((size_t)c.V * 4);
   }
   L.scalars = take(256);  // [0]: int nseg, [4]: int nseg of the noise-contrastive update list, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64..131]: 17 barrier/ticket counters
   L.total = o;
@@ -276,6 +286,7 @@ struct UpdateTargets {
   float alpha, lr;
   bool refresh_copies;
   bool advance_state;
+  int e_compact_ld = 0;  // > 0: the embedding rows go to a compact [runs][e_compact_ld] buffer (one row per run)
 };
 
 // Forward half of a window: tokens -> padded ids, state -> slot 0, gather, T recurrent steps,
@@ -611,10 +622,10 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
   StageTimer tm(h, RNNLM_STAGE_EMB, st);
   if (c.H % 4 == 0) {
     hipLaunchKernelGGL(scatter_update_kernel<4>, dim3(Tn * c.B, (c.H + 1023) / 1024), dim3(1024), 0, st, dA32, Hp, c.H,
-                       c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr);
+                       c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr, u.e_compact_ld);
   } else {
     hipLaunchKernelGGL(scatter_update_kernel<1>, dim3(Tn * c.B, (c.H + 255) / 256), dim3(1024), 0, st, dA32, Hp, c.H,
-                       c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr);
+                       c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr, u.e_compact_ld);
   }
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
@@ -818,6 +829,61 @@ int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t 
   hipStream_t st = (hipStream_t)stream;
   return (h->cfg.precision == RNNLM_FP32) ? score_call<float>(h, x, y, T, lnZ, score, st)
                                           : score_call<bf16_t>(h, x, y, T, lnZ, score, st);
+}
+
+namespace {
+bool rms_args_ok(rnnlm_t *h, float lr, float rho, float eps, const rnnlm_rmsprop_state *s) {
+  if (!h || !h->cfg.rmsprop || !s || !s->rE || !s->rU || !s->rWo || !s->rb) return false;
+  return (lr == lr) && rho >= 0.0f && rho <= 1.0f && eps >= 0.0f;
+}
+}  // namespace
+
+int rnnlm_train_chunk_rmsprop(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lr, float rho,
+                              float eps, const rnnlm_rmsprop_state *state, float *logp, double *sum_logp,
+                              void *stream) {
+  if (!window_args_ok(h, x, y, T) || !rms_args_ok(h, lr, rho, eps, state)) return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const rnnlm_config &c = h->cfg;
+  // gradients through the plain step's kernels, update epilogues redirected (out = 0*W + 1*g); the
+  // embedding rows go to a compact buffer (one row per distinct input word): the hidden-state gradient
+  // buffer, which is free once back-propagation through time is done
+  float *gWo = reinterpret_cast<float *>(h->ws + h->L.gWo), *gU = reinterpret_cast<float *>(h->ws + h->L.gU),
+        *gb = reinterpret_cast<float *>(h->ws + h->L.gb), *gE = reinterpret_cast<float *>(h->ws + h->L.dHs32);
+  UpdateTargets u{gE, gU, gWo, gb, 0.0f, -1.0f, false, true, h->Hp};
+  const bool f32 = c.precision == RNNLM_FP32;
+  int rc = f32 ? window_call<float>(h, x, y, T, logp, sum_logp, &u, true, st)
+               : window_call<bf16_t>(h, x, y, T, logp, sum_logp, &u, true, st);
+  if (rc) return rc;
+  StageTimer tm(h, RNNLM_STAGE_RMSPROP, st);
+  const long nU = (long)c.H * c.H;
+  const int32_t *xp = reinterpret_cast<int32_t *>(h->ws + h->L.xp), *perm = reinterpret_cast<int32_t *>(h->ws + h->L.perm),
+                *seg = reinterpret_cast<int32_t *>(h->ws + h->L.seg);
+  hipLaunchKernelGGL(rms_decay_kernel, dim3(blocks_for(c.V, 256)), dim3(256), 0, st, state->rE, (long)c.V, rho);
+  if (f32) {
+    float *Wo_c = reinterpret_cast<float *>(h->ws + h->L.Wo_c), *U_c = reinterpret_cast<float *>(h->ws + h->L.U_c);
+    hipLaunchKernelGGL(rms_row_apply_kernel<float>, dim3(c.V), dim3(256), 0, st, gWo, (long)c.H, nullptr, nullptr,
+                       nullptr, nullptr, c.B, h->Bp, c.H, h->Hp, h->buf.Wo, Wo_c, state->rWo, rho, lr, eps);
+    hipLaunchKernelGGL(rms_elem_apply_kernel<float>, dim3(blocks_for(nU, 256)), dim3(256), 0, st, gU, c.H, c.H, h->buf.U,
+                       U_c, h->Hp, state->rU, rho, lr, eps);
+    hipLaunchKernelGGL(transpose_kernel<float>, dim3(h->Hp / 32, h->Hp / 32), dim3(256), 0, st, U_c, h->Hp,
+                       reinterpret_cast<float *>(h->ws + h->L.UT_c));
+    hipLaunchKernelGGL(rms_row_apply_kernel<float>, dim3(T * c.B), dim3(256), 0, st, gE, (long)h->Hp, xp, perm, seg,
+                       p_nseg(h), c.B, h->Bp, c.H, h->Hp, h->buf.E, (float *)nullptr, state->rE, rho, lr, eps);
+  } else {
+    bf16_t *Wo_c = reinterpret_cast<bf16_t *>(h->ws + h->L.Wo_c), *U_c = reinterpret_cast<bf16_t *>(h->ws + h->L.U_c);
+    hipLaunchKernelGGL(rms_row_apply_kernel<bf16_t>, dim3(c.V), dim3(256), 0, st, gWo, (long)c.H, nullptr, nullptr,
+                       nullptr, nullptr, c.B, h->Bp, c.H, h->Hp, h->buf.Wo, Wo_c, state->rWo, rho, lr, eps);
+    hipLaunchKernelGGL(rms_elem_apply_kernel<bf16_t>, dim3(blocks_for(nU, 256)), dim3(256), 0, st, gU, c.H, c.H,
+                       h->buf.U, U_c, h->Hp, state->rU, rho, lr, eps);
+    hipLaunchKernelGGL(transpose_kernel<bf16_t>, dim3(h->Hp / 32, h->Hp / 32), dim3(256), 0, st, U_c, h->Hp,
+                       reinterpret_cast<bf16_t *>(h->ws + h->L.UT_c));
+    hipLaunchKernelGGL(rms_row_apply_kernel<bf16_t>, dim3(T * c.B), dim3(256), 0, st, gE, (long)h->Hp, xp, perm, seg,
+                       p_nseg(h), c.B, h->Bp, c.H, h->Hp, h->buf.E, (bf16_t *)nullptr, state->rE, rho, lr, eps);
+  }
+  hipLaunchKernelGGL(rms_elem_apply_kernel<float>, dim3(blocks_for(c.V, 256)), dim3(256), 0, st, gb, 1, c.V, h->buf.b,
+                     (float *)nullptr, 0, state->rb, rho, lr, eps);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
 }
 
 int rnnlm_reset_state(rnnlm_t *h, void *stream) {
