@@ -48,6 +48,9 @@ def main() -> int:
     ap.add_argument("--criterion", choices=["softmax", "nce", "score"], default="softmax",
                     help="softmax: training with the full normalised output (headline metric); nce: training with "
                          "noise-contrastive estimation; score: forward-only unnormalised scoring of given next words")
+    ap.add_argument("--optimizer", choices=["sgd", "rmsprop"], default="sgd",
+                    help="sgd: the fused plain SGD step (headline metric); rmsprop: the rmsprop-scaled step "
+                         "(smoothing 0.9995, one statistic per word for E and Wo), full softmax only")
     ap.add_argument("--streams", type=int, default=0, help="override the number of parallel streams B (scoring)")
     ap.add_argument("--noise", type=int, default=1024, help="noise words per window for --criterion nce")
     ap.add_argument("--calib-copy", action="store_true",
@@ -79,7 +82,12 @@ def main() -> int:
 
     nce = args.criterion == "nce"
     score = args.criterion == "score"
-    g = binding.Rnnlm(E, U, Wo, b, B, T, precision, K_max=args.noise if nce else 0)
+    rms = args.optimizer == "rmsprop"
+    if rms and args.criterion != "softmax":
+        print("bench.py: --optimizer rmsprop goes with --criterion softmax", file=sys.stderr)
+        return 2
+    g = binding.Rnnlm(E, U, Wo, b, B, T, precision, K_max=args.noise if nce else 0, rmsprop=rms, r_init=1e-4)
+    rms_lr, rms_rho, rms_eps = cfg.lr * 1e-2, 0.9995, 1e-4
     dtok = torch.as_tensor(tok).cuda()
     if nce:
         # noise distribution = smoothed unigram of the corpus; the draws of every window, generated up front
@@ -100,6 +108,8 @@ def main() -> int:
             g.rnnlm_nce_train_chunk(x, y, dnoise[k % total_steps], dlnq, lnZ, cfg.lr, None, sum_logp, stream)
         elif score:
             g.rnnlm_forward_score(x, y, float(np.log(V)), scores, stream)
+        elif rms:
+            g.rnnlm_train_chunk_rmsprop(x, y, rms_lr, rms_rho, rms_eps, None, sum_logp, stream)
         else:
             g.rnnlm_train_chunk(x, y, cfg.lr, None, sum_logp, stream)
 
@@ -107,6 +117,8 @@ def main() -> int:
     gemm_stages = ["rnn_fwd", "rnn_bwd", "nce_update"] if nce else ["out_fwd", "out_bwd_h", "out_bwd_w"]
     if score:
         gemm_stages = ["prep", "rnn_fwd", "nce_score"]
+    if rms:
+        gemm_stages = ["out_fwd", "out_bwd_h", "out_bwd_w", "rmsprop"]
 
     for k in range(args.warmup):
         step(k)
@@ -193,8 +205,14 @@ def main() -> int:
     else:
         flops_word = 6.0 * H * (V + H)
         gemm_flops = 2.0 * H * V * M  # algorithmic flops of each output-layer contraction per window
+        rms_ms = gemm_ms.pop("rmsprop", None)
+        dominant = max(gemm_ms, key=gemm_ms.get)
         achieved = gemm_flops / (gemm_ms[dominant] * 1e-3) / 1e12
         out_gemm_frac = 3 * gemm_flops / (sum(gemm_ms.values()) * 1e-3) / 1e12 / peak
+        if rms_ms is not None:
+            # the apply pass reads the gradient (4 B) and read-modify-writes the fp32 master (8 B) + bf16 copy (2 B)
+            extra["rmsprop_apply"] = {"ms": round(rms_ms, 4), "algorithmic_GBps":
+                                      round(14.0 * (V * H + H * H) / (rms_ms * 1e-3) / 1e9, 1), "peak_GBps": PEAK_HBM_GBS}
         roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                     "traffic": measured_traffic(cfg.name, dominant)}
@@ -202,9 +220,12 @@ def main() -> int:
         extra["gemm_ms"] = {k: round(v, 4) for k, v in gemm_ms.items()}
         criterion = "full softmax"
         metric = "training words/sec (fwd+BPTT+SGD) at 1 MI355X"
+        if rms:
+            criterion = "full softmax, rmsprop (0.9995, one statistic per word for E and Wo)"
+            metric = "training words/sec (fwd+BPTT+rmsprop-scaled SGD) at 1 MI355X"
 
     cpu = None
-    if not args.no_cpu_baseline and not score:
+    if not args.no_cpu_baseline and not score and not rms:
         cpu = cpu_baseline(cfg, E, U, Wo, b, tok,
                            (synth.noise_words(thr, args.noise, cfg.data_seed + 7, 0), lnq, lnZ) if nce else None)
 
@@ -222,7 +243,7 @@ def main() -> int:
         "dtype": cfg.precision if cfg.precision == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: Elman RNNLM V={V} H={H}, {B} streams x BPTT {T}, Zipf({cfg.zipf_s}) tokens, "
-                               f"{criterion}" + ("" if score else f" + SGD lr={cfg.lr}"), "V": V, "H": H, "B": B, "T": T, "tokens": int(N)},
+                               f"{criterion}" + ("" if score else f" + SGD lr={rms_lr if rms else cfg.lr}"), "V": V, "H": H, "B": B, "T": T, "tokens": int(N)},
         "whole_path_mfma_frac": round(words_per_s * flops_word / (peak * 1e12), 4),
         "loss_first_last": [round(first_loss, 4), round(last_loss, 4)],
         "roofline": roofline,

@@ -39,8 +39,27 @@ __global__ void __launch_bounds__(256) rms_row_apply_kernel(const float *__restr
     w = xp[(m0 / B) * Bp + (m0 % B)];
   }
   const float *g = G + (long)blockIdx.x * ldg;
+  float *wrow = W + (long)w * H;
+  const bool vec = (H & 3) == 0;  // 16-byte accesses; the first 4096 columns of the gradient row stay in registers
+  f32x4_t gc[4];
   float ss = 0.0f;
-  for (int c = threadIdx.x; c < H; c += 256) ss = fmaf(g[c], g[c], ss);
+  if (vec) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int c = (it * 256 + threadIdx.x) * 4;
+      gc[it] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+      if (c < H) gc[it] = *reinterpret_cast<const f32x4_t *>(g + c);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ss = fmaf(gc[it][e], gc[it][e], ss);
+    }
+    for (int c = (1024 + threadIdx.x) * 4; c < H; c += 1024) {
+      const f32x4_t v = *reinterpret_cast<const f32x4_t *>(g + c);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ss = fmaf(v[e], v[e], ss);
+    }
+  } else {
+    for (int c = threadIdx.x; c < H; c += 256) ss = fmaf(g[c], g[c], ss);
+  }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
@@ -51,15 +70,44 @@ __global__ void __launch_bounds__(256) rms_row_apply_kernel(const float *__restr
   const float scale = lr / (sqrtf(rnew) + eps);
   __syncthreads();  // every thread has read r[w] before it is overwritten
   if (threadIdx.x == 0) r[w] = rnew;
-  float *wrow = W + (long)w * H;
-  for (int c = threadIdx.x; c < H; c += 256) {
-    const float gv = g[c];
-    float v = wrow[c];
-    if (gv != 0.0f) {
-      v -= scale * gv;
-      wrow[c] = v;
+  auto apply4 = [&](int c, const f32x4_t &gv) {
+    f32x4_t v = *reinterpret_cast<const f32x4_t *>(wrow + c);
+    bool moved = false;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (gv[e] != 0.0f) {
+        v[e] -= scale * gv[e];
+        moved = true;
+      }
+    if (moved) *reinterpret_cast<f32x4_t *>(wrow + c) = v;
+    if (Wc) {
+      if constexpr (sizeof(T) == 2) {
+        bf16x4_t hv;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) hv[e] = (bf16_t)v[e];
+        *reinterpret_cast<bf16x4_t *>(Wc + (long)w * Hp + c) = hv;
+      } else {
+        *reinterpret_cast<f32x4_t *>(Wc + (long)w * Hp + c) = v;
+      }
     }
-    if (Wc) Wc[(long)w * Hp + c] = from_f32<T>(v);
+  };
+  if (vec) {
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int c = (it * 256 + threadIdx.x) * 4;
+      if (c < H) apply4(c, gc[it]);
+    }
+    for (int c = (1024 + threadIdx.x) * 4; c < H; c += 1024) apply4(c, *reinterpret_cast<const f32x4_t *>(g + c));
+  } else {
+    for (int c = threadIdx.x; c < H; c += 256) {
+      const float gv = g[c];
+      float v = wrow[c];
+      if (gv != 0.0f) {
+        v -= scale * gv;
+        wrow[c] = v;
+      }
+      if (Wc) Wc[(long)w * Hp + c] = from_f32<T>(v);
+    }
   }
 }
 
