@@ -19,15 +19,26 @@ __global__ void stream_chunk_kernel(const int32_t *__restrict__ tok, long L, lon
 
 // Token check + re-layout into the padded window: xp/yp[t*Bp + s]; padding rows get -1.  Ids outside
 // [0, V) are clamped and raise flags[0].  Also marks padded positions with lse = +inf so that the
-// softmax-gradient pass produces exact zeros there.
-__global__ void prep_tokens_kernel(const int32_t *__restrict__ x, const int32_t *__restrict__ y, int T, int B, int Bp,
+// softmax-gradient pass produces exact zeros there, copies the carried state into slot 0 of the
+// hidden-state buffer (compute type, padded with zeros) and clears the 17 barrier / ticket counters of
+// the persistent recurrent kernel that follows (slot / counters == nullptr: tokens only).  Grid: enough
+// threads for max(Mp, Bp*Hp).
+template <typename T>
+__global__ void prep_tokens_kernel(const int32_t *__restrict__ x, const int32_t *__restrict__ y, int Tn, int B, int Bp,
                                    int Mp, int V, int32_t *__restrict__ xp, int32_t *__restrict__ yp,
-                                   float *__restrict__ lse, int32_t *__restrict__ flags) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+                                   float *__restrict__ lse, int32_t *__restrict__ flags,
+                                   const float *__restrict__ h_state, int H, int Hp, T *__restrict__ slot,
+                                   unsigned *__restrict__ counters) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (counters && i < 17) counters[i] = 0u;
+  if (slot && i < (long)Bp * Hp) {
+    const int s = (int)(i / Hp), c = (int)(i % Hp);
+    slot[i] = from_f32<T>((s < B && c < H) ? h_state[(long)s * H + c] : 0.0f);
+  }
   if (i >= Mp) return;
-  const int t = i / Bp, s = i % Bp;
+  const int t = (int)i / Bp, s = (int)i % Bp;
   int xv = -1, yv = -1;
-  if (t < T && s < B) {
+  if (t < Tn && s < B) {
     xv = x[t * B + s];
     yv = y ? y[t * B + s] : 0;
     if (xv < 0 || xv >= V || yv < 0 || yv >= V) {
@@ -40,16 +51,6 @@ __global__ void prep_tokens_kernel(const int32_t *__restrict__ x, const int32_t 
   }
   xp[i] = xv;
   if (yp) yp[i] = yv;
-}
-
-// Carried state -> slot 0 of the hidden-state buffer (compute type, padded with zeros).
-template <typename T>
-__global__ void state_to_slot_kernel(const float *__restrict__ h_state, int B, int H, int Bp, int Hp,
-                                     T *__restrict__ slot) {
-  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (long)Bp * Hp) return;
-  const int s = (int)(i / Hp), c = (int)(i % Hp);
-  slot[i] = from_f32<T>((s < B && c < H) ? h_state[(long)s * H + c] : 0.0f);
 }
 
 // ---- a1: embedding gather: X[row][:] = E[xp[row]][:] (fp32), zero on padding -------------------
@@ -115,14 +116,22 @@ __global__ void __launch_bounds__(1024) merge_stats_kernel(const float2 *__restr
   const bool valid = m < T * Bp;
   float mx = -INFINITY, sum = 0.0f;
   if (valid) {
-    for (int p = grp; p < nPart; p += 16) {
-      const float2 q = part[(long)p * ldz + m];
+    auto merge = [&](const float2 q) {
       if (q.y > 0.0f) {
         const float nmx = fmaxf(mx, q.x);
         sum = sum * __expf(mx - nmx) + q.y * __expf(q.x - nmx);
         mx = nmx;
       }
+    };
+    int p = grp;
+    for (; p + 48 < nPart; p += 64) {  // four partials per round: their loads are independent
+      float2 q[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) q[u] = part[(long)(p + 16 * u) * ldz + m];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) merge(q[u]);
     }
+    for (; p < nPart; p += 16) merge(part[(long)p * ldz + m]);
   }
   sh[grp][lane] = make_float2(mx, sum);
   __syncthreads();
@@ -145,10 +154,13 @@ __global__ void __launch_bounds__(1024) merge_stats_kernel(const float2 *__restr
 }
 
 // Sum of the window's log-probabilities in fp64 with a fixed reduction tree; raises flags[1] when the
-// result is not finite.
+// result is not finite.  counters != nullptr: also clears the 17 barrier / ticket counters of the
+// persistent recurrent kernel (this kernel sits between its forward and its backward launch).
 __global__ void sum_logp_kernel(const float *__restrict__ logp, int n, double *__restrict__ out,
-                                double *__restrict__ running, int32_t *__restrict__ flags) {
+                                double *__restrict__ running, int32_t *__restrict__ flags,
+                                unsigned *__restrict__ counters) {
   __shared__ double sh[1024];
+  if (counters && threadIdx.x < 17) counters[threadIdx.x] = 0u;  // for the backward recurrent kernel
   double a = 0.0;
   for (int i = threadIdx.x; i < n; i += 1024) a += (double)logp[i];
   sh[threadIdx.x] = a;

@@ -254,7 +254,8 @@ int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st
   a.Bp = h->Bp;
   a.Hp = h->Hp;
   a.spin_limit = h->spin_limit;
-  hipLaunchKernelGGL(fill_kernel<uint32_t>, dim3(1), dim3(64), 0, st, p_counter(h), 17L, 0u);
+  // the 17 counters are zero here: cleared by the token-preparation kernel (forward) and by the
+  // log-probability sum (backward), which always run before this launch on the same stream
   // XCD-local mode: one group of Hp/32 workgroups per block of 32 streams, group x on XCD x
   const bool xcd = h->xcd_local && h->Bp / 32 <= NUM_XCD;
   const dim3 grid(xcd ? (unsigned)(NUM_XCD * (h->Hp / 32)) : (unsigned)((h->Bp / 32) * (h->Hp / 32)));
@@ -306,10 +307,9 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
 
   {
     StageTimer tm(h, RNNLM_STAGE_PREP, st);
-    hipLaunchKernelGGL(prep_tokens_kernel, dim3(blocks_for(Mp, 256)), dim3(256), 0, st, x, y, Tn, c.B, Bp, Mp, c.V, xp,
-                       yp, lse, p_flags(h));
-    hipLaunchKernelGGL(state_to_slot_kernel<T>, dim3(blocks_for((long)Bp * Hp, 256)), dim3(256), 0, st,
-                       h->buf.h_state, c.B, c.H, Bp, Hp, Hs_c);
+    hipLaunchKernelGGL(prep_tokens_kernel<T>, dim3(blocks_for(std::max<long>(Mp, (long)Bp * Hp), 256)), dim3(256), 0,
+                       st, x, y, Tn, c.B, Bp, Mp, c.V, xp, yp, lse, p_flags(h), h->buf.h_state, c.H, Hp, Hs_c,
+                       p_counter(h));
     hipLaunchKernelGGL(gather_kernel, dim3(Mrows), dim3(256), 0, st, h->buf.E, xp, c.H, Hp, X32);
     HIP_TRY(hipGetLastError());
   }
@@ -642,7 +642,7 @@ int window_call(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *l
   }
   if (sum_logp || u) {
     hipLaunchKernelGGL(sum_logp_kernel, dim3(1), dim3(1024), 0, st, at<float>(h, h->L.logp_int), Tn * h->cfg.B,
-                       sum_logp ? sum_logp : p_sum(h), (double *)nullptr, p_flags(h));
+                       sum_logp ? sum_logp : p_sum(h), (double *)nullptr, p_flags(h), u ? p_counter(h) : nullptr);
     HIP_TRY(hipGetLastError());
   }
   if (u) rc = backward_window<T>(h, Tn, *u, nce, st);
@@ -933,7 +933,7 @@ int rnnlm_perplexity(rnnlm_t *h, const int32_t *tok, int64_t N, int32_t T, doubl
                                           : forward_window<bf16_t>(h, xt, yt, T, nullptr, true, true, st);
     if (rc) return rc;
     hipLaunchKernelGGL(sum_logp_kernel, dim3(1), dim3(1024), 0, st, at<float>(h, h->L.logp_int), T * B,
-                       (double *)nullptr, p_running(h), p_flags(h));
+                       (double *)nullptr, p_running(h), p_flags(h), (unsigned *)nullptr);
   }
   HIP_TRY(hipGetLastError());
   double total = 0.0;
@@ -952,9 +952,10 @@ int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, 
   if (!h || !x || !perm || !seg_start || !nseg || T < 1 || T > h->cfg.T_max) return RNNLM_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   const int Mp = (int)round_up((long)T * h->Bp, PAD_M);
-  hipLaunchKernelGGL(prep_tokens_kernel, dim3(blocks_for(Mp, 256)), dim3(256), 0, st, x, (const int32_t *)nullptr, T,
-                     h->cfg.B, h->Bp, Mp, h->cfg.V, at<int32_t>(h, h->L.xp), (int32_t *)nullptr, at<float>(h, h->L.lse),
-                     p_flags(h));
+  hipLaunchKernelGGL(prep_tokens_kernel<float>, dim3(blocks_for(Mp, 256)), dim3(256), 0, st, x,
+                     (const int32_t *)nullptr, T, h->cfg.B, h->Bp, Mp, h->cfg.V, at<int32_t>(h, h->L.xp),
+                     (int32_t *)nullptr, at<float>(h, h->L.lse), p_flags(h), (const float *)nullptr, 0, 0,
+                     (float *)nullptr, (unsigned *)nullptr);
   HIP_TRY(hipGetLastError());
   return sort_segments<float>(h, T, perm, seg_start, nseg, st);
 }
