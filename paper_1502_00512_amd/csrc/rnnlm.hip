@@ -48,6 +48,10 @@ struct rnnlm {
   WsLayout L;
   char *ws;
   // stage timing (host-side only)
+  // the integer helpers of the row updates (sort by id, run starts) depend on the token ids only: they run
+  // on a second stream (default priority) next to the recurrent forward pass and are joined before the updates
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork[2] = {nullptr, nullptr}, ev_join[2] = {nullptr, nullptr};
   bool xcd_local = false;        // the probe at init saw round-robin placement over 8 XCDs
   unsigned spin_limit = 1u << 18;  // polls of a grid barrier before giving up (about a second)
   uint32_t prof_mask = 0;
@@ -292,9 +296,27 @@ struct UpdateTargets {
 
 // Forward half of a window: tokens -> padded ids, state -> slot 0, gather, T recurrent steps,
 // output layer with fused statistics, log-probabilities.
+// Fork: work enqueued on the side stream after this call starts once everything enqueued on `st` so far has
+// finished.  Join: `st` waits for everything enqueued on the side stream so far.  slot = which event pair.
+int side_fork(rnnlm_t *h, int slot, hipStream_t st) {
+  HIP_TRY(hipEventRecord(h->ev_fork[slot], st));
+  HIP_TRY(hipStreamWaitEvent(h->side, h->ev_fork[slot], 0));
+  return RNNLM_OK;
+}
+int side_join(rnnlm_t *h, int slot, hipStream_t st) {
+  HIP_TRY(hipEventRecord(h->ev_join[slot], h->side));
+  HIP_TRY(hipStreamWaitEvent(st, h->ev_join[slot], 0));
+  return RNNLM_OK;
+}
+
+template <typename T>
+int sort_segments(rnnlm_t *h, int Tn, int32_t *perm, int32_t *seg, int32_t *nseg, hipStream_t st);
+
+// sort_inputs: the window will be trained on, so the sort of its input ids for the embedding update is
+// started on the side stream as soon as the padded ids exist (joined in backward_window).
 template <typename T>
 int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *logp_out, bool advance_state,
-                   bool with_output, hipStream_t st) {
+                   bool with_output, hipStream_t st, bool sort_inputs = false) {
   const rnnlm_config &c = h->cfg;
   const int Hp = h->Hp, Bp = h->Bp, Vp = h->Vp;
   const int Mrows = Tn * Bp;
@@ -310,6 +332,12 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     hipLaunchKernelGGL(prep_tokens_kernel<T>, dim3(blocks_for(std::max<long>(Mp, (long)Bp * Hp), 256)), dim3(256), 0,
                        st, x, y, Tn, c.B, Bp, Mp, c.V, xp, yp, lse, p_flags(h), h->buf.h_state, c.H, Hp, Hs_c,
                        p_counter(h));
+    if (sort_inputs) {
+      int rc = side_fork(h, 0, st);
+      if (rc) return rc;
+      rc = sort_segments<T>(h, Tn, at<int32_t>(h, h->L.perm), at<int32_t>(h, h->L.seg), p_nseg(h), h->side);
+      if (rc) return rc;
+    }
     hipLaunchKernelGGL(gather_kernel, dim3(Mrows), dim3(256), 0, st, h->buf.E, xp, c.H, Hp, X32);
     HIP_TRY(hipGetLastError());
   }
@@ -369,6 +397,7 @@ struct NceCall {
   const float *lnq;
   float lnZ;
   float *J_out;
+  bool sort_ids;  // the call updates (or exports) rows: sort the touched-word list
 };
 
 // Scores of all positions against the gathered noise rows, the targets' own scores, then the
@@ -390,6 +419,17 @@ int nce_forward(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
     hipLaunchKernelGGL(nce_prep_kernel, dim3(blocks_for((long)Kp + M, 256)), dim3(256), 0, st, n.noise, K, Kp, c.V, n.lnq,
                        h->buf.b, lnZ_lnK, yp, M, c.B, Bp, at<int32_t>(h, h->L.noise_c), at<float>(h, h->L.noff),
                        at<int32_t>(h, h->L.ids), p_flags(h));
+    if (n.sort_ids) {  // the touched-word list is complete: sort it next to the contractions
+      int rc = side_fork(h, 1, st);
+      if (rc) return rc;
+      const int nent = K + M;
+      int32_t *ids = at<int32_t>(h, h->L.ids);
+      // the sort helpers index keys as key[(i / B) * Bp + i % B]: B = Bp = 1 reads the compact list
+      hipLaunchKernelGGL(rank_sort_kernel, dim3(blocks_for(nent, 64)), dim3(1024), 0, h->side, ids, nent, 1, 1,
+                         at<int32_t>(h, h->L.perm2));
+      hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(1024), 0, h->side, ids, at<int32_t>(h, h->L.perm2), nent, 1, 1,
+                         at<int32_t>(h, h->L.seg2), p_nseg2(h));
+    }
     hipLaunchKernelGGL(nce_gather_rows_kernel<T>, dim3(Kp), dim3(256), 0, st, at<T>(h, h->L.Wo_c), Hp,
                        at<int32_t>(h, h->L.noise_c), K, Wn);
     hipLaunchKernelGGL(nce_target_score_kernel<T>, dim3(blocks_for(Mrows, 4)), dim3(256), 0, st, Hs1,
@@ -468,9 +508,10 @@ int nce_update(rnnlm_t *h, int Tn, const NceCall &n, const UpdateTargets &u, hip
   StageTimer tm(h, RNNLM_STAGE_NCE_UPDATE, st);
   const int nent = K + M;
   int32_t *ids = at<int32_t>(h, h->L.ids), *perm = at<int32_t>(h, h->L.perm2), *seg = at<int32_t>(h, h->L.seg2);
-  // the sort helpers index keys as key[(i / B) * Bp + i % B]: B = Bp = 1 reads the compact list
-  hipLaunchKernelGGL(rank_sort_kernel, dim3(blocks_for(nent, 64)), dim3(1024), 0, st, ids, nent, 1, 1, perm);
-  hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(1024), 0, st, ids, perm, nent, 1, 1, seg, p_nseg2(h));
+  {  // the sort of the list was started on the side stream by nce_forward
+    int rc = side_join(h, 1, st);
+    if (rc) return rc;
+  }
   T *Wc = u.refresh_copies ? at<T>(h, h->L.Wo_c) : nullptr;
   if (c.H % 4 == 0) {
     hipLaunchKernelGGL((nce_row_update_kernel<T, 4>), dim3(nent, (c.H + 255) / 256), dim3(1024), 0, st, G, Hs1, Hp,
@@ -504,12 +545,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
   int32_t *xp = at<int32_t>(h, h->L.xp), *yp = at<int32_t>(h, h->L.yp);
   int32_t *perm = at<int32_t>(h, h->L.perm), *seg = at<int32_t>(h, h->L.seg);
 
-  // integer helpers of the embedding update (independent of everything above)
-  {
-    StageTimer tm(h, RNNLM_STAGE_EMB, st);
-    int rc = sort_segments<T>(h, Tn, perm, seg, p_nseg(h), st);
-    if (rc) return rc;
-  }
+  // the integer helpers of the embedding update were started on the side stream by forward_window
 
   if (nce) {
     int rc = nce_backward_h<T>(h, Tn, *nce, st);
@@ -619,6 +655,10 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     }
   }
   // E[w] -= lr * sum_{m: x[m] = w} dA[m]
+  {
+    int rc = side_join(h, 0, st);
+    if (rc) return rc;
+  }
   StageTimer tm(h, RNNLM_STAGE_EMB, st);
   if (c.H % 4 == 0) {
     hipLaunchKernelGGL(scatter_update_kernel<4>, dim3(Tn * c.B, (c.H + 1023) / 1024), dim3(1024), 0, st, dA32, Hp, c.H,
@@ -634,7 +674,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
 template <typename T>
 int window_call(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *logp, double *sum_logp,
                 const UpdateTargets *u, bool advance_state, hipStream_t st, const NceCall *nce = nullptr) {
-  int rc = forward_window<T>(h, x, y, Tn, logp, advance_state, nce == nullptr, st);
+  int rc = forward_window<T>(h, x, y, Tn, logp, advance_state, nce == nullptr, st, u != nullptr);
   if (rc) return rc;
   if (nce) {  // per-position losses take the place of the log-probabilities
     rc = nce_forward<T>(h, Tn, *nce, st);
@@ -726,8 +766,15 @@ int rnnlm_init(const rnnlm_config *cfg, const rnnlm_buffers *buf, rnnlm_t **out)
       h->xcd_local = rr;
     }
   }
+  if (rc == RNNLM_OK) {
+    bool ok = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i)
+      ok = hipEventCreateWithFlags(&h->ev_fork[i], hipEventDisableTiming) == hipSuccess &&
+           hipEventCreateWithFlags(&h->ev_join[i], hipEventDisableTiming) == hipSuccess;
+    if (!ok) rc = RNNLM_ERR_HIP;
+  }
   if (rc != RNNLM_OK) {
-    delete h;
+    rnnlm_free(h);
     return rc;
   }
   *out = h;
@@ -739,6 +786,14 @@ void rnnlm_free(rnnlm_t *h) {
   for (EventPair &e : h->prof_pool) {
     (void)hipEventDestroy(e.start);
     (void)hipEventDestroy(e.stop);
+  }
+  for (int i = 0; i < 2; ++i) {
+    if (h->ev_fork[i]) (void)hipEventDestroy(h->ev_fork[i]);
+    if (h->ev_join[i]) (void)hipEventDestroy(h->ev_join[i]);
+  }
+  if (h->side) {
+    (void)hipStreamSynchronize(h->side);
+    (void)hipStreamDestroy(h->side);
   }
   delete h;
 }
@@ -797,7 +852,7 @@ int rnnlm_nce_train_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_
   if (!window_args_ok(h, x, y, T) || !nce_args_ok(h, noise, K, lnq, lnZ) || !(lr == lr)) return RNNLM_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   UpdateTargets u{h->buf.E, h->buf.U, h->buf.Wo, h->buf.b, 1.0f, lr, true, true};
-  NceCall n{noise, K, lnq, lnZ, J};
+  NceCall n{noise, K, lnq, lnZ, J, true};
   return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, nullptr, sum_J, &u, true, st, &n)
                                           : window_call<bf16_t>(h, x, y, T, nullptr, sum_J, &u, true, st, &n);
 }
@@ -818,7 +873,7 @@ int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t
   hipLaunchKernelGGL(fill_kernel<float>, dim3(blocks_for(h->cfg.V, 256)), dim3(256), 0, st, db, (long)h->cfg.V, 0.0f);
   HIP_TRY(hipGetLastError());
   UpdateTargets u{dE, dU, dWo, db, 0.0f, -1.0f, false, false};
-  NceCall n{noise, K, lnq, lnZ, J};
+  NceCall n{noise, K, lnq, lnZ, J, true};
   return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, nullptr, nullptr, &u, false, st, &n)
                                           : window_call<bf16_t>(h, x, y, T, nullptr, nullptr, &u, false, st, &n);
 }
