@@ -30,6 +30,7 @@ def lib():
         _lib.oracle_nce_train_chunk.restype = C.c_int
         _lib.oracle_forward_score.restype = C.c_int
         _lib.oracle_train_chunk_rmsprop.restype = C.c_int
+        _lib.oracle_nce_train_chunk_rmsprop.restype = C.c_int
         _lib.oracle_sort_segments.restype = C.c_int
         _lib.oracle_num_threads.restype = C.c_int
     return _lib
@@ -222,6 +223,24 @@ def nce_train_chunk(m: Model, x, y, noise, lnq, lnZ, lr: float):
                                         _i(np.ascontiguousarray(x, np.int32)), _i(np.ascontiguousarray(y, np.int32)),
                                         noise.size, _i(noise), _d(lnq), C.c_double(lnZ), C.c_double(lr), _d(J),
                                         C.byref(s)))
+    return J, s.value
+
+
+def nce_train_chunk_rmsprop(m: Model, st: RmspropState, x, y, noise, lnq, lnZ, lr: float, rho: float, eps: float):
+    """One rmsprop-scaled step on one window under the noise-contrastive criterion (the paper's own
+    combination, Sec. 4.2), in place.  Returns (J[T][B], sum_J)."""
+    T = x.shape[0]
+    noise = np.ascontiguousarray(noise, np.int32).reshape(-1)
+    lnq = np.ascontiguousarray(lnq, np.float64)
+    assert lnq.shape == (m.V,)
+    J = np.empty((T, m.B), np.float64)
+    s = C.c_double(0.0)
+    _check(lib().oracle_nce_train_chunk_rmsprop(m.V, m.H, m.B, T, _d(m.E), _d(m.U), _d(m.Wo), _d(m.b), _d(m.h),
+                                                _i(np.ascontiguousarray(x, np.int32)),
+                                                _i(np.ascontiguousarray(y, np.int32)), noise.size, _i(noise),
+                                                _d(lnq), C.c_double(lnZ), C.c_double(lr), C.c_double(rho),
+                                                C.c_double(eps), _d(st.rE), _d(st.rU), _d(st.rWo), _d(st.rb), _d(J),
+                                                C.byref(s)))
     return J, s.value
 
 

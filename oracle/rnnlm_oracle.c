@@ -291,6 +291,38 @@ int oracle_train_chunk(int V, int H, int B, int T, double *E, double *U, double 
  * word's row (rE[V], rWo[V]: Sec. 4.2 averages over the nstate units so that each word has one value).
  * Rows whose gradient is zero (words not in the window) keep their weights and their value decays by
  * rho like any other.  The statistics are caller-initialised state, updated in place. */
+/* The rmsprop-scaled step itself, given the gradients (see oracle_train_chunk_rmsprop for the readings). */
+static void rmsprop_apply(int V, int H, double *E, double *U, double *Wo, double *b, const double *gE,
+                          const double *gU, const double *gWo, const double *gb, double lr, double rho, double eps,
+                          double *rE, double *rU, double *rWo, double *rb) {
+  const size_t nHH = (size_t)H * H;
+  /* one value per word for E and Wo */
+  for (int w = 0; w < V; ++w) {
+    double sE = 0.0, sW = 0.0;
+    for (int j = 0; j < H; ++j) {
+      sE += gE[(size_t)w * H + j] * gE[(size_t)w * H + j];
+      sW += gWo[(size_t)w * H + j] * gWo[(size_t)w * H + j];
+    }
+    rE[w] = rho * rE[w] + (1.0 - rho) * (sE / H);
+    rWo[w] = rho * rWo[w] + (1.0 - rho) * (sW / H);
+    const double dE = sqrt(rE[w]) + eps, dW = sqrt(rWo[w]) + eps;
+    for (int j = 0; j < H; ++j) {
+      /* a zero gradient moves nothing (also when the denominator is zero) */
+      if (gE[(size_t)w * H + j] != 0.0) E[(size_t)w * H + j] -= lr * gE[(size_t)w * H + j] / dE;
+      if (gWo[(size_t)w * H + j] != 0.0) Wo[(size_t)w * H + j] -= lr * gWo[(size_t)w * H + j] / dW;
+    }
+  }
+  /* one value per element for U and b */
+  for (size_t i = 0; i < nHH; ++i) {
+    rU[i] = rho * rU[i] + (1.0 - rho) * gU[i] * gU[i];
+    if (gU[i] != 0.0) U[i] -= lr * gU[i] / (sqrt(rU[i]) + eps);
+  }
+  for (int v = 0; v < V; ++v) {
+    rb[v] = rho * rb[v] + (1.0 - rho) * gb[v] * gb[v];
+    if (gb[v] != 0.0) b[v] -= lr * gb[v] / (sqrt(rb[v]) + eps);
+  }
+}
+
 int oracle_train_chunk_rmsprop(int V, int H, int B, int T, double *E, double *U, double *Wo, double *b, double *h,
                                const int32_t *x, const int32_t *y, double lr, double rho, double eps, double *rE,
                                double *rU, double *rWo, double *rb, double *logp, double *sum_logp) {
@@ -305,31 +337,7 @@ int oracle_train_chunk_rmsprop(int V, int H, int B, int T, double *E, double *U,
   if (gE && gWo && gU && gb && hn)
     rc = oracle_grad_chunk(V, H, B, T, E, U, Wo, b, h, x, y, logp, gE, gU, gWo, gb, hn, NULL, NULL, NULL, NULL);
   if (rc == ORACLE_OK) {
-    /* one value per word for E and Wo */
-    for (int w = 0; w < V; ++w) {
-      double sE = 0.0, sW = 0.0;
-      for (int j = 0; j < H; ++j) {
-        sE += gE[(size_t)w * H + j] * gE[(size_t)w * H + j];
-        sW += gWo[(size_t)w * H + j] * gWo[(size_t)w * H + j];
-      }
-      rE[w] = rho * rE[w] + (1.0 - rho) * (sE / H);
-      rWo[w] = rho * rWo[w] + (1.0 - rho) * (sW / H);
-      const double dE = sqrt(rE[w]) + eps, dW = sqrt(rWo[w]) + eps;
-      for (int j = 0; j < H; ++j) {
-        /* a zero gradient moves nothing (also when the denominator is zero) */
-        if (gE[(size_t)w * H + j] != 0.0) E[(size_t)w * H + j] -= lr * gE[(size_t)w * H + j] / dE;
-        if (gWo[(size_t)w * H + j] != 0.0) Wo[(size_t)w * H + j] -= lr * gWo[(size_t)w * H + j] / dW;
-      }
-    }
-    /* one value per element for U and b */
-    for (size_t i = 0; i < nHH; ++i) {
-      rU[i] = rho * rU[i] + (1.0 - rho) * gU[i] * gU[i];
-      if (gU[i] != 0.0) U[i] -= lr * gU[i] / (sqrt(rU[i]) + eps);
-    }
-    for (int v = 0; v < V; ++v) {
-      rb[v] = rho * rb[v] + (1.0 - rho) * gb[v] * gb[v];
-      if (gb[v] != 0.0) b[v] -= lr * gb[v] / (sqrt(rb[v]) + eps);
-    }
+    rmsprop_apply(V, H, E, U, Wo, b, gE, gU, gWo, gb, lr, rho, eps, rE, rU, rWo, rb);
     memcpy(h, hn, sizeof(double) * (size_t)B * H);
     if (sum_logp) {
       double sacc = 0.0;
@@ -466,6 +474,37 @@ int oracle_nce_train_chunk(int V, int H, int B, int T, double *E, double *U, dou
     for (size_t i = 0; i < nVH; ++i) Wo[i] -= lr * gWo[i];
     for (size_t i = 0; i < nHH; ++i) U[i] -= lr * gU[i];
     for (int v = 0; v < V; ++v) b[v] -= lr * gb[v];
+    memcpy(h, hn, sizeof(double) * (size_t)B * H);
+    if (sum_J) {
+      double sacc = 0.0;
+      for (size_t m = 0; m < (size_t)B * T; ++m) sacc += J[m];
+      *sum_J = sacc;
+    }
+  }
+  free(gE); free(gWo); free(gU); free(gb); free(hn);
+  return rc;
+}
+
+/* The noise-contrastive step with the rmsprop scaling: the paper's own combination (Sec. 4.2 trains with
+ * noise-contrastive estimation, SGD and rmsprop).  Gradients of oracle_nce_grad_chunk, step of
+ * rmsprop_apply; words that are neither target nor noise have a zero row in gWo and a zero entry in gb. */
+int oracle_nce_train_chunk_rmsprop(int V, int H, int B, int T, double *E, double *U, double *Wo, double *b, double *h,
+                                   const int32_t *x, const int32_t *y, int K, const int32_t *noise, const double *lnq,
+                                   double lnZ, double lr, double rho, double eps, double *rE, double *rU, double *rWo,
+                                   double *rb, double *J, double *sum_J) {
+  if (V <= 0 || H <= 0 || B <= 0 || T <= 0 || !rE || !rU || !rWo || !rb) return ORACLE_ERR_ARG;
+  const size_t nVH = (size_t)V * H, nHH = (size_t)H * H;
+  double *gE = (double *)malloc(sizeof(double) * nVH);
+  double *gWo = (double *)malloc(sizeof(double) * nVH);
+  double *gU = (double *)malloc(sizeof(double) * nHH);
+  double *gb = (double *)malloc(sizeof(double) * (size_t)V);
+  double *hn = (double *)malloc(sizeof(double) * (size_t)B * H);
+  int rc = ORACLE_ERR_NOMEM;
+  if (gE && gWo && gU && gb && hn)
+    rc = oracle_nce_grad_chunk(V, H, B, T, E, U, Wo, b, h, x, y, K, noise, lnq, lnZ, J, gE, gU, gWo, gb, hn, NULL,
+                               NULL, NULL, NULL);
+  if (rc == ORACLE_OK) {
+    rmsprop_apply(V, H, E, U, Wo, b, gE, gU, gWo, gb, lr, rho, eps, rE, rU, rWo, rb);
     memcpy(h, hn, sizeof(double) * (size_t)B * H);
     if (sum_J) {
       double sacc = 0.0;

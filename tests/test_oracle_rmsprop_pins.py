@@ -128,3 +128,53 @@ def test_training_with_rmsprop_lowers_the_loss():
         first = tot if first is None else first
         last = tot
     assert last > first   # summed log-probability of the training text rises
+
+
+# ---- the paper's own combination: noise-contrastive criterion + rmsprop (Sec. 4.2) ----------------------
+
+def nce_inputs(m, seed):
+    r = np.random.default_rng(seed)
+    q = r.uniform(0.2, 1.0, m.V)
+    return r.integers(0, m.V - 2, 5).astype(np.int32), np.log(q / q.sum())
+
+
+def test_nce_rmsprop_with_frozen_unit_statistics_is_the_pinned_nce_sgd_step():
+    m, x, y = setup(21)
+    noise, lnq = nce_inputs(m, 22)
+    a, b_ = m.copy(), m.copy()
+    st = O.RmspropState.filled(m.V, m.H, 1.0)
+    J1, s1 = O.nce_train_chunk_rmsprop(a, st, x, y, noise, lnq, 0.3, 0.2, 1.0, 0.0)
+    J2, s2 = O.nce_train_chunk(b_, x, y, noise, lnq, 0.3, 0.2)
+    assert np.array_equal(J1, J2) and s1 == s2
+    for n in ("E", "U", "Wo", "b", "h"):
+        assert getattr(a, n) == pytest.approx(getattr(b_, n), rel=1e-15, abs=1e-18), n
+
+
+def test_nce_rmsprop_scales_the_pinned_nce_gradient():
+    """First step from r = 0, eps = 0: touched rows of Wo move along the NCE gradient with length
+    lr*sqrt(H)/sqrt(1-rho), touched biases by lr/sqrt(1-rho) against the gradient's sign; words that are
+    neither target nor noise keep row, bias, and a statistic that only decays."""
+    m, x, y = setup(23)
+    noise, lnq = nce_inputs(m, 24)
+    lr, rho = 0.01, 0.9
+    g = O.nce_grad_chunk(m, x, y, noise, lnq, 0.1)
+    a = m.copy()
+    st = O.RmspropState.filled(m.V, m.H, 0.0)
+    st.rWo[:] = 0.5
+    st.rb[:] = 0.5
+    touched = np.zeros(m.V, bool)
+    touched[np.concatenate([y.ravel(), noise])] = True
+    st.rWo[touched] = 0.0
+    st.rb[touched] = 0.0
+    O.nce_train_chunk_rmsprop(a, st, x, y, noise, lnq, 0.1, lr, rho, 0.0)
+    step = lr / math.sqrt(1 - rho)
+    for w in range(m.V):
+        d = a.Wo[w] - m.Wo[w]
+        if not touched[w]:
+            assert not d.any() and a.b[w] == m.b[w]
+            assert st.rWo[w] == pytest.approx(0.5 * rho) and st.rb[w] == pytest.approx(0.5 * rho)
+            continue
+        assert np.linalg.norm(d) == pytest.approx(step * math.sqrt(m.H), rel=1e-12)
+        assert -(d @ g["gWo"][w]) / (np.linalg.norm(d) * np.linalg.norm(g["gWo"][w])) == pytest.approx(1.0, abs=1e-12)
+        assert a.b[w] - m.b[w] == pytest.approx(-step * np.sign(g["gb"][w]), rel=1e-12)
+    assert (~touched).sum() >= 1
