@@ -83,8 +83,8 @@ def main() -> int:
     nce = args.criterion == "nce"
     score = args.criterion == "score"
     rms = args.optimizer == "rmsprop"
-    if rms and args.criterion != "softmax":
-        print("bench.py: --optimizer rmsprop goes with --criterion softmax", file=sys.stderr)
+    if rms and score:
+        print("bench.py: --criterion score has no optimiser", file=sys.stderr)
         return 2
     g = binding.Rnnlm(E, U, Wo, b, B, T, precision, K_max=args.noise if nce else 0, rmsprop=rms, r_init=1e-4)
     rms_lr, rms_rho, rms_eps = cfg.lr * 1e-2, 0.9995, 1e-4
@@ -104,7 +104,10 @@ def main() -> int:
 
     def step(k):
         g.rnnlm_stream_chunk(dtok, k, T, x, y, stream)
-        if nce:
+        if nce and rms:
+            g.rnnlm_nce_train_chunk_rmsprop(x, y, dnoise[k % total_steps], dlnq, lnZ, rms_lr, rms_rho, rms_eps, None,
+                                            sum_logp, stream)
+        elif nce:
             g.rnnlm_nce_train_chunk(x, y, dnoise[k % total_steps], dlnq, lnZ, cfg.lr, None, sum_logp, stream)
         elif score:
             g.rnnlm_forward_score(x, y, float(np.log(V)), scores, stream)
@@ -117,7 +120,7 @@ def main() -> int:
     gemm_stages = ["rnn_fwd", "rnn_bwd", "nce_update"] if nce else ["out_fwd", "out_bwd_h", "out_bwd_w"]
     if score:
         gemm_stages = ["prep", "rnn_fwd", "nce_score"]
-    if rms:
+    if rms and not nce:
         gemm_stages = ["out_fwd", "out_bwd_h", "out_bwd_w", "rmsprop"]
 
     for k in range(args.warmup):
@@ -202,6 +205,9 @@ def main() -> int:
         extra["noise_words"] = Kn
         criterion = f"noise-contrastive output ({Kn} shared noise words per window, lnZ = ln V)"
         metric = "training words/sec (fwd+BPTT+SGD, noise-contrastive criterion) at 1 MI355X"
+        if rms:
+            criterion += ", rmsprop (0.9995, one statistic per word for E and Wo)"
+            metric = "training words/sec (fwd+BPTT+rmsprop-scaled SGD, noise-contrastive criterion) at 1 MI355X"
     else:
         flops_word = 6.0 * H * (V + H)
         gemm_flops = 2.0 * H * V * M  # algorithmic flops of each output-layer contraction per window

@@ -133,6 +133,14 @@ int rnnlm_train_chunk_rmsprop(rnnlm_t *h, const int32_t *x, const int32_t *y, in
                               float eps, const rnnlm_rmsprop_state *state, float *logp, double *sum_logp,
                               void *stream);
 
+/* rnnlm_nce_train_chunk with the rmsprop scaling of rnnlm_train_chunk_rmsprop: the combination Sec. 4.2
+ * trains with (noise-contrastive estimation, SGD, rmsprop).  Words that are neither target nor noise in
+ * the window have a zero gradient row in Wo and entry in b: they keep their weights and their statistics
+ * decay by rho.  Requires cfg.K_max >= K and cfg.rmsprop = 1. */
+int rnnlm_nce_train_chunk_rmsprop(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, const int32_t *noise,
+                                  int32_t K, const float *lnq, float lnZ, float lr, float rho, float eps,
+                                  const rnnlm_rmsprop_state *state, float *J, double *sum_J, void *stream);
+
 /* Same kernels as rnnlm_train_chunk but the update epilogues write the gradients (of the mean
  * negative log-likelihood) into caller buffers instead of updating: dE: dev float[V][H] (rows of ids
  * not in x are zero), dU: dev float[H][H], dWo: dev float[V][H], db: dev float[V]; logp as above or

@@ -22,7 +22,7 @@ SYMBOLS = [
     "rnnlm_sync_compute_copies", "rnnlm_check", "rnnlm_sort_segments", "rnnlm_status_string",
     "rnnlm_profile_enable", "rnnlm_profile_read", "rnnlm_set_barrier_spin_limit", "rnnlm_measure_peaks",
     "rnnlm_nce_train_chunk", "rnnlm_nce_grad_chunk", "rnnlm_forward_score",
-    "rnnlm_train_chunk_rmsprop",
+    "rnnlm_train_chunk_rmsprop", "rnnlm_nce_train_chunk_rmsprop",
 ]
 
 STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce",
@@ -81,6 +81,8 @@ def load():
     lib.rnnlm_nce_train_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, f32, vp, vp, vp]
     lib.rnnlm_nce_grad_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp]
     lib.rnnlm_train_chunk_rmsprop.argtypes = [vp, vp, vp, i32, f32, f32, f32, C.POINTER(rnnlm_rmsprop_state), vp, vp, vp]
+    lib.rnnlm_nce_train_chunk_rmsprop.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, f32, f32, f32,
+                                                  C.POINTER(rnnlm_rmsprop_state), vp, vp, vp]
     lib.rnnlm_forward_score.argtypes = [vp, vp, vp, i32, f32, vp, vp]
     lib.rnnlm_profile_enable.argtypes = [vp, C.c_uint32]
     lib.rnnlm_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -206,6 +208,14 @@ class Rnnlm:
         _ok(self.lib.rnnlm_train_chunk_rmsprop(self.handle, _ptr(x), _ptr(y), x.shape[0], lr, rho, eps,
                                                C.byref(state) if state is not None else None, _ptr(logp),
                                                _ptr(sum_logp), _stream(stream)), "rnnlm_train_chunk_rmsprop")
+
+    def rnnlm_nce_train_chunk_rmsprop(self, x, y, noise, lnq, lnZ: float, lr: float, rho: float, eps: float, J=None,
+                                      sum_J=None, stream=None):
+        state = getattr(self, "rms_state", None)
+        _ok(self.lib.rnnlm_nce_train_chunk_rmsprop(self.handle, _ptr(x), _ptr(y), x.shape[0], _ptr(noise),
+                                                   noise.numel(), _ptr(lnq), lnZ, lr, rho, eps,
+                                                   C.byref(state) if state is not None else None, _ptr(J),
+                                                   _ptr(sum_J), _stream(stream)), "rnnlm_nce_train_chunk_rmsprop")
 
     def rnnlm_forward_score(self, x, y, lnZ: float = 0.0, score=None, stream=None):
         import torch

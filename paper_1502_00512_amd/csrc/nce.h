@@ -187,6 +187,7 @@ __global__ void __launch_bounds__(256) nce_target_dhs_kernel(const T *__restrict
 // blockIdx.x = run of equal ids in the sorted update list (exits when >= *nseg), blockIdx.y = block of
 // 64*VEC columns.  The run's members are dealt round-robin to 16 partial sums (each in ascending list
 // order) which are then added in order.  Also refreshes the compute copy of the row when Wc != nullptr.
+// compact_ld > 0 redirects the results to compact per-run buffers (see below).
 // The first column block also updates the word's bias the same way:
 //   b_out[w] = alpha*b[w] - lr * (sum of gcol over w's noise entries + sum of ct over its target entries).
 template <typename T, int VEC>
@@ -200,7 +201,7 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
                                                               const float *__restrict__ W, float *__restrict__ out,
                                                               T *__restrict__ Wc, const float *__restrict__ gcol,
                                                               const float *__restrict__ b, float *__restrict__ b_out,
-                                                              float alpha, float lr) {
+                                                              float alpha, float lr, int compact_ld) {
   constexpr int PARTS = 16, LANES = 64;
   __shared__ float sh[PARTS][LANES * VEC];
   __shared__ float shb[PARTS];
@@ -269,7 +270,7 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
     const int wb = ids[perm[r0]];
     float tot = shb[0];
     for (int q = 1; q < PARTS; ++q) tot += shb[q];
-    b_out[wb] = ((alpha != 0.0f) ? alpha * b[wb] : 0.0f) - lr * tot;
+    b_out[compact_ld > 0 ? g : wb] = ((alpha != 0.0f) ? alpha * b[wb] : 0.0f) - lr * tot;
   }
   if (partn != 0 || !live) return;
 #pragma unroll
@@ -278,12 +279,15 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
     for (int e = 0; e < VEC; ++e) acc[e] += sh[q][lane * VEC + e];
   const int w = ids[perm[r0]];
   const long idx = (long)w * H + col;
+  // compact_ld > 0: the run's result goes to row g of a compact [runs][compact_ld] buffer (and its bias
+  // term to entry g of b_out) instead of the word's own row
+  const long oidx = compact_ld > 0 ? (long)g * compact_ld + col : idx;
   if constexpr (VEC == 4) {  // H % 4 == 0: 16-byte accesses to the master row
     f32x4_t v = {0.0f, 0.0f, 0.0f, 0.0f};
     if (alpha != 0.0f) v = *reinterpret_cast<const f32x4_t *>(W + idx) * alpha;
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] -= lr * acc[e];
-    *reinterpret_cast<f32x4_t *>(out + idx) = v;
+    *reinterpret_cast<f32x4_t *>(out + oidx) = v;
     if (Wc) {
       if constexpr (sizeof(T) == 2) {
         bf16x4_t hv;
@@ -298,7 +302,7 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
       const float v = ((alpha != 0.0f) ? alpha * W[idx + e] : 0.0f) - lr * acc[e];
-      out[idx + e] = v;
+      out[oidx + e] = v;
       if (Wc) Wc[(long)w * Hp + col + e] = from_f32<T>(v);
     }
   }

@@ -111,6 +111,21 @@ __global__ void __launch_bounds__(256) rms_row_apply_kernel(const float *__restr
   }
 }
 
+// Per-element statistic on a compact list (the output bias under the noise-contrastive criterion): entry i
+// < *nseg holds the gradient of the word of the i-th run of the sorted update list; rb was decayed already.
+__global__ void rms_bias_compact_kernel(const float *__restrict__ g, const int32_t *__restrict__ ids,
+                                        const int32_t *__restrict__ perm, const int32_t *__restrict__ seg_start,
+                                        const int32_t *__restrict__ nseg, float *__restrict__ b,
+                                        float *__restrict__ rb, float rho, float lr, float eps) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= *nseg) return;
+  const int w = ids[perm[seg_start[i]]];
+  const float gv = g[i];
+  const float rnew = rb[w] + (1.0f - rho) * gv * gv;
+  rb[w] = rnew;
+  if (gv != 0.0f) b[w] -= lr * gv / (sqrtf(rnew) + eps);
+}
+
 // One statistic per element (U: R x C with a compute copy of leading dimension ldc; b: 1 x V, no copy).
 template <typename T>
 __global__ void rms_elem_apply_kernel(const float *__restrict__ G, int R, int C, float *__restrict__ W,

@@ -30,7 +30,7 @@ struct WsLayout {
   // noise-contrastive calls (present when K_max > 0)
   size_t Wn_c, S32, dS_c, G32, noff, ndt, nct, gcol, noise_c, ids, perm2, seg2;
   // rmsprop calls (present when cfg.rmsprop != 0): gradient buffers the redirected update epilogues fill
-  size_t gWo, gU, gb;
+  size_t gWo, gU, gb, gN, gbN;
   long partElems;
 };
 
@@ -199,6 +199,12 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
     L.gU = take((size_t)c.H * c.H * 4);
     L.gb = take((size_t)c.V * 4);
   }
+  L.gN = L.gbN = 0;
+  if (c.rmsprop && KpMax > 0) {  // compact per-touched-word gradient rows of the noise-contrastive calls
+    const size_t nent = (size_t)KpMax + (size_t)c.T_max * c.B;
+    L.gN = take(nent * Hp * 4);
+    L.gbN = take(nent * 4);
+  }
   L.scalars = take(256);  // [0]: int nseg, [4]: int nseg of the noise-contrastive update list, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64..131]: 17 barrier/ticket counters
   L.total = o;
 }
@@ -292,6 +298,7 @@ struct UpdateTargets {
   bool refresh_copies;
   bool advance_state;
   int e_compact_ld = 0;  // > 0: the embedding rows go to a compact [runs][e_compact_ld] buffer (one row per run)
+  int wo_compact_ld = 0; // > 0: likewise the touched rows of Wo and entries of b of the noise-contrastive calls
 };
 
 // Forward half of a window: tokens -> padded ids, state -> slot 0, gather, T recurrent steps,
@@ -516,11 +523,11 @@ int nce_update(rnnlm_t *h, int Tn, const NceCall &n, const UpdateTargets &u, hip
   if (c.H % 4 == 0) {
     hipLaunchKernelGGL((nce_row_update_kernel<T, 4>), dim3(nent, (c.H + 255) / 256), dim3(1024), 0, st, G, Hs1, Hp,
                        c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
-                       at<float>(h, h->L.gcol), h->buf.b, u.b, u.alpha, u.lr);
+                       at<float>(h, h->L.gcol), h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
   } else {
     hipLaunchKernelGGL((nce_row_update_kernel<T, 1>), dim3(nent, (c.H + 63) / 64), dim3(1024), 0, st, G, Hs1, Hp,
                        c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
-                       at<float>(h, h->L.gcol), h->buf.b, u.b, u.alpha, u.lr);
+                       at<float>(h, h->L.gcol), h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
   }
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
@@ -937,6 +944,63 @@ int rnnlm_train_chunk_rmsprop(rnnlm_t *h, const int32_t *x, const int32_t *y, in
   }
   hipLaunchKernelGGL(rms_elem_apply_kernel<float>, dim3(blocks_for(c.V, 256)), dim3(256), 0, st, gb, 1, c.V, h->buf.b,
                      (float *)nullptr, 0, state->rb, rho, lr, eps);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+int rnnlm_nce_train_chunk_rmsprop(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, const int32_t *noise,
+                                  int32_t K, const float *lnq, float lnZ, float lr, float rho, float eps,
+                                  const rnnlm_rmsprop_state *state, float *J, double *sum_J, void *stream) {
+  if (!window_args_ok(h, x, y, T) || !nce_args_ok(h, noise, K, lnq, lnZ) || !rms_args_ok(h, lr, rho, eps, state))
+    return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const rnnlm_config &c = h->cfg;
+  float *gU = reinterpret_cast<float *>(h->ws + h->L.gU), *gE = reinterpret_cast<float *>(h->ws + h->L.dHs32),
+        *gN = reinterpret_cast<float *>(h->ws + h->L.gN), *gbN = reinterpret_cast<float *>(h->ws + h->L.gbN);
+  // gradients through the plain step's kernels; the touched rows of Wo / entries of b and the embedding rows
+  // go to compact one-row-per-word buffers
+  UpdateTargets u{gE, gU, gN, gbN, 0.0f, -1.0f, false, true, h->Hp, h->Hp};
+  NceCall n{noise, K, lnq, lnZ, J, true};
+  const bool f32 = c.precision == RNNLM_FP32;
+  int rc = f32 ? window_call<float>(h, x, y, T, nullptr, sum_J, &u, true, st, &n)
+               : window_call<bf16_t>(h, x, y, T, nullptr, sum_J, &u, true, st, &n);
+  if (rc) return rc;
+  StageTimer tm(h, RNNLM_STAGE_RMSPROP, st);
+  const long nU = (long)c.H * c.H;
+  const int nent = K + T * c.B;
+  const int32_t *xp = reinterpret_cast<int32_t *>(h->ws + h->L.xp), *perm = reinterpret_cast<int32_t *>(h->ws + h->L.perm),
+                *seg = reinterpret_cast<int32_t *>(h->ws + h->L.seg);
+  const int32_t *ids = reinterpret_cast<int32_t *>(h->ws + h->L.ids),
+                *perm2 = reinterpret_cast<int32_t *>(h->ws + h->L.perm2),
+                *seg2 = reinterpret_cast<int32_t *>(h->ws + h->L.seg2);
+  const unsigned vb = blocks_for(c.V, 256);
+  hipLaunchKernelGGL(rms_decay_kernel, dim3(vb), dim3(256), 0, st, state->rE, (long)c.V, rho);
+  hipLaunchKernelGGL(rms_decay_kernel, dim3(vb), dim3(256), 0, st, state->rWo, (long)c.V, rho);
+  hipLaunchKernelGGL(rms_decay_kernel, dim3(vb), dim3(256), 0, st, state->rb, (long)c.V, rho);
+  if (f32) {
+    float *Wo_c = reinterpret_cast<float *>(h->ws + h->L.Wo_c), *U_c = reinterpret_cast<float *>(h->ws + h->L.U_c);
+    // the sort helpers' key indexing key[(i / B) * Bp + i % B] with B = Bp = 1 reads the compact id list
+    hipLaunchKernelGGL(rms_row_apply_kernel<float>, dim3(nent), dim3(256), 0, st, gN, (long)h->Hp, ids, perm2, seg2,
+                       p_nseg2(h), 1, 1, c.H, h->Hp, h->buf.Wo, Wo_c, state->rWo, rho, lr, eps);
+    hipLaunchKernelGGL(rms_elem_apply_kernel<float>, dim3(blocks_for(nU, 256)), dim3(256), 0, st, gU, c.H, c.H, h->buf.U,
+                       U_c, h->Hp, state->rU, rho, lr, eps);
+    hipLaunchKernelGGL(transpose_kernel<float>, dim3(h->Hp / 32, h->Hp / 32), dim3(256), 0, st, U_c, h->Hp,
+                       reinterpret_cast<float *>(h->ws + h->L.UT_c));
+    hipLaunchKernelGGL(rms_row_apply_kernel<float>, dim3(T * c.B), dim3(256), 0, st, gE, (long)h->Hp, xp, perm, seg,
+                       p_nseg(h), c.B, h->Bp, c.H, h->Hp, h->buf.E, (float *)nullptr, state->rE, rho, lr, eps);
+  } else {
+    bf16_t *Wo_c = reinterpret_cast<bf16_t *>(h->ws + h->L.Wo_c), *U_c = reinterpret_cast<bf16_t *>(h->ws + h->L.U_c);
+    hipLaunchKernelGGL(rms_row_apply_kernel<bf16_t>, dim3(nent), dim3(256), 0, st, gN, (long)h->Hp, ids, perm2, seg2,
+                       p_nseg2(h), 1, 1, c.H, h->Hp, h->buf.Wo, Wo_c, state->rWo, rho, lr, eps);
+    hipLaunchKernelGGL(rms_elem_apply_kernel<bf16_t>, dim3(blocks_for(nU, 256)), dim3(256), 0, st, gU, c.H, c.H,
+                       h->buf.U, U_c, h->Hp, state->rU, rho, lr, eps);
+    hipLaunchKernelGGL(transpose_kernel<bf16_t>, dim3(h->Hp / 32, h->Hp / 32), dim3(256), 0, st, U_c, h->Hp,
+                       reinterpret_cast<bf16_t *>(h->ws + h->L.UT_c));
+    hipLaunchKernelGGL(rms_row_apply_kernel<bf16_t>, dim3(T * c.B), dim3(256), 0, st, gE, (long)h->Hp, xp, perm, seg,
+                       p_nseg(h), c.B, h->Bp, c.H, h->Hp, h->buf.E, (bf16_t *)nullptr, state->rE, rho, lr, eps);
+  }
+  hipLaunchKernelGGL(rms_bias_compact_kernel, dim3(blocks_for(nent, 256)), dim3(256), 0, st, gbN, ids, perm2, seg2,
+                     p_nseg2(h), h->buf.b, state->rb, rho, lr, eps);
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }

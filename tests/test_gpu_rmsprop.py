@@ -133,3 +133,84 @@ def test_rmsprop_needs_the_configuration_flag():
     x, y = O.stream_chunk(tok, 2, 4, 0)
     with pytest.raises(binding.RnnlmError):
         g.rnnlm_train_chunk_rmsprop(dev(x), dev(y), 0.1, 0.9, 1e-6)
+
+
+# ---- the paper's own combination: noise-contrastive criterion + rmsprop -----------------------------------
+
+def make_nce(V, H, B, T, K, precision, seed, r0, scale=0.1):
+    E, U, Wo, b = synth.make_weights(V, H, "uniform", scale, seed)
+    g = binding.Rnnlm(E, U, Wo, b, B, T, precision, K_max=K, rmsprop=True, r_init=r0)
+    o = O.Model.from_weights(E, U, Wo, b, B)
+    return g, o, O.RmspropState.filled(V, H, r0)
+
+
+@pytest.mark.parametrize("V,H,B,T,K,W,r0,rho,eps", [
+    (1000, 64, 4, 8, 16, 8, 1.0, 0.9, 1e-6),
+    (777, 50, 5, 7, 13, 5, 1e-2, 0.9995, 1e-4),
+    (2500, 160, 20, 5, 300, 4, 1e-3, 0.95, 1e-3),
+])
+def test_nce_rmsprop_train_chunks_fp32(V, H, B, T, K, W, r0, rho, eps):
+    lr, lnZ = 0.02, 0.5 * math.log(V)
+    g, o, st = make_nce(V, H, B, T, K, FP32, seed=V + K, r0=r0)
+    tok = synth.zipf_tokens(W * B * T + B + 1, V, 1.1, 8)
+    lnq, thr = synth.unigram_noise(tok, V)
+    dtok, dlnq = dev(tok), dev(lnq)
+    J = torch.empty(T, B, device="cuda")
+    s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for k in range(W):
+        x, y = g.rnnlm_stream_chunk(dtok, k, T)
+        noise = synth.noise_words(thr, K, 19, k)
+        g.rnnlm_nce_train_chunk_rmsprop(x, y, dev(noise), dlnq, lnZ, lr, rho, eps, J, s)
+        ref, sref = O.nce_train_chunk_rmsprop(o, st, *O.stream_chunk(tok, B, T, k), noise, lnq.astype(np.float64), lnZ,
+                                              lr, rho, eps)
+        got = J.cpu().numpy().astype(np.float64)
+        assert (np.abs(got - ref) <= 2e-4 * np.abs(ref) + 1e-6).all(), (k, np.abs(got - ref).max())
+        assert abs(s.item() - sref) <= 2e-4 * abs(sref)
+    for name, a, c in (("E", g.E, o.E), ("U", g.U, o.U), ("Wo", g.Wo, o.Wo), ("b", g.b, o.b), ("h", g.h_state, o.h)):
+        d = np.abs(a.cpu().numpy() - c).max()
+        assert d <= 1e-4 * max(1.0, np.abs(c).max()), (name, d)
+    for name, a, c in (("rE", g.rE, st.rE), ("rU", g.rU, st.rU), ("rWo", g.rWo, st.rWo), ("rb", g.rb, st.rb)):
+        a = a.cpu().numpy().astype(np.float64)
+        assert (np.abs(a - c) <= 1e-3 * np.abs(c) + 1e-12).all(), (name, np.abs(a / c - 1).max())
+    xe, ye = O.stream_chunk(tok, B, T, 0)
+    lp = g.rnnlm_forward_logprob(dev(xe), dev(ye)).cpu().numpy().astype(np.float64)
+    lr_ = O.forward_logprob(o, xe, ye)
+    assert (np.abs(lp - lr_) <= 2e-4 * np.abs(lr_) + 1e-6).all()     # compute copies of the touched rows refreshed
+    g.rnnlm_check()
+
+
+def test_nce_rmsprop_frozen_unit_statistics_equal_nce_sgd_bitwise():
+    V, H, B, T, K = 1500, 96, 8, 5, 64
+    E, U, Wo, b = synth.make_weights(V, H, "uniform", 0.1, 5)
+    g1 = binding.Rnnlm(E, U, Wo, b, B, T, FP32, K_max=K, rmsprop=True, r_init=1.0)
+    g2 = binding.Rnnlm(E, U, Wo, b, B, T, FP32, K_max=K)
+    tok = synth.zipf_tokens(3 * B * T + B + 1, V, 1.1, 6)
+    lnq, thr = synth.unigram_noise(tok, V)
+    for k in range(3):
+        x, y = O.stream_chunk(tok, B, T, k)
+        noise = dev(synth.noise_words(thr, K, 7, k))
+        g1.rnnlm_nce_train_chunk_rmsprop(dev(x), dev(y), noise, dev(lnq), 1.0, 0.25, 1.0, 0.0)
+        g2.rnnlm_nce_train_chunk(dev(x), dev(y), noise, dev(lnq), 1.0, 0.25)
+    for a, c in ((g1.E, g2.E), (g1.U, g2.U), (g1.Wo, g2.Wo), (g1.b, g2.b), (g1.h_state, g2.h_state)):
+        assert torch.equal(a, c)
+
+
+def test_nce_rmsprop_bf16_training_tracks_oracle():
+    V, H, B, T, K, W = 4000, 256, 32, 10, 256, 30
+    lr, rho, eps, r0 = 0.002, 0.9995, 1e-4, 1e-4
+    g, o, st = make_nce(V, H, B, T, K, BF16, seed=41, r0=r0)
+    tok = synth.zipf_tokens(W * B * T + B + 1, V, 1.1, 42)
+    lnq, thr = synth.unigram_noise(tok, V)
+    dtok, dlnq = dev(tok), dev(lnq)
+    lnZ = 0.5 * math.log(V)
+    s = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ratios = []
+    for k in range(W):
+        x, y = g.rnnlm_stream_chunk(dtok, k, T)
+        noise = synth.noise_words(thr, K, 43, k)
+        g.rnnlm_nce_train_chunk_rmsprop(x, y, dev(noise), dlnq, lnZ, lr, rho, eps, None, s)
+        _, sref = O.nce_train_chunk_rmsprop(o, st, *O.stream_chunk(tok, B, T, k), noise, lnq.astype(np.float64), lnZ,
+                                            lr, rho, eps)
+        ratios.append(s.item() / sref)
+    assert max(abs(r - 1) for r in ratios) < 2e-2, (ratios[0], ratios[-1])
+    g.rnnlm_check()
