@@ -556,6 +556,44 @@ struct EpiSgdT {
   __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
     const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
     const bool vec_ok = ((ldw | ldc) & 3) == 0;
+    if (vec_ok && row0 + 32 * TM <= C) {
+      // Interior of the matrix along the weight columns: no per-element checks, and the master values of
+      // a batch of 8 (or 4) 16-byte groups are all requested before any of them is used.  W and out are
+      // the same array when training in place, so the compiler keeps loads behind earlier stores; issuing
+      // a batch's loads first is what keeps several memory round trips in flight per wave.
+      constexpr int IB = (TM % 2 == 0) ? 2 : 1;  // 32-row blocks per batch
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int r = col0 + j * 32 + (lane & 31);  // weight row
+        if (r >= R) continue;
+#pragma unroll
+        for (int i0 = 0; i0 < TM; i0 += IB) {
+          f32x4_t w[IB][4];
+          if (alpha != 0.0f) {
+#pragma unroll
+            for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                const int j0 = row0 + (i0 + ii) * 32 + 8 * g + ((lane >> 5) << 2);
+                w[ii][g] = *reinterpret_cast<const f32x4_t *>(W + (long)r * ldw + j0);
+              }
+          }
+#pragma unroll
+          for (int ii = 0; ii < IB; ++ii)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const int j0 = row0 + (i0 + ii) * 32 + 8 * g + ((lane >> 5) << 2);
+              f32x4_t nv;
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                nv[e] = ((alpha != 0.0f) ? alpha * w[ii][g][e] : 0.0f) - lr * acc[i0 + ii][j][4 * g + e];
+              *reinterpret_cast<f32x4_t *>(out + (long)r * ldw + j0) = nv;
+              if (Wc) store4(Wc + (long)r * ldc + j0, nv);
+            }
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int r = col0 + j * 32 + (lane & 31);  // weight row
