@@ -561,7 +561,7 @@ struct EpiSgdT {
       // a batch of 8 (or 4) 16-byte groups are all requested before any of them is used.  W and out are
       // the same array when training in place, so the compiler keeps loads behind earlier stores; issuing
       // a batch's loads first is what keeps several memory round trips in flight per wave.
-      constexpr int IB = (TM % 2 == 0) ? 2 : 1;  // 32-row blocks per batch
+      constexpr int IB = (TM % 4 == 0) ? 4 : ((TM % 2 == 0) ? 2 : 1);  // 32-row blocks per batch
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int r = col0 + j * 32 + (lane & 31);  // weight row
