@@ -102,6 +102,66 @@ __global__ void __launch_bounds__(256) transpose_kernel(const T *__restrict__ sr
   for (int r = ty; r < 32; r += 8) dst[(long)(bx + r) * n + by + tx] = tile[tx][r];
 }
 
+// ---- a2 / a8, per-step path for hidden sizes beyond the persistent kernel: the step's contraction runs
+// split over the contraction dimension (so that every compute unit gets a workgroup and each operand panel
+// is fetched by few of them); these kernels sum the partial products in a fixed order and apply the step's
+// elementwise part.  n4 = Bp*Hp/4 groups of 4 columns; part[split][Bp][Hp].
+template <typename T>
+__global__ void rnn_step_fwd_kernel(const float *__restrict__ part, long split_stride, int splits,
+                                    const float *__restrict__ X, int B, int H, int Hp, long n4,
+                                    T *__restrict__ Hnext, float *__restrict__ h_state) {
+  const long i4 = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i4 >= n4) return;
+  const long i = i4 * 4;
+  const int row = (int)(i / Hp), col = (int)(i % Hp);
+  f32x4_t a = *reinterpret_cast<const f32x4_t *>(part + i);
+  for (int s = 1; s < splits; ++s) a += *reinterpret_cast<const f32x4_t *>(part + (long)s * split_stride + i);
+  const f32x4_t x = *reinterpret_cast<const f32x4_t *>(X + i);
+  f32x4_t hv;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) hv[e] = (row < B && col + e < H) ? sigmoidf_(a[e] + x[e]) : 0.0f;
+  if constexpr (sizeof(T) == 2) {
+    bf16x4_t o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)hv[e];
+    *reinterpret_cast<bf16x4_t *>(Hnext + i) = o;
+  } else {
+    *reinterpret_cast<f32x4_t *>(Hnext + i) = hv;
+  }
+  if (h_state && row < B)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (col + e < H) h_state[(long)row * H + col + e] = hv[e];
+}
+
+template <typename T>
+__global__ void rnn_step_bwd_kernel(const float *__restrict__ part, long split_stride, int splits,
+                                    const float *__restrict__ dHs, const T *__restrict__ Hs, int B, int H, int Hp,
+                                    long n4, float *__restrict__ dA32, T *__restrict__ dAc) {
+  const long i4 = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i4 >= n4) return;
+  const long i = i4 * 4;
+  const int row = (int)(i / Hp), col = (int)(i % Hp);
+  f32x4_t a = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int s = 0; s < splits; ++s) a += *reinterpret_cast<const f32x4_t *>(part + (long)s * split_stride + i);
+  const f32x4_t g = *reinterpret_cast<const f32x4_t *>(dHs + i);
+  f32x4_t d;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float hv = to_f32(Hs[i + e]);
+    d[e] = (row < B && col + e < H) ? (g[e] + a[e]) * hv * (1.0f - hv) : 0.0f;
+  }
+  *reinterpret_cast<f32x4_t *>(dA32 + i) = d;
+  if constexpr (sizeof(T) == 2) {
+    bf16x4_t o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)d[e];
+    *reinterpret_cast<bf16x4_t *>(dAc + i) = o;
+  } else {
+    *reinterpret_cast<f32x4_t *>(dAc + i) = d;
+  }
+}
+
 // ---- a4 (part 1): merge the per-row-block (max, sum exp) partials of each position into the log
 // normaliser, and form log P(target) = z_target - lse (Sec. 4.2: explicitly normalised output).
 // Block = 64 positions x 16 groups of partials; each group is merged sequentially in a fixed order, then

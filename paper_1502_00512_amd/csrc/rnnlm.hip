@@ -3,6 +3,7 @@
 #include "../../include/rnnlm.h"
 
 #include <math.h>
+#include <stdlib.h>
 
 #include <algorithm>
 #include <new>
@@ -247,6 +248,17 @@ bool persistent_ok(const rnnlm_t *h) {
   return false;
 }
 
+// Per-step recurrent path for shapes the persistent kernel does not cover: with whole blocks of 256 streams
+// and a wide hidden layer the step's contraction is split over its contraction dimension (0: not split).
+int rnn_step_splits(const rnnlm_t *h) {
+  if (h->Bp % 256 != 0 || h->Hp < 2048) return 0;
+  const long tiles = (long)(h->Bp / 256) * (h->Hp / 64);
+  long S = std::max<long>(1, 256 / tiles);
+  const int BK = (h->cfg.precision == RNNLM_FP32) ? 32 : 64;
+  S = std::min<long>(std::min<long>(S, 8), std::min<long>(h->Hp / BK, h->L.partElems / ((long)h->Bp * h->Hp)));
+  return S >= 2 ? (int)S : 0;
+}
+
 template <typename T, bool BACKWARD>
 int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st) {
   RnnPersistArgs a;
@@ -363,8 +375,23 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     epi.B = c.B;
     epi.H = c.H;
     epi.ld = Hp;
-    HIP_TRY((launch_gemm<T, 32, 64, 1, 2, ROWK, ROWK>(st, Hs_c + (long)t * Bp * Hp, Hp, at<T>(h, h->L.U_c), Hp, Bp, Hp,
-                                                      Hp, 1, epi)));
+    const T *A_ = Hs_c + (long)t * Bp * Hp;
+    const T *B_ = at<T>(h, h->L.U_c);
+    const int S = rnn_step_splits(h);
+    if (S > 0) {
+      // wide step: all streams x 64 units per workgroup, contraction split S ways, then sum + sigmoid
+      const long per = (long)Bp * Hp;
+      EpiPartial ep;
+      ep.part = at<float>(h, h->L.part32);
+      ep.ld = Hp;
+      ep.split_stride = per;
+      HIP_TRY((launch_gemm<T, 256, 64, 4, 2, ROWK, ROWK>(st, A_, Hp, B_, Hp, Bp, Hp, Hp, S, ep)));
+      hipLaunchKernelGGL(rnn_step_fwd_kernel<T>, dim3(blocks_for(per / 4, 256)), dim3(256), 0, st,
+                         at<float>(h, h->L.part32), per, S, epi.X, c.B, c.H, Hp, per / 4, epi.Hnext, epi.h_state);
+      HIP_TRY(hipGetLastError());
+    } else {
+      HIP_TRY((launch_gemm<T, 32, 64, 1, 2, ROWK, ROWK>(st, A_, Hp, B_, Hp, Bp, Hp, Hp, 1, epi)));
+    }
   }
   if (!with_output) return RNNLM_OK;  // the noise-contrastive calls score the hidden states themselves
   {
@@ -613,8 +640,22 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     epi.H = c.H;
     epi.ld = Hp;
     const long K = (t == Tn - 1) ? 0 : Hp;
-    HIP_TRY((launch_gemm<T, 32, 64, 1, 2, ROWK, KROW>(st, dA_c + (long)(t + 1) * Bp * Hp, Hp, U_c, Hp, Bp, Hp, K, 1,
-                                                      epi)));
+    const T *A_ = dA_c + (long)(t + 1) * Bp * Hp;
+    const int S = rnn_step_splits(h);
+    if (S > 0) {
+      const long per = (long)Bp * Hp;
+      EpiPartial ep;
+      ep.part = at<float>(h, h->L.part32);
+      ep.ld = Hp;
+      ep.split_stride = per;
+      if (K > 0) HIP_TRY((launch_gemm<T, 256, 64, 4, 2, ROWK, KROW>(st, A_, Hp, U_c, Hp, Bp, Hp, K, S, ep)));
+      hipLaunchKernelGGL(rnn_step_bwd_kernel<T>, dim3(blocks_for(per / 4, 256)), dim3(256), 0, st,
+                         at<float>(h, h->L.part32), per, K > 0 ? S : 0, epi.dHs, epi.Hs, c.B, c.H, Hp, per / 4,
+                         epi.dA32, epi.dAc);
+      HIP_TRY(hipGetLastError());
+    } else {
+      HIP_TRY((launch_gemm<T, 32, 64, 1, 2, ROWK, KROW>(st, A_, Hp, U_c, Hp, Bp, Hp, K, 1, epi)));
+    }
   }
 
   if (nce) {

@@ -58,6 +58,7 @@ SHAPES_FP32 = [
     (500, 200, 800, 2),   # too many streams for the persistent recurrent kernel: per-step launches
     (400, 1100, 6, 3),    # H > 1024 in fp32: per-step launches
     (300, 100, 300, 3),   # more than 8 blocks of 32 streams: chip-wide (agent-scope) persistent kernel
+    (300, 2100, 256, 2),  # wide hidden layer, whole blocks of 256 streams: per-step launches split over the contraction
 ]
 
 
@@ -224,7 +225,8 @@ def test_token_out_of_range_is_reported_not_faulted():
 
 
 # the last two: 1024 < H <= 2048 (8-wave persistent recurrent kernel) and H > 2048 (per-step launches)
-BF16_SHAPES = [(3000, 256, 32, 4), (2049, 130, 5, 9), (5000, 384, 64, 6), (1000, 1100, 8, 3), (700, 2100, 4, 2)]
+BF16_SHAPES = [(3000, 256, 32, 4), (2049, 130, 5, 9), (5000, 384, 64, 6), (1000, 1100, 8, 3), (700, 2100, 4, 2),
+               (600, 2200, 256, 2)]  # last: wide hidden layer, 256 streams: per-step launches split over the contraction
 
 
 @pytest.mark.parametrize("V,H,B,T", BF16_SHAPES)
