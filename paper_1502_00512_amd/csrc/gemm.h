@@ -459,32 +459,60 @@ struct EpiOutFwd {
 #pragma unroll
         for (int e = 0; e < 4; ++e) bias[i][g][e] = (v + e < V) ? b[v + e] : 0.0f;
       }
+    const bool interior = c.tile_row0 + BM <= V;  // every vocabulary row of the tile exists (all but the last row block)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int m = col0 + j * 32 + (lane & 31);
       const int target = yp[m];
       float mx = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int v = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
-          float z = 0.0f;
-          if (v < V) {
-            z = acc[i][j][r] + bias[i][r >> 2][r & 3];
-            mx = fmaxf(mx, z);
-            if (v == target) zy[m] = z;
-          }
-          acc[i][j][r] = z;
-        }
       float sum = 0.0f;
+      if (interior) {
+        // no per-row checks; the exponentials work in base 2 with the scale folded into one multiply-add
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int v = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
-          if (v < V) sum += __expf(acc[i][j][r] - mx);
+          for (int r = 0; r < 16; ++r) {
+            const float z = acc[i][j][r] + bias[i][r >> 2][r & 3];
+            acc[i][j][r] = z;
+            mx = fmaxf(mx, z);
+          }
+        constexpr float LOG2E = 1.4426950408889634f;
+        const float off = -mx * LOG2E;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[i][j][r], LOG2E, off));
+        // the target's logit: only if it lies in this wave's rows (rare), then a compare chain over the registers
+        const int trel = target - row0 - ((lane >> 5) << 2);  // row offset inside the wave tile, this half-wave's share removed
+        if (trel >= 0 && trel < 32 * TM && ((trel >> 2) & 1) == 0) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if (trel == i * 32 + 8 * (r >> 2) + (r & 3)) zy[m] = acc[i][j][r];
         }
+      } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int v = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
+            float z = 0.0f;
+            if (v < V) {
+              z = acc[i][j][r] + bias[i][r >> 2][r & 3];
+              mx = fmaxf(mx, z);
+              if (v == target) zy[m] = z;
+            }
+            acc[i][j][r] = z;
+          }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int v = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
+            if (v < V) sum += __expf(acc[i][j][r] - mx);
+          }
+      }
       // the other half-wave holds the other rows of the same position
       const float omx = __shfl_xor(mx, 32, 64);
       const float osum = __shfl_xor(sum, 32, 64);
