@@ -193,6 +193,20 @@ struct StageGeom {
   static constexpr int PITCH = BN * 2 + 64;
 };
 
+// Start value of the accumulators.  Every epilogue provides init<TM, TN>(acc, row0, col0, lane, split),
+// called before the main loop with the origin of the wave's sub-tile in C; the default is zero.
+struct EpiZeroInit {
+  template <int TM, int TN>
+  __device__ inline void init(f32x16_t (&acc)[TM][TN], int, int, int, int) const {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+  }
+};
+
 // What an epilogue sees: the workgroup's LDS (reusable: the main loop ends with a barrier), the
 // origin of the workgroup tile in C, the origin of this wave's sub-tile inside it, and ids.
 struct EpiCtx {
@@ -227,12 +241,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64, MINWG) gemm_kernel(const GemmSh
   const int nk = kb1 - kb0;
 
   f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+  epi.template init<TM, TN>(acc, tile_m * BM + wm * WTM, tile_n * BN + wn * WTN, lane, split);
 
   TileLoader<T, BM, LA, NT, KBYTES> la[PF];
   TileLoader<T, BN, LB, NT, KBYTES> lb[PF];
@@ -399,7 +408,7 @@ constexpr int stage_lds_bytes() {
 
 // Recurrent forward step (Sec. 4.1): h = sigmoid(X + Hprev U^T).  Rows = streams, cols = units.
 template <typename T>
-struct EpiRnnFwd {
+struct EpiRnnFwd : EpiZeroInit {
   const float *X;   // [Bp][ld]  gathered embedding rows of this timestep
   T *Hnext;         // [Bp][ld]  hidden state slot of this timestep (padding written as zero)
   float *h_state;   // [B][H] or nullptr: carried state, written at the window's last step
@@ -433,7 +442,7 @@ struct EpiRnnFwd {
 // position's target word.  A lane owns one position (column), so its statistics need no cross-lane
 // traffic except one exchange between the two half-waves.
 template <typename T>
-struct EpiOutFwd {
+struct EpiOutFwd : EpiZeroInit {
   const float *b;   // [V]
   T *ZT;            // [Vp][ldz]
   float2 *part;     // [Vp / BM][ldz]: one (max, sum exp) per tile row block and position
@@ -445,20 +454,28 @@ struct EpiOutFwd {
   static constexpr int lds_bytes() {
     return stage_lds_bytes<T, BM, BN>() > 8 * BN * 8 ? stage_lds_bytes<T, BM, BN>() : 8 * BN * 8;
   }
-  template <int BM, int BN, int TM, int TN, int NT>
-  __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
-    const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
-    float2 *red = reinterpret_cast<float2 *>(c.smem_lo);  // [waves along rows][BN] statistics exchange
-    // bias: a lane needs b[v .. v+3] for 4*TM aligned groups of rows
-    float bias[TM][4][4];
+  // The accumulators start at the bias of their vocabulary row (0 for rows >= V): the bias costs neither
+  // an addition per logit nor a load whose latency the epilogue would have to wait for.  The contraction
+  // is never split for this epilogue.
+  template <int TM, int TN>
+  __device__ inline void init(f32x16_t (&acc)[TM][TN], int row0, int, int lane, int) const {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int v = row0 + i * 32 + 8 * g + ((lane >> 5) << 2);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) bias[i][g][e] = (v + e < V) ? b[v + e] : 0.0f;
+        for (int e = 0; e < 4; ++e) {
+          const float bv = (v + e < V) ? b[v + e] : 0.0f;
+#pragma unroll
+          for (int j = 0; j < TN; ++j) acc[i][j][4 * g + e] = bv;
+        }
       }
+  }
+  template <int BM, int BN, int TM, int TN, int NT>
+  __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
+    const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
+    float2 *red = reinterpret_cast<float2 *>(c.smem_lo);  // [waves along rows][BN] statistics exchange
     const bool interior = c.tile_row0 + BM <= V;  // every vocabulary row of the tile exists (all but the last row block)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
@@ -472,9 +489,7 @@ struct EpiOutFwd {
         for (int i = 0; i < TM; ++i)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float z = acc[i][j][r] + bias[i][r >> 2][r & 3];
-            acc[i][j][r] = z;
-            mx = fmaxf(mx, z);
+            mx = fmaxf(mx, acc[i][j][r]);
           }
         constexpr float LOG2E = 1.4426950408889634f;
         const float off = -mx * LOG2E;
@@ -499,7 +514,7 @@ struct EpiOutFwd {
             const int v = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
             float z = 0.0f;
             if (v < V) {
-              z = acc[i][j][r] + bias[i][r >> 2][r & 3];
+              z = acc[i][j][r];
               mx = fmaxf(mx, z);
               if (v == target) zy[m] = z;
             }
@@ -544,7 +559,7 @@ struct EpiOutFwd {
 };
 
 // Split-K partial sums: part[split][row][col] = acc.
-struct EpiPartial {
+struct EpiPartial : EpiZeroInit {
   float *part;
   long ld;           // columns
   long split_stride; // elements between splits
@@ -564,7 +579,7 @@ struct EpiPartial {
 // caller buffer, alpha = 0, lr = -1, Wc = nullptr.  Padding entries of Wc are never written (they
 // stay zero).
 template <typename T>
-struct EpiSgdT {
+struct EpiSgdT : EpiZeroInit {
   const float *W;
   float *out;
   T *Wc;
@@ -662,7 +677,7 @@ struct EpiSgdT {
 
 // Recurrent backward step: dA = (dH_out + dA_next U) * h * (1 - h).  Rows = streams, cols = units.
 template <typename T>
-struct EpiRnnBwd {
+struct EpiRnnBwd : EpiZeroInit {
   const float *dHs;  // [Bp][ld] gradient arriving from the output layer at this timestep
   const T *Hs;       // [Bp][ld] hidden state of this timestep
   float *dA32;       // [Bp][ld]

@@ -154,12 +154,7 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma_kernel(const GemmShape
   const int nk = kb1 - kb0;
 
   f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+  epi.template init<TM, TN>(acc, tile_m * BM + wm * WTM, tile_n * BN + wn * WTN, lane, split);
 
   DmaLoader<BM, LA, NT> la;
   DmaLoader<BN, LB, NT> lb;
