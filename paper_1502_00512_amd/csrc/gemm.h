@@ -211,6 +211,7 @@ struct EpiZeroInit {
 // origin of the workgroup tile in C, the origin of this wave's sub-tile inside it, and ids.
 struct EpiCtx {
   char *smem_lo, *smem_hi;  // LDS for staging the upper / lower half of the tile's rows
+  char *q[4];               // the same LDS seen as four regions, one per quarter of the tile's rows
   int tile_row0, tile_col0;
   int wrow, wcol;
   int lane, tid, split;
@@ -322,6 +323,8 @@ __global__ void __launch_bounds__(WGM *WGN * 64, MINWG) gemm_kernel(const GemmSh
   EpiCtx ctx;
   ctx.smem_lo = smem;
   ctx.smem_hi = smem + (BM / 2) * StageGeom<BN>::PITCH;
+#pragma unroll
+  for (int qi = 0; qi < 4; ++qi) ctx.q[qi] = smem + qi * (BM / 4) * StageGeom<BN>::PITCH;
   ctx.tile_row0 = tile_m * BM;
   ctx.tile_col0 = tile_n * BN;
   ctx.wrow = wm * WTM;
@@ -330,6 +333,12 @@ __global__ void __launch_bounds__(WGM *WGN * 64, MINWG) gemm_kernel(const GemmSh
   ctx.tid = tid;
   ctx.split = split;
   epi.template run<BM, BN, TM, TN, NT>(acc, ctx);
+}
+
+// LDS region of quarter qi of the tile's rows (a select chain: indexing the pointer array with a run-time
+// value would move it to scratch memory).
+__device__ inline char *quarter_ptr(const EpiCtx &c, int qi) {
+  return qi == 0 ? c.q[0] : (qi == 1 ? c.q[1] : (qi == 2 ? c.q[2] : c.q[3]));
 }
 
 // Accumulator element r (0..15) of a 32x32 block lives at row 8*(r/4) + 4*(lane/32) + r%4,
@@ -358,14 +367,19 @@ __device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c
 }
 // bf16: a lane holds one column and runs of 4 consecutive rows.  Neighbouring lanes swap one packed
 // pair so that each lane owns two adjacent columns of one row (one dword), the tile is assembled in
-// LDS (which the main loop no longer needs) and leaves as 16-byte row-contiguous stores.
+// LDS (which the main loop no longer needs; four regions, one per quarter of the rows) and leaves as
+// 16-byte row-contiguous stores.
 template <int BM, int BN, int TM, int TN, int NT>
 __device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c, bf16_t *out, long ld) {
   constexpr int PITCH = StageGeom<BN>::PITCH;
+  constexpr int QR = BM / 4;  // rows per LDS region
   typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
   const bool odd = c.lane & 1;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
+    // with at least 32 rows per region a 32-row block lies in one region: its base is uniform for the wave
+    const int blk = c.wrow + i * 32;
+    char *blk_base = quarter_ptr(c, blk / QR) + (blk % QR) * PITCH;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = c.wcol + j * 32 + (c.lane & 31);
@@ -381,19 +395,37 @@ __device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c
         const unsigned mine = pk.u;
         const unsigned theirs = (unsigned)__builtin_amdgcn_mov_dpp((int)mine, 0xB1, 0xF, 0xF, true);  // lane ^ 1
         const unsigned word = odd ? ((theirs >> 16) | (mine & 0xffff0000u)) : ((mine & 0xffffu) | (theirs << 16));
-        const int row = c.wrow + i * 32 + RNNLM_ACC_ROW(r0, c.lane) + (odd ? 1 : 0);
-        char *half = row < BM / 2 ? c.smem_lo : c.smem_hi;
-        *reinterpret_cast<unsigned *>(half + (row % (BM / 2)) * PITCH + (col & ~1) * 2) = word;
+        const int rin = RNNLM_ACC_ROW(r0, c.lane) + (odd ? 1 : 0);  // row inside the 32-row block
+        if constexpr (QR >= 32) {
+          *reinterpret_cast<unsigned *>(blk_base + rin * PITCH + (col & ~1) * 2) = word;
+        } else {
+          const int row = blk + rin;
+          *reinterpret_cast<unsigned *>(quarter_ptr(c, row / QR) + (row % QR) * PITCH + (col & ~1) * 2) = word;
+        }
       }
     }
+  }
   __syncthreads();
   constexpr int CPR = BN * 2 / 16;  // 16-byte chunks per row
+  constexpr int RPI = NT / CPR;     // rows the workgroup moves per iteration
+  if constexpr (NT % CPR == 0 && QR % RPI == 0 && BM % RPI == 0) {
+    // an iteration's rows lie in one region, known at compile time once the loop is unrolled
+    const int r_lo = c.tid / CPR, ch = c.tid % CPR;
+#pragma unroll
+    for (int k = 0; k < BM / RPI; ++k) {
+      const int row = k * RPI + r_lo;
+      const char *quarter = c.q[(k * RPI) / QR];
+      const u32x4_t v = *reinterpret_cast<const u32x4_t *>(quarter + ((k * RPI) % QR + r_lo) * PITCH + ch * 16);
+      *reinterpret_cast<u32x4_t *>(out + (long)(c.tile_row0 + row) * ld + c.tile_col0 + ch * 8) = v;
+    }
+  } else {
 #pragma unroll 4
-  for (int idx = c.tid; idx < BM * CPR; idx += NT) {
-    const int row = idx / CPR, ch = idx % CPR;
-    const char *half = row < BM / 2 ? c.smem_lo : c.smem_hi;
-    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(half + (row % (BM / 2)) * PITCH + ch * 16);
-    *reinterpret_cast<u32x4_t *>(out + (long)(c.tile_row0 + row) * ld + c.tile_col0 + ch * 8) = v;
+    for (int idx = c.tid; idx < BM * CPR; idx += NT) {
+      const int row = idx / CPR, ch = idx % CPR;
+      const char *quarter = quarter_ptr(c, row / QR);
+      const u32x4_t v = *reinterpret_cast<const u32x4_t *>(quarter + (row % QR) * PITCH + ch * 16);
+      *reinterpret_cast<u32x4_t *>(out + (long)(c.tile_row0 + row) * ld + c.tile_col0 + ch * 8) = v;
+    }
   }
 }
 template <typename T, int BM, int BN>

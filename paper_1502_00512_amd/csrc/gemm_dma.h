@@ -237,6 +237,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma_kernel(const GemmShape
   EpiCtx ctx;
   ctx.smem_lo = stage0;
   ctx.smem_hi = stage1;
+  ctx.q[0] = stage0;
+  ctx.q[1] = stage0 + (BM / 4) * StageGeom<BN>::PITCH;
+  ctx.q[2] = stage1;
+  ctx.q[3] = stage1 + (BM / 4) * StageGeom<BN>::PITCH;
   ctx.tile_row0 = tile_m * BM;
   ctx.tile_col0 = tile_n * BN;
   ctx.wrow = wm * WTM;

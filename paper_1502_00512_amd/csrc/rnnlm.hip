@@ -12,6 +12,7 @@
 #include "common.h"
 #include "gemm.h"
 #include "gemm_dma.h"
+#include "gemm_dma4.h"
 #include "kernels.h"
 #include "nce.h"
 #include "rmsprop.h"
@@ -108,11 +109,16 @@ namespace {
 // Tile shape of the three output-layer contractions and of the recurrent weight gradient: 256x256
 // output tile, 8 waves as 2 x 4 (wave tile 128 x 64).
 constexpr int BIG = 256;
-// The large contractions: bf16 operands take the direct global->LDS kernel, fp32 the register-staged one.
-template <typename T, int WGM, int WGN, int LA, int LB, class Epi>
+// The large contractions: bf16 operands take the direct global->LDS kernel (four-stage ring), fp32 the
+// register-staged one.
+// RING4: the four-stage ring of 32-deep K blocks (deeper prefetch; pays when at least one operand is
+// K-major, whose 32-deep blocks are still made of full cache lines) instead of two stages of 64.
+template <typename T, int WGM, int WGN, int LA, int LB, bool RING4, class Epi>
 hipError_t big_gemm(hipStream_t st, const void *A, long lda, const void *B, long ldb, long Mg, long Ng, long K,
                     int splits, const Epi &epi, int band = 4) {
-  if constexpr (sizeof(T) == 2) {
+  if constexpr (sizeof(T) == 2 && RING4) {
+    return launch_gemm_dma4<BIG, BIG, WGM, WGN, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
+  } else if constexpr (sizeof(T) == 2) {
     return launch_gemm_dma<BIG, BIG, WGM, WGN, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
   } else {
     return launch_gemm<T, BIG, BIG, 2, 4, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
@@ -404,7 +410,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     epi.zy = zy;
     epi.V = c.V;
     epi.ldz = ldz;
-    HIP_TRY((big_gemm<T, 4, 2, ROWK, ROWK>(st, at<T>(h, h->L.Wo_c), Hp, Hs_c + (long)Bp * Hp, Hp, Vp, Mp, Hp, 1, epi)));
+    HIP_TRY((big_gemm<T, 4, 2, ROWK, ROWK, false>(st, at<T>(h, h->L.Wo_c), Hp, Hs_c + (long)Bp * Hp, Hp, Vp, Mp, Hp, 1, epi)));
   }
   StageTimer tm(h, RNNLM_STAGE_STATS, st);
   hipLaunchKernelGGL(merge_stats_kernel, dim3(blocks_for(Mrows, 64)), dim3(1024), 0, st, at<float2>(h, h->L.stat),
@@ -605,7 +611,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     epi.split_stride = per;
     {
       StageTimer tm(h, RNNLM_STAGE_OUT_BWD_H, st);
-      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW>(st, ZT, ldz, Wo_c, Hp, Mp, Hp, Vp, S, epi)));
+      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW, true>(st, ZT, ldz, Wo_c, Hp, Mp, Hp, Vp, S, epi)));
     }
     if (S > 1) {
       StageTimer tm(h, RNNLM_STAGE_REDUCE, st);
@@ -674,7 +680,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     epi.C = c.H;
     epi.alpha = u.alpha;
     epi.lr = u.lr;
-    HIP_TRY((big_gemm<T, 2, 4, KROW, ROWK>(st, Hs_c + (long)Bp * Hp, Hp, ZT, ldz, Hp, Vp, Mp, 1, epi, -2)));
+    HIP_TRY((big_gemm<T, 2, 4, KROW, ROWK, true>(st, Hs_c + (long)Bp * Hp, Hp, ZT, ldz, Hp, Vp, Mp, 1, epi, -2)));
   }
   // U[i][j] -= lr * sum_m dA[m][i] Hprev[m][j], contracted transposed (tile rows = j, tile columns = i)
   {
@@ -690,7 +696,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     epi.alpha = u.alpha;
     epi.lr = u.lr;
     if (sizeof(T) == 2 && (long)(Hp / BIG) * (Hp / BIG) >= 64) {
-      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
+      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW, true>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
     } else if (Hp <= 1024) {  // small matrix: 64x64 tiles give up to 256 workgroups
       HIP_TRY((launch_gemm<T, 64, 64, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
     } else {
