@@ -682,6 +682,23 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     epi.lr = u.lr;
     HIP_TRY((big_gemm<T, 2, 4, KROW, ROWK, true>(st, Hs_c + (long)Bp * Hp, Hp, ZT, ldz, Hp, Vp, Mp, 1, epi, -2)));
   }
+  // E[w] -= lr * sum_{m: x[m] = w} dA[m]: on the side stream, behind the sort helpers already queued there,
+  // next to the recurrent weight-gradient contraction of the main stream (joined at the end of this function;
+  // started after the large output weight update, which it would only slow down)
+  {
+    int rc = side_fork(h, 0, st);  // the side stream waits for everything queued so far
+    if (rc) return rc;
+    StageTimer tm(h, RNNLM_STAGE_EMB, h->side);
+    if (c.H % 4 == 0) {
+      hipLaunchKernelGGL(scatter_update_kernel<4>, dim3(Tn * c.B, (c.H + 1023) / 1024), dim3(1024), 0, h->side, dA32,
+                         Hp, c.H, c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr, u.e_compact_ld);
+    } else {
+      hipLaunchKernelGGL(scatter_update_kernel<1>, dim3(Tn * c.B, (c.H + 255) / 256), dim3(1024), 0, h->side, dA32,
+                         Hp, c.H, c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr, u.e_compact_ld);
+    }
+    HIP_TRY(hipGetLastError());
+  }
+
   // U[i][j] -= lr * sum_m dA[m][i] Hprev[m][j], contracted transposed (tile rows = j, tile columns = i)
   {
     StageTimer tm(h, RNNLM_STAGE_REC_W, st);
@@ -708,21 +725,8 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
       HIP_TRY(hipGetLastError());
     }
   }
-  // E[w] -= lr * sum_{m: x[m] = w} dA[m]
-  {
-    int rc = side_join(h, 0, st);
-    if (rc) return rc;
-  }
-  StageTimer tm(h, RNNLM_STAGE_EMB, st);
-  if (c.H % 4 == 0) {
-    hipLaunchKernelGGL(scatter_update_kernel<4>, dim3(Tn * c.B, (c.H + 1023) / 1024), dim3(1024), 0, st, dA32, Hp, c.H,
-                       c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr, u.e_compact_ld);
-  } else {
-    hipLaunchKernelGGL(scatter_update_kernel<1>, dim3(Tn * c.B, (c.H + 255) / 256), dim3(1024), 0, st, dA32, Hp, c.H,
-                       c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr, u.e_compact_ld);
-  }
-  HIP_TRY(hipGetLastError());
-  return RNNLM_OK;
+  // wait for the embedding update running on the side stream
+  return side_join(h, 0, st);
 }
 
 template <typename T>
