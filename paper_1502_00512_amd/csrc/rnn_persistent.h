@@ -239,9 +239,9 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
       xin = *reinterpret_cast<const f32x4_t *>(a.X + eidx);
       if (BACKWARD) hcur = load4<T>(Hs + slot + eidx);
     }
-    f32x16_t acc;
+    f32x16_t acc, acc2;  // two accumulation chains: consecutive MFMAs do not wait for one another
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+    for (int r = 0; r < 16; ++r) acc[r] = acc2[r] = 0.0f;
     const bool contract = !(BACKWARD && step == 0);  // nothing flows into the window's last position
     if (contract) {
       const T *src = BACKWARD ? dAc + (long)(t + 1) * slot : Hs + (long)t * slot;
@@ -250,7 +250,12 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) f[kk] = load_frag_global<T, !XCD>(Ap + kk * 16);
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) mma16(acc, f[kk], w[kk]);
+      for (int kk = 0; kk < KS; kk += 2) {
+        mma16(acc, f[kk], w[kk]);
+        if (kk + 1 < KS) mma16(acc2, f[kk + 1], w[kk + 1]);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] += acc2[r];
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r];
