@@ -296,8 +296,13 @@ def cpu_baseline(cfg, E, U, Wo, b, tok, nce=None):
     if dt < 5.0 and T > 1:        # then as many timesteps as fit about 15 s
         Ts = int(max(2, min(T, 15.0 // dt)))
         dt = timed(Ts)
-    return {"value": round(B * Ts / dt, 2), "unit": "words/s", "cores": O.num_threads(), "kind": "oracle",
-            "sample": f"one training window of {B} streams x {Ts} of {T} timesteps ({B * Ts} words, {dt:.1f} s)"}
+    words, total, reps = B * Ts, dt, 1
+    while Ts == T and total < 10.0 and reps < 8:   # a whole window is short: repeat it up to about 10 s
+        total += timed(Ts)
+        words += B * Ts
+        reps += 1
+    return {"value": round(words / total, 2), "unit": "words/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"{reps} x one training window of {B} streams x {Ts} of {T} timesteps ({words} words, {total:.1f} s)"}
 
 
 if __name__ == "__main__":
