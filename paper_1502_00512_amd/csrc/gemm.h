@@ -609,12 +609,13 @@ struct EpiPartial : EpiZeroInit {
 // read-modify-write.  out = alpha*W - lr*acc for the R x C valid entries; training passes out = W (in
 // place, alpha = 1) and also refreshes the compute copy Wc; the gradient-export call passes out =
 // caller buffer, alpha = 0, lr = -1, Wc = nullptr.  Padding entries of Wc are never written (they
-// stay zero).
+// stay zero).  WcT, when given, receives the same values transposed (the recurrent matrix keeps both).
 template <typename T>
 struct EpiSgdT : EpiZeroInit {
   const float *W;
   float *out;
   T *Wc;
+  T *WcT = nullptr;  // optional: the transposed compute copy (leading dimension ldc), refreshed as well
   long ldw, ldc;  // ldw: W/out leading dimension; ldc: compute copy leading dimension
   int R, C;       // valid weight rows (tile columns) and weight columns (tile rows)
   float alpha, lr;
@@ -664,6 +665,10 @@ struct EpiSgdT : EpiZeroInit {
                 nv[e] = ((alpha != 0.0f) ? alpha * w[ii][g][e] : 0.0f) - lr * acc[i0 + ii][j][4 * g + e];
               *reinterpret_cast<f32x4_t *>(out + (long)r * ldw + j0) = nv;
               if (Wc) store4(Wc + (long)r * ldc + j0, nv);
+              if (WcT) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) WcT[(long)(j0 + e) * ldc + r] = from_f32<T>(nv[e]);
+              }
             }
         }
       }
@@ -692,6 +697,10 @@ struct EpiSgdT : EpiZeroInit {
             }
             *reinterpret_cast<f32x4_t *>(out + idx) = nv;
             if (Wc) store4(Wc + (long)r * ldc + j0, nv);
+            if (WcT) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) WcT[(long)(j0 + e) * ldc + r] = from_f32<T>(nv[e]);
+            }
           } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
@@ -700,6 +709,7 @@ struct EpiSgdT : EpiZeroInit {
                 const float nv = w - lr * acc[i][j][4 * g + e];
                 out[idx + e] = nv;
                 if (Wc) Wc[(long)r * ldc + j0 + e] = from_f32<T>(nv);
+                if (WcT) WcT[(long)(j0 + e) * ldc + r] = from_f32<T>(nv);
               }
           }
         }

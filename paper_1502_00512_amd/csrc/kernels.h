@@ -17,18 +17,42 @@ __global__ void stream_chunk_kernel(const int32_t *__restrict__ tok, long L, lon
   y[i] = tok[p + 1];
 }
 
-// Token check + re-layout into the padded window: xp/yp[t*Bp + s]; padding rows get -1.  Ids outside
-// [0, V) are clamped and raise flags[0].  Also marks padded positions with lse = +inf so that the
-// softmax-gradient pass produces exact zeros there, copies the carried state into slot 0 of the
-// hidden-state buffer (compute type, padded with zeros) and clears the 17 barrier / ticket counters of
-// the persistent recurrent kernel that follows (slot / counters == nullptr: tokens only).  Grid: enough
-// threads for max(Mp, Bp*Hp).
+// First kernel of a window, two kinds of workgroups:
+// blockIdx.x < prep_blocks: token check + re-layout into the padded window: xp/yp[t*Bp + s]; padding rows
+//   get -1.  Ids outside [0, V) are clamped and raise flags[0].  Also marks padded positions with
+//   lse = +inf so that the softmax-gradient pass produces exact zeros there, copies the carried state into
+//   slot 0 of the hidden-state buffer (compute type, padded with zeros) and clears the 17 barrier / ticket
+//   counters of the persistent recurrent kernel that follows (slot / counters == nullptr: tokens only).
+//   prep_blocks covers max(Mp, Bp*Hp) threads.
+// blockIdx.x >= prep_blocks (present when X != nullptr): a1, embedding gather of padded row
+//   r = blockIdx.x - prep_blocks: X[r][:] = E[x of that position][:] (fp32), zero on padding.
 template <typename T>
-__global__ void prep_tokens_kernel(const int32_t *__restrict__ x, const int32_t *__restrict__ y, int Tn, int B, int Bp,
-                                   int Mp, int V, int32_t *__restrict__ xp, int32_t *__restrict__ yp,
-                                   float *__restrict__ lse, int32_t *__restrict__ flags,
-                                   const float *__restrict__ h_state, int H, int Hp, T *__restrict__ slot,
-                                   unsigned *__restrict__ counters) {
+__global__ void __launch_bounds__(256) prep_tokens_kernel(const int32_t *__restrict__ x, const int32_t *__restrict__ y,
+                                                          int Tn, int B, int Bp, int Mp, int V,
+                                                          int32_t *__restrict__ xp, int32_t *__restrict__ yp,
+                                                          float *__restrict__ lse, int32_t *__restrict__ flags,
+                                                          const float *__restrict__ h_state, int H, int Hp,
+                                                          T *__restrict__ slot, unsigned *__restrict__ counters,
+                                                          int prep_blocks, const float *__restrict__ E,
+                                                          float *__restrict__ X) {
+  if ((int)blockIdx.x >= prep_blocks) {
+    const int row = blockIdx.x - prep_blocks;
+    const int t = row / Bp, s = row % Bp;
+    int w = -1;
+    if (t < Tn && s < B) w = min(max(x[t * B + s], 0), V - 1);
+    const float *src = E + (long)max(w, 0) * H;
+    float *dst = X + (long)row * Hp;
+    if ((H & 3) == 0) {
+      for (int c = threadIdx.x * 4; c < Hp; c += 256 * 4) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (w >= 0 && c < H) v = *reinterpret_cast<const float4 *>(src + c);
+        *reinterpret_cast<float4 *>(dst + c) = v;
+      }
+    } else {
+      for (int c = threadIdx.x; c < Hp; c += 256) dst[c] = (w >= 0 && c < H) ? src[c] : 0.0f;
+    }
+    return;
+  }
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (counters && i < 17) counters[i] = 0u;
   if (slot && i < (long)Bp * Hp) {
@@ -51,24 +75,6 @@ __global__ void prep_tokens_kernel(const int32_t *__restrict__ x, const int32_t 
   }
   xp[i] = xv;
   if (yp) yp[i] = yv;
-}
-
-// ---- a1: embedding gather: X[row][:] = E[xp[row]][:] (fp32), zero on padding -------------------
-__global__ void gather_kernel(const float *__restrict__ E, const int32_t *__restrict__ xp, int H, int Hp,
-                              float *__restrict__ X) {
-  const int row = blockIdx.x;
-  const int w = xp[row];
-  const float *src = E + (long)max(w, 0) * H;
-  float *dst = X + (long)row * Hp;
-  if ((H & 3) == 0) {
-    for (int c = threadIdx.x * 4; c < Hp; c += blockDim.x * 4) {
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (w >= 0 && c < H) v = *reinterpret_cast<const float4 *>(src + c);
-      *reinterpret_cast<float4 *>(dst + c) = v;
-    }
-  } else {
-    for (int c = threadIdx.x; c < Hp; c += blockDim.x) dst[c] = (w >= 0 && c < H) ? src[c] : 0.0f;
-  }
 }
 
 template <typename T>

@@ -22,41 +22,39 @@ __device__ inline float logisticf_(float d) {
   return (d >= 0.0f) ? 1.0f / (1.0f + e) : e / (1.0f + e);
 }
 
-// Noise ids checked (flags[0] on an id outside [0,V), clamped), per-noise-word offset
-// off[j] = b[n_j] - lnZ - ln K - lnq[n_j] (0 for the padding j >= K) and the update list ids[K + M].
-__global__ void nce_prep_kernel(const int32_t *__restrict__ noise, int K, int Kp, int V,
-                                const float *__restrict__ lnq, const float *__restrict__ b, float lnZ_lnK,
-                                const int32_t *__restrict__ yp, int M, int B, int Bp, int32_t *__restrict__ noise_c,
-                                float *__restrict__ off, int32_t *__restrict__ ids, int32_t *__restrict__ flags) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < Kp) {
-    int w = 0;
-    float o = 0.0f;
-    if (i < K) {
-      w = noise[i];
-      if (w < 0 || w >= V) {
-        flags[0] = 1;
-        w = min(max(w, 0), V - 1);
-      }
-      o = b[w] - lnZ_lnK - lnq[w];
-      ids[i] = w;
-    }
-    noise_c[i] = w;
-    off[i] = o;
-  } else if (i - Kp < M) {
-    const int m = i - Kp;
-    ids[K + m] = yp[(m / B) * Bp + (m % B)];
-  }
-}
-
-// Wn[j][:] = Wo_c[n_j][:] for j < K, zero rows for K <= j < Kp (Hp is a multiple of 256).
+// Preparation of a window's noise words, one workgroup per (padded) noise slot j < Kp plus ceil(M/256)
+// workgroups for the targets:
+//   noise id checked (flags[0] on an id outside [0,V), clamped); offset off[j] = b[n_j] - lnZ - ln K - lnq[n_j]
+//   (0 for the padding j >= K); panel row Wn[j][:] = Wo_c[n_j][:] (zero rows for the padding; Hp is a multiple
+//   of 256); update list ids[0..K) = noise words, ids[K + m] = target of compact position m.
 template <typename T>
-__global__ void __launch_bounds__(256) nce_gather_rows_kernel(const T *__restrict__ Wo_c, int Hp,
-                                                              const int32_t *__restrict__ noise_c, int K,
-                                                              T *__restrict__ Wn) {
+__global__ void __launch_bounds__(256) nce_prep_kernel(const int32_t *__restrict__ noise, int K, int Kp, int V,
+                                                       const float *__restrict__ lnq, const float *__restrict__ b,
+                                                       float lnZ_lnK, const int32_t *__restrict__ yp, int M, int B,
+                                                       int Bp, const T *__restrict__ Wo_c, int Hp,
+                                                       T *__restrict__ Wn, float *__restrict__ off,
+                                                       int32_t *__restrict__ ids, int32_t *__restrict__ flags) {
   constexpr int VEC = 16 / (int)sizeof(T);
   const int j = blockIdx.x;
-  const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Wo_c + (long)noise_c[j] * Hp);
+  if (j >= Kp) {  // target part of the update list
+    const int m = (j - Kp) * 256 + threadIdx.x;
+    if (m < M) ids[K + m] = yp[(m / B) * Bp + (m % B)];
+    return;
+  }
+  int w = 0;
+  if (j < K) {
+    w = noise[j];
+    const bool bad = w < 0 || w >= V;
+    w = min(max(w, 0), V - 1);
+    if (threadIdx.x == 0) {
+      if (bad) flags[0] = 1;
+      off[j] = b[w] - lnZ_lnK - lnq[w];
+      ids[j] = w;
+    }
+  } else if (threadIdx.x == 0) {
+    off[j] = 0.0f;
+  }
+  const u32x4_t *src = reinterpret_cast<const u32x4_t *>(Wo_c + (long)w * Hp);
   u32x4_t *dst = reinterpret_cast<u32x4_t *>(Wn + (long)j * Hp);
   const u32x4_t zero = {0u, 0u, 0u, 0u};
   for (int c = threadIdx.x; c < Hp / VEC; c += 256) dst[c] = (j < K) ? src[c] : zero;
@@ -135,7 +133,8 @@ __global__ void __launch_bounds__(256) nce_grad_kernel(const float *__restrict__
 // Bias gradient of noise word j: gcol[j] = sum over valid positions of sigmoid(S[row][j] + off[j]) * scale,
 // in two fixed-order levels.  Level 1: workgroup (column block x, row block y) = 64 columns x 16 row
 // groups over the positions m = y, y + gridDim.y, ...; each group sums its positions in ascending order,
-// the 16 group sums are added in order into part[y][j].  Level 2 adds the row blocks in order.
+// the 16 group sums are added in order into part[y][j].  Level 2 (the row blocks, in order) is done by the
+// consumer, nce_row_update_kernel, when it forms the word's bias gradient.
 __global__ void __launch_bounds__(1024) nce_colsum_kernel(const float *__restrict__ S, int Kp, int K,
                                                           const float *__restrict__ off, int Tn, int B, int Bp,
                                                           float scale, float *__restrict__ part) {
@@ -157,14 +156,6 @@ __global__ void __launch_bounds__(1024) nce_colsum_kernel(const float *__restric
   float tot = 0.0f;
   for (int g = 0; g < 16; ++g) tot += sh[g][c];
   part[(long)blockIdx.y * Kp + j] = tot;
-}
-
-__global__ void nce_colsum_merge_kernel(const float *__restrict__ part, int Kp, int nblk, float *__restrict__ gcol) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= Kp) return;
-  float tot = 0.0f;
-  for (int y = 0; y < nblk; ++y) tot += part[(long)y * Kp + j];
-  gcol[j] = tot;
 }
 
 // dHs[row][:] += ct[row] * Wo_c[y_row][:]: the target word's share of what the output layer sends back.
@@ -189,7 +180,8 @@ __global__ void __launch_bounds__(256) nce_target_dhs_kernel(const T *__restrict
 // order) which are then added in order.  Also refreshes the compute copy of the row when Wc != nullptr.
 // compact_ld > 0 redirects the results to compact per-run buffers (see below).
 // The first column block also updates the word's bias the same way:
-//   b_out[w] = alpha*b[w] - lr * (sum of gcol over w's noise entries + sum of ct over its target entries).
+//   b_out[w] = alpha*b[w] - lr * (sum over w's noise entries of their column sums + sum of ct over its target
+//   entries); a noise entry's column sum is the sum, in order, of the gparts row-block partials gpart[y][Kp].
 template <typename T, int VEC>
 __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__restrict__ G, const T *__restrict__ Hs1,
                                                               int Hp, int H, int K, int B, int Bp,
@@ -199,7 +191,8 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
                                                               const int32_t *__restrict__ seg_start,
                                                               const int32_t *__restrict__ nseg,
                                                               const float *__restrict__ W, float *__restrict__ out,
-                                                              T *__restrict__ Wc, const float *__restrict__ gcol,
+                                                              T *__restrict__ Wc, const float *__restrict__ gpart,
+                                                              int gparts, int Kp,
                                                               const float *__restrict__ b, float *__restrict__ b_out,
                                                               float alpha, float lr, int compact_ld) {
   constexpr int PARTS = 16, LANES = 64;
@@ -219,7 +212,8 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
   auto fetch = [&](int r, float (&v)[VEC], float &bv) {
     const int ent = perm[r];
     if (ent < K) {
-      bv = gcol[ent];
+      bv = gpart[ent];
+      for (int y = 1; y < gparts; ++y) bv += gpart[(long)y * Kp + ent];
       if (live) {
         const float *src = G + (long)ent * Hp + col;
 #pragma unroll

@@ -30,7 +30,7 @@ struct WsLayout {
   size_t Wo_c, U_c, UT_c, Hs_c, ZT, dA_c, X32, dHs32, dA32, part32, stat, lse, zy, logp_int, xp, yp, perm, seg, xtmp, ytmp,
       scalars, total;
   // noise-contrastive calls (present when K_max > 0)
-  size_t Wn_c, S32, dS_c, G32, noff, ndt, nct, gcol, noise_c, ids, perm2, seg2;
+  size_t Wn_c, S32, dS_c, G32, noff, ndt, nct, gcol, ids, perm2, seg2;
   // rmsprop calls (present when cfg.rmsprop != 0): gradient buffers the redirected update epilogues fill
   size_t gWo, gU, gb, gN, gbN;
   long partElems;
@@ -184,7 +184,7 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
   L.xtmp = take((size_t)c.T_max * c.B * 4);
   L.ytmp = take((size_t)c.T_max * c.B * 4);
   KpMax = (int)round_up(c.K_max, 256);
-  L.Wn_c = L.S32 = L.dS_c = L.G32 = L.noff = L.ndt = L.nct = L.gcol = L.noise_c = L.ids = L.perm2 = L.seg2 = 0;
+  L.Wn_c = L.S32 = L.dS_c = L.G32 = L.noff = L.ndt = L.nct = L.gcol = L.ids = L.perm2 = L.seg2 = 0;
   if (KpMax > 0) {
     const size_t nent = (size_t)KpMax + (size_t)c.T_max * c.B;
     L.Wn_c = take((size_t)KpMax * Hp * es);
@@ -194,8 +194,7 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
     L.noff = take((size_t)KpMax * 4);
     L.ndt = take((size_t)MpMax * 4);
     L.nct = take((size_t)MpMax * 4);
-    L.gcol = take((size_t)KpMax * 4);
-    L.noise_c = take((size_t)KpMax * 4);
+    L.gcol = take((size_t)16 * KpMax * 4);  // 16 row-block partials of the noise words' bias gradient
     L.ids = take(nent * 4);
     L.perm2 = take(nent * 4);
     L.seg2 = take((nent + 1) * 4);
@@ -354,17 +353,17 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
 
   {
     StageTimer tm(h, RNNLM_STAGE_PREP, st);
-    hipLaunchKernelGGL(prep_tokens_kernel<T>, dim3(blocks_for(std::max<long>(Mp, (long)Bp * Hp), 256)), dim3(256), 0,
-                       st, x, y, Tn, c.B, Bp, Mp, c.V, xp, yp, lse, p_flags(h), h->buf.h_state, c.H, Hp, Hs_c,
-                       p_counter(h));
+    const int prep_blocks = (int)blocks_for(std::max<long>(Mp, (long)Bp * Hp), 256);
+    hipLaunchKernelGGL(prep_tokens_kernel<T>, dim3(prep_blocks + Mrows), dim3(256), 0, st, x, y, Tn, c.B, Bp, Mp, c.V,
+                       xp, yp, lse, p_flags(h), h->buf.h_state, c.H, Hp, Hs_c, p_counter(h), prep_blocks, h->buf.E,
+                       X32);
+    HIP_TRY(hipGetLastError());
     if (sort_inputs) {
       int rc = side_fork(h, 0, st);
       if (rc) return rc;
       rc = sort_segments<T>(h, Tn, at<int32_t>(h, h->L.perm), at<int32_t>(h, h->L.seg), p_nseg(h), h->side);
       if (rc) return rc;
     }
-    hipLaunchKernelGGL(gather_kernel, dim3(Mrows), dim3(256), 0, st, h->buf.E, xp, c.H, Hp, X32);
-    HIP_TRY(hipGetLastError());
   }
 
   if (persistent_ok(h)) {
@@ -430,6 +429,8 @@ int sort_segments(rnnlm_t *h, int Tn, int32_t *perm, int32_t *seg, int32_t *nseg
   return RNNLM_OK;
 }
 
+constexpr int NCE_COLSUM_PARTS = 16;  // row-block partials of the noise words' bias gradient
+
 // One call of the noise-contrastive criterion (Sec. 4.2): K noise words shared by the window.
 struct NceCall {
   const int32_t *noise;
@@ -456,8 +457,8 @@ int nce_forward(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
   const float scale = 1.0f / (float)M;
   {
     StageTimer tm(h, RNNLM_STAGE_NCE_SCORE, st);
-    hipLaunchKernelGGL(nce_prep_kernel, dim3(blocks_for((long)Kp + M, 256)), dim3(256), 0, st, n.noise, K, Kp, c.V, n.lnq,
-                       h->buf.b, lnZ_lnK, yp, M, c.B, Bp, at<int32_t>(h, h->L.noise_c), at<float>(h, h->L.noff),
+    hipLaunchKernelGGL(nce_prep_kernel<T>, dim3(Kp + blocks_for(M, 256)), dim3(256), 0, st, n.noise, K, Kp, c.V, n.lnq,
+                       h->buf.b, lnZ_lnK, yp, M, c.B, Bp, at<T>(h, h->L.Wo_c), Hp, Wn, at<float>(h, h->L.noff),
                        at<int32_t>(h, h->L.ids), p_flags(h));
     if (n.sort_ids) {  // the touched-word list is complete: sort it next to the contractions
       int rc = side_fork(h, 1, st);
@@ -470,8 +471,6 @@ int nce_forward(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
       hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(1024), 0, h->side, ids, at<int32_t>(h, h->L.perm2), nent, 1, 1,
                          at<int32_t>(h, h->L.seg2), p_nseg2(h));
     }
-    hipLaunchKernelGGL(nce_gather_rows_kernel<T>, dim3(Kp), dim3(256), 0, st, at<T>(h, h->L.Wo_c), Hp,
-                       at<int32_t>(h, h->L.noise_c), K, Wn);
     hipLaunchKernelGGL(nce_target_score_kernel<T>, dim3(blocks_for(Mrows, 4)), dim3(256), 0, st, Hs1,
                        at<T>(h, h->L.Wo_c), Hp, yp, h->buf.b, n.lnq, lnZ_lnK, Mrows, c.B, Bp, at<float>(h, h->L.ndt),
                        (float *)nullptr);
@@ -486,13 +485,9 @@ int nce_forward(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
   hipLaunchKernelGGL(nce_grad_kernel<T>, dim3(Mp), dim3(256), 0, st, S, Kp, K, at<float>(h, h->L.noff),
                      at<float>(h, h->L.ndt), Tn, c.B, Bp, scale, at<T>(h, h->L.dS_c), at<float>(h, h->L.nct),
                      at<float>(h, h->L.logp_int), n.J_out);
-  // bias-gradient column sums in two levels; the 16 x Kp level-1 partials borrow the gradient panel
-  // (Kp x Hp floats, Hp >= 256), which is written only later in the window
-  const int rowBlocks = 16;
-  hipLaunchKernelGGL(nce_colsum_kernel, dim3(Kp / 64, rowBlocks), dim3(1024), 0, st, S, Kp, K,
-                     at<float>(h, h->L.noff), Tn, c.B, Bp, scale, at<float>(h, h->L.G32));
-  hipLaunchKernelGGL(nce_colsum_merge_kernel, dim3(blocks_for(Kp, 256)), dim3(256), 0, st, at<float>(h, h->L.G32), Kp,
-                     rowBlocks, at<float>(h, h->L.gcol));
+  // bias-gradient column sums of the noise words: 16 row-block partials, added in order by the row update
+  hipLaunchKernelGGL(nce_colsum_kernel, dim3(Kp / 64, NCE_COLSUM_PARTS), dim3(1024), 0, st, S, Kp, K,
+                     at<float>(h, h->L.noff), Tn, c.B, Bp, scale, at<float>(h, h->L.gcol));
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }
@@ -556,11 +551,11 @@ int nce_update(rnnlm_t *h, int Tn, const NceCall &n, const UpdateTargets &u, hip
   if (c.H % 4 == 0) {
     hipLaunchKernelGGL((nce_row_update_kernel<T, 4>), dim3(nent, (c.H + 255) / 256), dim3(1024), 0, st, G, Hs1, Hp,
                        c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
-                       at<float>(h, h->L.gcol), h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
+                       at<float>(h, h->L.gcol), NCE_COLSUM_PARTS, Kp, h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
   } else {
     hipLaunchKernelGGL((nce_row_update_kernel<T, 1>), dim3(nent, (c.H + 63) / 64), dim3(1024), 0, st, G, Hs1, Hp,
                        c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
-                       at<float>(h, h->L.gcol), h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
+                       at<float>(h, h->L.gcol), NCE_COLSUM_PARTS, Kp, h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
   }
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
@@ -706,6 +701,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     epi.W = h->buf.U;
     epi.out = u.U;
     epi.Wc = u.refresh_copies ? U_c : nullptr;
+    epi.WcT = u.refresh_copies ? at<T>(h, h->L.UT_c) : nullptr;  // the backward pass reads the transposed copy
     epi.ldw = c.H;
     epi.ldc = Hp;
     epi.R = c.H;
@@ -718,11 +714,6 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
       HIP_TRY((launch_gemm<T, 64, 64, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
     } else {
       HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
-    }
-    if (u.refresh_copies) {
-      hipLaunchKernelGGL(transpose_kernel<T>, dim3(Hp / 32, Hp / 32), dim3(256), 0, st, U_c, Hp,
-                         at<T>(h, h->L.UT_c));
-      HIP_TRY(hipGetLastError());
     }
   }
   // wait for the embedding update running on the side stream
@@ -1122,10 +1113,11 @@ int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, 
   if (!h || !x || !perm || !seg_start || !nseg || T < 1 || T > h->cfg.T_max) return RNNLM_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   const int Mp = (int)round_up((long)T * h->Bp, PAD_M);
-  hipLaunchKernelGGL(prep_tokens_kernel<float>, dim3(blocks_for(Mp, 256)), dim3(256), 0, st, x,
-                     (const int32_t *)nullptr, T, h->cfg.B, h->Bp, Mp, h->cfg.V, at<int32_t>(h, h->L.xp),
-                     (int32_t *)nullptr, at<float>(h, h->L.lse), p_flags(h), (const float *)nullptr, 0, 0,
-                     (float *)nullptr, (unsigned *)nullptr);
+  const int prep_blocks = (int)blocks_for(Mp, 256);
+  hipLaunchKernelGGL(prep_tokens_kernel<float>, dim3(prep_blocks), dim3(256), 0, st, x, (const int32_t *)nullptr, T,
+                     h->cfg.B, h->Bp, Mp, h->cfg.V, at<int32_t>(h, h->L.xp), (int32_t *)nullptr,
+                     at<float>(h, h->L.lse), p_flags(h), (const float *)nullptr, 0, 0, (float *)nullptr,
+                     (unsigned *)nullptr, prep_blocks, (const float *)nullptr, (float *)nullptr);
   HIP_TRY(hipGetLastError());
   return sort_segments<float>(h, T, perm, seg_start, nseg, st);
 }
