@@ -16,6 +16,8 @@
 
 namespace rnnlm_dev {
 
+constexpr int NCE_COLSUM_PARTS = 16;  // row-block partials of the noise words' bias gradient
+
 __device__ inline float softplusf_(float d) { return fmaxf(d, 0.0f) + log1pf(__expf(-fabsf(d))); }
 __device__ inline float logisticf_(float d) {
   const float e = __expf(-fabsf(d));
@@ -181,7 +183,8 @@ __global__ void __launch_bounds__(256) nce_target_dhs_kernel(const T *__restrict
 // compact_ld > 0 redirects the results to compact per-run buffers (see below).
 // The first column block also updates the word's bias the same way:
 //   b_out[w] = alpha*b[w] - lr * (sum over w's noise entries of their column sums + sum of ct over its target
-//   entries); a noise entry's column sum is the sum, in order, of the gparts row-block partials gpart[y][Kp].
+//   entries); a noise entry's column sum is the sum, in order, of the NCE_COLSUM_PARTS row-block partials
+//   gpart[y][Kp].
 template <typename T, int VEC>
 __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__restrict__ G, const T *__restrict__ Hs1,
                                                               int Hp, int H, int K, int B, int Bp,
@@ -192,7 +195,7 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
                                                               const int32_t *__restrict__ nseg,
                                                               const float *__restrict__ W, float *__restrict__ out,
                                                               T *__restrict__ Wc, const float *__restrict__ gpart,
-                                                              int gparts, int Kp,
+                                                              int Kp,
                                                               const float *__restrict__ b, float *__restrict__ b_out,
                                                               float alpha, float lr, int compact_ld) {
   constexpr int PARTS = 16, LANES = 64;
@@ -206,14 +209,21 @@ __global__ void __launch_bounds__(1024) nce_row_update_kernel(const float *__res
   float acc[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
-  float bacc = 0.0f;  // every lane of a part walks the same entries, so each holds the part's bias sum
+  float bacc = 0.0f;  // bias sum of the part (meaningful in its first lane)
   const bool live = col < H;
   // one member: its row (times its coefficient) and its bias term
   auto fetch = [&](int r, float (&v)[VEC], float &bv) {
     const int ent = perm[r];
     if (ent < K) {
-      bv = gpart[ent];
-      for (int y = 1; y < gparts; ++y) bv += gpart[(long)y * Kp + ent];
+      bv = 0.0f;
+      if (lane == 0) {  // the part's bias sum is kept by its first lane only
+        float pv[NCE_COLSUM_PARTS];  // all partials requested before any is added
+#pragma unroll
+        for (int y = 0; y < NCE_COLSUM_PARTS; ++y) pv[y] = gpart[(long)y * Kp + ent];
+        bv = pv[0];
+#pragma unroll
+        for (int y = 1; y < NCE_COLSUM_PARTS; ++y) bv += pv[y];
+      }
       if (live) {
         const float *src = G + (long)ent * Hp + col;
 #pragma unroll

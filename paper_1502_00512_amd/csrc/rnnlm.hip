@@ -194,7 +194,7 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
     L.noff = take((size_t)KpMax * 4);
     L.ndt = take((size_t)MpMax * 4);
     L.nct = take((size_t)MpMax * 4);
-    L.gcol = take((size_t)16 * KpMax * 4);  // 16 row-block partials of the noise words' bias gradient
+    L.gcol = take((size_t)NCE_COLSUM_PARTS * KpMax * 4);  // 16 row-block partials of the noise words' bias gradient
     L.ids = take(nent * 4);
     L.perm2 = take(nent * 4);
     L.seg2 = take((nent + 1) * 4);
@@ -429,8 +429,6 @@ int sort_segments(rnnlm_t *h, int Tn, int32_t *perm, int32_t *seg, int32_t *nseg
   return RNNLM_OK;
 }
 
-constexpr int NCE_COLSUM_PARTS = 16;  // row-block partials of the noise words' bias gradient
-
 // One call of the noise-contrastive criterion (Sec. 4.2): K noise words shared by the window.
 struct NceCall {
   const int32_t *noise;
@@ -551,11 +549,11 @@ int nce_update(rnnlm_t *h, int Tn, const NceCall &n, const UpdateTargets &u, hip
   if (c.H % 4 == 0) {
     hipLaunchKernelGGL((nce_row_update_kernel<T, 4>), dim3(nent, (c.H + 255) / 256), dim3(1024), 0, st, G, Hs1, Hp,
                        c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
-                       at<float>(h, h->L.gcol), NCE_COLSUM_PARTS, Kp, h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
+                       at<float>(h, h->L.gcol), Kp, h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
   } else {
     hipLaunchKernelGGL((nce_row_update_kernel<T, 1>), dim3(nent, (c.H + 63) / 64), dim3(1024), 0, st, G, Hs1, Hp,
                        c.H, K, c.B, Bp, at<float>(h, h->L.nct), ids, perm, seg, p_nseg2(h), h->buf.Wo, u.Wo, Wc,
-                       at<float>(h, h->L.gcol), NCE_COLSUM_PARTS, Kp, h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
+                       at<float>(h, h->L.gcol), Kp, h->buf.b, u.b, u.alpha, u.lr, u.wo_compact_ld);
   }
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
