@@ -71,6 +71,9 @@ typedef struct {
                         not used (no workspace is set aside for them), >= 0, at most 65536 */
   int32_t rmsprop;   /* 1: rnnlm_train_chunk_rmsprop may be called (adds gradient buffers of the size of Wo, U
                         and b to the workspace); 0: it may not */
+  int32_t P;         /* 0: the plain architecture above.  > 0: the compressed architecture of Sec. 5.3 with
+                        layers of P units below and above the state and tied word matrices (see "Compressed
+                        architecture" below); requires K_max = 0 and rmsprop = 0 */
 } rnnlm_config;
 
 typedef struct {
@@ -81,6 +84,9 @@ typedef struct {
   float *h_state;         /* dev [B][H]  carried hidden state */
   void *workspace;        /* dev, 256-byte aligned, >= rnnlm_workspace_bytes(cfg) */
   size_t workspace_bytes;
+  /* compressed architecture only (cfg.P > 0; NULL otherwise): then E is dev [V][P] and Wo must be NULL */
+  float *A;               /* dev [H][P]  layer below the state -> state */
+  float *C;               /* dev [P][H]  state -> layer above the state */
 } rnnlm_buffers;
 
 /* Device bytes of workspace the configuration needs (0 if cfg is invalid). */
@@ -181,6 +187,42 @@ int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t
 int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lnZ, float *score,
                         void *stream);
 
+/* ---- Compressed architecture (Sec. 5.3: word prediction under a memory limit) ---------------------------
+ * Sec. 5.3 shrinks the network by inserting layers of 512 units below and above the hidden state, tying the
+ * input-side and output-side word matrices as each other's transpose, and quantising all weights, trained
+ * end to end.  It gives no formulas; the readings taken (cfg.P > 0 selects this model):
+ *     x_t = E[w_t] (P values),  h_t = sigmoid(A x_t + U h_{t-1}),  p_t = C h_t,  z_t = E p_t + b
+ * - the inserted layers are linear and have no bias (a low-rank factorisation of the two word-sized
+ * matrices); E[V][P] is both the table of input rows and the output matrix; b stays a parameter.
+ * rnnlm_forward_logprob, rnnlm_train_chunk, rnnlm_perplexity, rnnlm_stream_chunk and the state calls work on
+ * this model unchanged (the tied matrix receives the sum of its input-side and output-side gradients; the
+ * output-side part is applied first); rnnlm_grad_chunk_compressed exports its gradients.  The
+ * noise-contrastive, rmsprop and rnnlm_forward_score calls and rnnlm_grad_chunk return RNNLM_ERR_ARG. */
+
+/* rnnlm_grad_chunk for the compressed architecture: gradients of the window's mean negative
+ * log-likelihood into dE: dev float[V][P] (both roles of the tied matrix added), dA: dev float[H][P],
+ * dU: dev float[H][H], dC: dev float[P][H], db: dev float[V] (all 16-byte aligned); logp: dev float[T][B] or
+ * NULL.  Parameters and h_state are left unchanged.  Requires cfg.P > 0. */
+int rnnlm_grad_chunk_compressed(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *dE, float *dA,
+                                float *dU, float *dC, float *db, float *logp, void *stream);
+
+/* 8-bit weights of the compressed architecture (Sec. 5.3 quantises all the weights; the scheme is a
+ * reading): symmetric, linear, one scale per matrix row, scale = max|row| / 127 (1 for an all-zero row),
+ * code = round-half-to-even(w / scale) in [-127, 127], both computed in fp32.  Caller-owned device
+ * arrays: codes int8 [rows][cols] of the matrix, scales float [rows]. */
+typedef struct {
+  int8_t *qE; float *sE; /* dev [V][P], [V] */
+  int8_t *qA; float *sA; /* dev [H][P], [H] */
+  int8_t *qU; float *sU; /* dev [H][H], [H] */
+  int8_t *qC; float *sC; /* dev [P][H], [P] */
+} rnnlm_quantized;
+
+/* Quantises E, A, U and C from the fp32 masters into q and makes the model RUN on the quantised values
+ * w' = code * scale: the compute copies every forward pass reads are rebuilt from them (the masters and b
+ * are not touched, so rnnlm_sync_compute_copies returns to the unquantised model).  Training calls after
+ * this update the masters as usual and refresh the copies of what they touch.  Requires cfg.P > 0. */
+int rnnlm_quantize_weights(rnnlm_t *h, const rnnlm_quantized *q, void *stream);
+
 /* Perplexity (Sec. 1, Sec. 4.2: normalised output) of tok: dev int32[N]: h_state is reset to zero,
  * the array is split into B streams as in rnnlm_stream_chunk and every full window of T positions
  * is scored; *ppl (HOST) = exp(-sum logp / scored), *scored (HOST, may be NULL) = windows*B*T.
@@ -191,8 +233,8 @@ int rnnlm_perplexity(rnnlm_t *h, const int32_t *tok, int64_t N, int32_t T, doubl
 /* h_state <- 0. */
 int rnnlm_reset_state(rnnlm_t *h, void *stream);
 
-/* Rebuilds the compute copies of U and Wo from the fp32 masters (after the caller overwrote the
- * masters, e.g. when loading a checkpoint). */
+/* Rebuilds the compute copies of U and Wo (compressed architecture: of E, A, U and C) from the fp32
+ * masters (after the caller overwrote the masters, e.g. when loading a checkpoint). */
 int rnnlm_sync_compute_copies(rnnlm_t *h, void *stream);
 
 /* Waits for the stream and returns RNNLM_ERR_TOKEN_RANGE if any call since the last check saw an
@@ -241,7 +283,9 @@ typedef enum {
   RNNLM_STAGE_NCE_BWD_W = 14,   /* noise-row weight gradient contraction */
   RNNLM_STAGE_NCE_UPDATE = 15,  /* sort/segments of the touched words + row and bias updates */
   RNNLM_STAGE_RMSPROP = 16,     /* rmsprop calls: statistics + scaled updates from the gradient buffers */
-  RNNLM_STAGE_COUNT = 17
+  RNNLM_STAGE_PROJ = 17,        /* compressed architecture: the contractions through the layers below and above
+                                   the state (forward, backward and their weight updates) */
+  RNNLM_STAGE_COUNT = 18
 } rnnlm_stage;
 
 /* Brackets every later execution of the stages whose bit (1u << stage) is set in stage_mask with a

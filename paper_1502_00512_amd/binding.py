@@ -23,15 +23,17 @@ SYMBOLS = [
     "rnnlm_profile_enable", "rnnlm_profile_read", "rnnlm_set_barrier_spin_limit", "rnnlm_measure_peaks",
     "rnnlm_nce_train_chunk", "rnnlm_nce_grad_chunk", "rnnlm_forward_score",
     "rnnlm_train_chunk_rmsprop", "rnnlm_nce_train_chunk_rmsprop",
+    "rnnlm_grad_chunk_compressed", "rnnlm_quantize_weights",
 ]
 
 STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce",
-          "nce_score", "nce_grad", "nce_bwd_h", "nce_bwd_w", "nce_update", "rmsprop"]
+          "nce_score", "nce_grad", "nce_bwd_h", "nce_bwd_w", "nce_update", "rmsprop", "proj"]
 
 
 class rnnlm_config(C.Structure):
     _fields_ = [("V", C.c_int32), ("H", C.c_int32), ("B", C.c_int32), ("T_max", C.c_int32),
-                ("precision", C.c_int32), ("device", C.c_int32), ("K_max", C.c_int32), ("rmsprop", C.c_int32)]
+                ("precision", C.c_int32), ("device", C.c_int32), ("K_max", C.c_int32), ("rmsprop", C.c_int32),
+                ("P", C.c_int32)]
 
 
 class rnnlm_rmsprop_state(C.Structure):
@@ -40,7 +42,13 @@ class rnnlm_rmsprop_state(C.Structure):
 
 class rnnlm_buffers(C.Structure):
     _fields_ = [("E", C.c_void_p), ("U", C.c_void_p), ("Wo", C.c_void_p), ("b", C.c_void_p),
-                ("h_state", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("h_state", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("A", C.c_void_p), ("C", C.c_void_p)]
+
+
+class rnnlm_quantized(C.Structure):
+    _fields_ = [("qE", C.c_void_p), ("sE", C.c_void_p), ("qA", C.c_void_p), ("sA", C.c_void_p),
+                ("qU", C.c_void_p), ("sU", C.c_void_p), ("qC", C.c_void_p), ("sC", C.c_void_p)]
 
 
 class RnnlmError(RuntimeError):
@@ -84,6 +92,8 @@ def load():
     lib.rnnlm_nce_train_chunk_rmsprop.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, f32, f32, f32,
                                                   C.POINTER(rnnlm_rmsprop_state), vp, vp, vp]
     lib.rnnlm_forward_score.argtypes = [vp, vp, vp, i32, f32, vp, vp]
+    lib.rnnlm_grad_chunk_compressed.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.rnnlm_quantize_weights.argtypes = [vp, C.POINTER(rnnlm_quantized), vp]
     lib.rnnlm_profile_enable.argtypes = [vp, C.c_uint32]
     lib.rnnlm_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i64)]
     lib.rnnlm_status_string.argtypes = [C.c_int]
@@ -114,27 +124,42 @@ def _stream(stream):
     return C.c_void_p(s.cuda_stream)
 
 
-def rnnlm_workspace_bytes(V, H, B, T_max, precision, device=0, K_max=0, rmsprop=0) -> int:
-    cfg = rnnlm_config(V, H, B, T_max, precision, device, K_max, rmsprop)
+def rnnlm_workspace_bytes(V, H, B, T_max, precision, device=0, K_max=0, rmsprop=0, P=0) -> int:
+    cfg = rnnlm_config(V, H, B, T_max, precision, device, K_max, rmsprop, P)
     return int(load().rnnlm_workspace_bytes(C.byref(cfg)))
 
 
 class Rnnlm:
-    """Owns the torch tensors (masters, state, workspace) and the library handle."""
+    """Owns the torch tensors (masters, state, workspace) and the library handle.
+
+    Plain architecture: E[V][H], U, Wo[V][H], b.  Compressed architecture (Sec. 5.3): pass Wo=None and
+    A[H][P], C[P][H]; then E is the tied word matrix [V][P]."""
 
     def __init__(self, E, U, Wo, b, B: int, T_max: int, precision: int, device: int = 0, K_max: int = 0,
-                 rmsprop: bool = False, r_init: float = 1.0):
+                 rmsprop: bool = False, r_init: float = 1.0, A=None, C_=None):
         import torch
         self.lib = load()
         dev = torch.device("cuda", device)
         f = lambda a: torch.as_tensor(a, dtype=torch.float32).contiguous().to(dev).clone()
-        self.E, self.U, self.Wo, self.b = f(E), f(U), f(Wo), f(b)
-        self.V, self.H = self.E.shape
+        self.E, self.U, self.b = f(E), f(U), f(b)
+        self.H = self.U.shape[0]
+        self.V = self.E.shape[0]
+        self.P = 0
+        self.Wo = self.A = self.C = None
+        if A is not None:
+            assert Wo is None and C_ is not None
+            self.A, self.C = f(A), f(C_)
+            self.P = self.E.shape[1]
+            assert self.A.shape == (self.H, self.P) and self.C.shape == (self.P, self.H)
+        else:
+            self.Wo = f(Wo)
+            assert self.E.shape == (self.V, self.H) and self.Wo.shape == (self.V, self.H)
         self.B, self.T_max, self.precision, self.device = int(B), int(T_max), int(precision), dev
-        assert self.U.shape == (self.H, self.H) and self.Wo.shape == (self.V, self.H) and self.b.shape == (self.V,)
+        assert self.U.shape == (self.H, self.H) and self.b.shape == (self.V,)
         self.h_state = torch.zeros(self.B, self.H, dtype=torch.float32, device=dev)
         self.K_max = int(K_max)
-        cfg = rnnlm_config(self.V, self.H, self.B, self.T_max, self.precision, device, self.K_max, int(bool(rmsprop)))
+        cfg = rnnlm_config(self.V, self.H, self.B, self.T_max, self.precision, device, self.K_max, int(bool(rmsprop)),
+                           self.P)
         if rmsprop:  # the caller-owned statistics, all starting at r_init
             fill = lambda *shp: torch.full(shp, float(r_init), dtype=torch.float32, device=dev)
             self.rE, self.rU, self.rWo, self.rb = fill(self.V), fill(self.H, self.H), fill(self.V), fill(self.V)
@@ -144,8 +169,9 @@ class Rnnlm:
         if nbytes == 0:
             raise RnnlmError(-1, "rnnlm_workspace_bytes")
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        buf = rnnlm_buffers(self.E.data_ptr(), self.U.data_ptr(), self.Wo.data_ptr(), self.b.data_ptr(),
-                            self.h_state.data_ptr(), self.workspace.data_ptr(), nbytes)
+        opt = lambda t: None if t is None else t.data_ptr()
+        buf = rnnlm_buffers(self.E.data_ptr(), self.U.data_ptr(), opt(self.Wo), self.b.data_ptr(),
+                            self.h_state.data_ptr(), self.workspace.data_ptr(), nbytes, opt(self.A), opt(self.C))
         self.handle = C.c_void_p()
         torch.cuda.synchronize(dev)
         _ok(self.lib.rnnlm_init(C.byref(cfg), C.byref(buf), C.byref(self.handle)), "rnnlm_init")
@@ -194,6 +220,30 @@ class Rnnlm:
         _ok(self.lib.rnnlm_grad_chunk(self.handle, _ptr(x), _ptr(y), x.shape[0], _ptr(dE), _ptr(dU), _ptr(dWo),
                                       _ptr(db), _ptr(logp), _stream(stream)), "rnnlm_grad_chunk")
         return dict(gE=dE, gU=dU, gWo=dWo, gb=db, logp=logp)
+
+    def rnnlm_grad_chunk_compressed(self, x, y, want_logp=True, stream=None):
+        import torch
+        z = lambda *s: torch.empty(*s, dtype=torch.float32, device=self.device)
+        dE, dA, dU, dC, db = z(self.V, self.P), z(self.H, self.P), z(self.H, self.H), z(self.P, self.H), z(self.V)
+        logp = z(x.shape[0], self.B) if want_logp else None
+        _ok(self.lib.rnnlm_grad_chunk_compressed(self.handle, _ptr(x), _ptr(y), x.shape[0], _ptr(dE), _ptr(dA),
+                                                 _ptr(dU), _ptr(dC), _ptr(db), _ptr(logp), _stream(stream)),
+            "rnnlm_grad_chunk_compressed")
+        return dict(gE=dE, gA=dA, gU=dU, gC=dC, gb=db, logp=logp)
+
+    def rnnlm_quantize_weights(self, stream=None):
+        """Returns dict name -> (codes int8 tensor, scale float tensor); the model then runs on the quantised values."""
+        import torch
+        out = {}
+        ptrs = []
+        for name, W in (("E", self.E), ("A", self.A), ("U", self.U), ("C", self.C)):
+            q = torch.empty(W.shape, dtype=torch.int8, device=self.device)
+            s = torch.empty(W.shape[0], dtype=torch.float32, device=self.device)
+            out[name] = (q, s)
+            ptrs += [q.data_ptr(), s.data_ptr()]
+        qs = rnnlm_quantized(*ptrs)
+        _ok(self.lib.rnnlm_quantize_weights(self.handle, C.byref(qs), _stream(stream)), "rnnlm_quantize_weights")
+        return out
 
     def rnnlm_perplexity(self, tok, T: int, stream=None):
         ppl = C.c_double(0.0)

@@ -603,6 +603,31 @@ struct EpiPartial : EpiZeroInit {
   }
 };
 
+// Plain store of the tile into a tile-padded buffer, in fp32 (out32) and/or in the compute type (outc).
+template <typename T>
+struct EpiStore : EpiZeroInit {
+  float *out32;
+  T *outc;
+  long ld;
+  template <int BM, int BN>
+  static constexpr int lds_bytes() { return 0; }
+  template <int BM, int BN, int TM, int TN, int NT>
+  __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const long col = c.tile_col0 + c.wcol + j * 32 + (c.lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const long row = c.tile_row0 + c.wrow + i * 32 + RNNLM_ACC_ROW(r, c.lane);
+          if (out32) out32[row * ld + col] = acc[i][j][r];
+          if (outc) outc[row * ld + col] = from_f32<T>(acc[i][j][r]);
+        }
+      }
+  }
+};
+
 // Fused SGD (Sec. 4.2) on a weight-gradient contraction computed TRANSPOSED: the accumulator tile is
 // C[j][r] = dLoss/dW[r][j] (rows = columns j of the weight matrix, columns = its rows r), so a lane
 // holds runs of 4 consecutive j for one weight row and updates W[r][j..j+3] with one 16-byte

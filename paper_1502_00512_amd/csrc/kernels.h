@@ -24,8 +24,10 @@ __global__ void stream_chunk_kernel(const int32_t *__restrict__ tok, long L, lon
 //   slot 0 of the hidden-state buffer (compute type, padded with zeros) and clears the 17 barrier / ticket
 //   counters of the persistent recurrent kernel that follows (slot / counters == nullptr: tokens only).
 //   prep_blocks covers max(Mp, Bp*Hp) threads.
-// blockIdx.x >= prep_blocks (present when X != nullptr): a1, embedding gather of padded row
-//   r = blockIdx.x - prep_blocks: X[r][:] = E[x of that position][:] (fp32), zero on padding.
+// blockIdx.x >= prep_blocks (present when X or Xc != nullptr): a1, embedding gather of padded row
+//   r = blockIdx.x - prep_blocks: X[r][:] = E[x of that position][:] (fp32), zero on padding.  Compressed
+//   architecture (Xc != nullptr): the row is an operand of the contraction through the layer below the
+//   state, so it is copied in the compute type from the tile-padded compute copy Ec[.][ldc] into Xc[r][ldc].
 template <typename T>
 __global__ void __launch_bounds__(256) prep_tokens_kernel(const int32_t *__restrict__ x, const int32_t *__restrict__ y,
                                                           int Tn, int B, int Bp, int Mp, int V,
@@ -34,12 +36,21 @@ __global__ void __launch_bounds__(256) prep_tokens_kernel(const int32_t *__restr
                                                           const float *__restrict__ h_state, int H, int Hp,
                                                           T *__restrict__ slot, unsigned *__restrict__ counters,
                                                           int prep_blocks, const float *__restrict__ E,
-                                                          float *__restrict__ X) {
+                                                          float *__restrict__ X, const T *__restrict__ Ec = nullptr,
+                                                          int ldc = 0, T *__restrict__ Xc = nullptr) {
   if ((int)blockIdx.x >= prep_blocks) {
     const int row = blockIdx.x - prep_blocks;
     const int t = row / Bp, s = row % Bp;
     int w = -1;
     if (t < Tn && s < B) w = min(max(x[t * B + s], 0), V - 1);
+    if (Xc) {
+      const u32x4_t *src16 = reinterpret_cast<const u32x4_t *>(Ec + (long)max(w, 0) * ldc);
+      u32x4_t *dst16 = reinterpret_cast<u32x4_t *>(Xc + (long)row * ldc);
+      const int n16 = ldc * (int)sizeof(T) / 16;
+      const u32x4_t zero = {0u, 0u, 0u, 0u};
+      for (int c = threadIdx.x; c < n16; c += 256) dst16[c] = (w >= 0) ? src16[c] : zero;
+      return;
+    }
     const float *src = E + (long)max(w, 0) * H;
     float *dst = X + (long)row * Hp;
     if ((H & 3) == 0) {
@@ -407,14 +418,17 @@ __global__ void segment_kernel(const int32_t *__restrict__ xp, const int32_t *__
 // fetched four at a time so the row loads are independent), which are then added in order
 // 0..PARTS-1: a fixed summation tree, so results are bitwise reproducible.
 // VEC = 4: a lane owns 4 consecutive columns (H % 4 == 0); VEC = 1: any H.
-template <int VEC>
+// Ec (may be nullptr): compute copy [.][ldc] of the updated matrix, refreshed with the new row (the tied word
+// matrix of the compressed architecture is an operand of the output layer as well).
+template <int VEC, typename T>
 __global__ void __launch_bounds__(1024) scatter_update_kernel(const float *__restrict__ dA, int Hp, int H, int B,
                                                               int Bp, const int32_t *__restrict__ xp,
                                                               const int32_t *__restrict__ perm,
                                                               const int32_t *__restrict__ seg_start,
                                                               const int32_t *__restrict__ nseg,
                                                               const float *__restrict__ E, float *__restrict__ out,
-                                                              float alpha, float lr, int compact_ld) {
+                                                              float alpha, float lr, int compact_ld,
+                                                              T *__restrict__ Ec, int ldc) {
   constexpr int PARTS = 4, LANES = 256;
   __shared__ float sh[PARTS][LANES * VEC];
   const int g = blockIdx.x;
@@ -471,7 +485,49 @@ __global__ void __launch_bounds__(1024) scatter_update_kernel(const float *__res
   // compact_ld > 0: the run's result goes to row g of a compact [runs][compact_ld] buffer instead of row w
   const long oidx = compact_ld > 0 ? (long)g * compact_ld + col : idx;
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) out[oidx + e] = ((alpha != 0.0f) ? alpha * E[idx + e] : 0.0f) - lr * acc[e];
+  for (int e = 0; e < VEC; ++e) {
+    const float nv = ((alpha != 0.0f) ? alpha * E[idx + e] : 0.0f) - lr * acc[e];
+    out[oidx + e] = nv;
+    if (Ec) Ec[(long)w * ldc + col + e] = from_f32<T>(nv);
+  }
+}
+
+// fp32 -> compute type, element by element (n elements).
+template <typename T>
+__global__ void to_compute_kernel(const float *__restrict__ src, long n, T *__restrict__ dst) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long stride = (long)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = from_f32<T>(src[i]);
+}
+
+// 8-bit row-wise quantisation (Sec. 5.3 quantises all the weights; the scheme is a reading): one workgroup
+// per row r of W[R][C]: scale = max|row| / 127 (1 for an all-zero row), code = round-half-to-even(w / scale)
+// clipped to [-127, 127], all in fp32 with correctly rounded division; the compute copy Wc[r][ldc] receives
+// code * scale.  max is order-independent, so the result does not depend on the reduction tree.
+template <typename T>
+__global__ void __launch_bounds__(256) quantize_rows_kernel(const float *__restrict__ W, int C,
+                                                            int8_t *__restrict__ codes, float *__restrict__ scale,
+                                                            T *__restrict__ Wc, int ldc) {
+  __shared__ float red[256];
+  const int r = blockIdx.x;
+  const float *row = W + (long)r * C;
+  float amax = 0.0f;
+  for (int c = threadIdx.x; c < C; c += 256) amax = fmaxf(amax, fabsf(row[c]));
+  red[threadIdx.x] = amax;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + s]);
+    __syncthreads();
+  }
+  amax = red[0];
+  const float sc = amax > 0.0f ? amax / 127.0f : 1.0f;
+  if (threadIdx.x == 0) scale[r] = sc;
+  for (int c = threadIdx.x; c < C; c += 256) {
+    float q = rintf(row[c] / sc);
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    codes[(long)r * C + c] = (int8_t)q;
+    Wc[(long)r * ldc + c] = from_f32<T>(q * sc);
+  }
 }
 
 // ---- measured peaks of the box (reported next to the published ones) -----------------------------

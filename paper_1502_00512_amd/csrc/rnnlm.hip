@@ -33,6 +33,8 @@ struct WsLayout {
   size_t Wn_c, S32, dS_c, G32, noff, ndt, nct, gcol, ids, perm2, seg2;
   // rmsprop calls (present when cfg.rmsprop != 0): gradient buffers the redirected update epilogues fill
   size_t gWo, gU, gb, gN, gbN;
+  // compressed architecture (present when cfg.P > 0; then Wo_c holds the compute copy of the tied matrix E)
+  size_t A_c, C_c, Xp_c, P_c, dP32, dP_c, dX32;
   long partElems;
 };
 
@@ -45,6 +47,8 @@ struct rnnlm {
   rnnlm_config cfg;
   rnnlm_buffers buf;
   int Hp, Vp, Bp, MpMax;
+  int Pp;     // cfg.P rounded up to the tile size (0: plain architecture)
+  int D, Dp;  // width of the output layer's input: H / Hp, or P / Pp for the compressed architecture
   int KpMax;  // K_max rounded up to the tile size (0: no noise-contrastive workspace)
   int nPart;
   WsLayout L;
@@ -135,6 +139,7 @@ bool cfg_ok(const rnnlm_config *c) {
   if (c->K_max < 0 || c->K_max > 65536) return false;
   if (c->rmsprop != 0 && c->rmsprop != 1) return false;
   if ((long)c->B * c->T_max > (1L << 24)) return false;
+  if (c->P < 0 || (c->P > 0 && (c->K_max != 0 || c->rmsprop != 0))) return false;
   return true;
 }
 
@@ -149,21 +154,23 @@ int desired_splits(long Mp, long Hp, long kBlocks) {
 
 void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, int &nPart, int &KpMax, WsLayout &L) {
   const size_t es = (c.precision == RNNLM_FP32) ? 4 : 2;
+  const int Pp = (int)round_up(c.P, PAD_H);
   Hp = (int)round_up(c.H, PAD_H);
+  const int Dp = Pp > 0 ? Pp : Hp;
   Vp = (int)round_up(c.V, PAD_V);
   Bp = (int)round_up(c.B, PAD_B);
   MpMax = (int)round_up((long)c.T_max * Bp, PAD_M);
   nPart = Vp / BIG;  // one softmax-statistics partial per tile row block
   const int BK = (es == 4) ? 32 : 64;
-  const int S = desired_splits(MpMax, Hp, Vp / BK);
-  L.partElems = (long)S * MpMax * Hp;
+  const int S = desired_splits(MpMax, Dp, Vp / BK);
+  L.partElems = (long)S * MpMax * Dp;
   size_t o = 0;
   auto take = [&](size_t bytes) {
     size_t at = o;
     o = align256(o + bytes);
     return at;
   };
-  L.Wo_c = take((size_t)Vp * Hp * es);
+  L.Wo_c = take((size_t)Vp * Dp * es);
   L.U_c = take((size_t)Hp * Hp * es);
   L.UT_c = take((size_t)Hp * Hp * es);
   L.Hs_c = take((size_t)(MpMax + Bp) * Hp * es);
@@ -211,6 +218,16 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
     L.gN = take(nent * Hp * 4);
     L.gbN = take(nent * 4);
   }
+  L.A_c = L.C_c = L.Xp_c = L.P_c = L.dP32 = L.dP_c = L.dX32 = 0;
+  if (Pp > 0) {
+    L.A_c = take((size_t)Hp * Pp * es);
+    L.C_c = take((size_t)Pp * Hp * es);
+    L.Xp_c = take((size_t)MpMax * Pp * es);
+    L.P_c = take((size_t)MpMax * Pp * es);
+    L.dP32 = take((size_t)MpMax * Pp * 4);
+    L.dP_c = take((size_t)MpMax * Pp * es);
+    L.dX32 = take((size_t)MpMax * Pp * 4);
+  }
   L.scalars = take(256);  // [0]: int nseg, [4]: int nseg of the noise-contrastive update list, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64..131]: 17 barrier/ticket counters
   L.total = o;
 }
@@ -231,9 +248,17 @@ inline unsigned blocks_for(long n, int per) { return (unsigned)((n + per - 1) / 
 template <typename T>
 int sync_copies(rnnlm_t *h, hipStream_t st) {
   const rnnlm_config &c = h->cfg;
-  const long nWo = (long)h->Vp * h->Hp, nU = (long)h->Hp * h->Hp;
+  const long nWo = (long)h->Vp * h->Dp, nU = (long)h->Hp * h->Hp;
+  // the output layer's matrix: Wo, or the tied matrix E of the compressed architecture
   hipLaunchKernelGGL(to_compute_copy_kernel<T>, dim3(std::min<long>(blocks_for(nWo, 256), 65535)), dim3(256), 0, st,
-                     h->buf.Wo, c.V, c.H, h->Hp, nWo, at<T>(h, h->L.Wo_c));
+                     c.P > 0 ? h->buf.E : h->buf.Wo, c.V, h->D, h->Dp, nWo, at<T>(h, h->L.Wo_c));
+  if (c.P > 0) {
+    const long nA = (long)h->Hp * h->Pp;
+    hipLaunchKernelGGL(to_compute_copy_kernel<T>, dim3(std::min<long>(blocks_for(nA, 256), 65535)), dim3(256), 0, st,
+                       h->buf.A, c.H, c.P, h->Pp, nA, at<T>(h, h->L.A_c));
+    hipLaunchKernelGGL(to_compute_copy_kernel<T>, dim3(std::min<long>(blocks_for(nA, 256), 65535)), dim3(256), 0, st,
+                       h->buf.C, c.P, c.H, h->Hp, nA, at<T>(h, h->L.C_c));
+  }
   hipLaunchKernelGGL(to_compute_copy_kernel<T>, dim3(std::min<long>(blocks_for(nU, 256), 65535)), dim3(256), 0, st,
                      h->buf.U, c.H, c.H, h->Hp, nU, at<T>(h, h->L.U_c));
   hipLaunchKernelGGL(transpose_kernel<T>, dim3(h->Hp / 32, h->Hp / 32), dim3(256), 0, st, at<T>(h, h->L.U_c), h->Hp,
@@ -316,6 +341,8 @@ struct UpdateTargets {
   bool advance_state;
   int e_compact_ld = 0;  // > 0: the embedding rows go to a compact [runs][e_compact_ld] buffer (one row per run)
   int wo_compact_ld = 0; // > 0: likewise the touched rows of Wo and entries of b of the noise-contrastive calls
+  // compressed architecture: Wo is unused, E is the tied matrix (output-side update first, then the input rows)
+  float *A = nullptr, *C = nullptr;
 };
 
 // Forward half of a window: tokens -> padded ids, state -> slot 0, gather, T recurrent steps,
@@ -354,9 +381,16 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
   {
     StageTimer tm(h, RNNLM_STAGE_PREP, st);
     const int prep_blocks = (int)blocks_for(std::max<long>(Mp, (long)Bp * Hp), 256);
-    hipLaunchKernelGGL(prep_tokens_kernel<T>, dim3(prep_blocks + Mrows), dim3(256), 0, st, x, y, Tn, c.B, Bp, Mp, c.V,
-                       xp, yp, lse, p_flags(h), h->buf.h_state, c.H, Hp, Hs_c, p_counter(h), prep_blocks, h->buf.E,
-                       X32);
+    if (c.P > 0) {  // compressed architecture: the gathered rows are operands of the contraction below
+      hipLaunchKernelGGL(prep_tokens_kernel<T>, dim3(prep_blocks + Mrows), dim3(256), 0, st, x, y, Tn, c.B, Bp, Mp, c.V,
+                         xp, yp, lse, p_flags(h), h->buf.h_state, c.H, Hp, Hs_c, p_counter(h), prep_blocks,
+                         (const float *)nullptr, (float *)nullptr, (const T *)at<T>(h, h->L.Wo_c), h->Pp,
+                         at<T>(h, h->L.Xp_c));
+    } else {
+      hipLaunchKernelGGL(prep_tokens_kernel<T>, dim3(prep_blocks + Mrows), dim3(256), 0, st, x, y, Tn, c.B, Bp, Mp, c.V,
+                         xp, yp, lse, p_flags(h), h->buf.h_state, c.H, Hp, Hs_c, p_counter(h), prep_blocks, h->buf.E,
+                         X32, (const T *)nullptr, 0, (T *)nullptr);
+    }
     HIP_TRY(hipGetLastError());
     if (sort_inputs) {
       int rc = side_fork(h, 0, st);
@@ -364,6 +398,17 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
       rc = sort_segments<T>(h, Tn, at<int32_t>(h, h->L.perm), at<int32_t>(h, h->L.seg), p_nseg(h), h->side);
       if (rc) return rc;
     }
+  }
+
+  if (c.P > 0) {
+    // layer below the state: X[m][i] = sum_p x_m[p] A[i][p], the additive input of every recurrent step
+    StageTimer tm(h, RNNLM_STAGE_PROJ, st);
+    EpiPartial epi;
+    epi.part = X32;
+    epi.ld = Hp;
+    epi.split_stride = 0;
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, ROWK>(st, at<T>(h, h->L.Xp_c), h->Pp, at<T>(h, h->L.A_c), h->Pp, Mp,
+                                                        Hp, h->Pp, 1, epi)));
   }
 
   if (persistent_ok(h)) {
@@ -399,6 +444,17 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     }
   }
   if (!with_output) return RNNLM_OK;  // the noise-contrastive calls score the hidden states themselves
+  const T *feat = Hs_c + (long)Bp * Hp;  // what the output layer reads: the states, or the layer above them
+  if (c.P > 0) {
+    StageTimer tm(h, RNNLM_STAGE_PROJ, st);
+    EpiStore<T> epi;
+    epi.out32 = nullptr;
+    epi.outc = at<T>(h, h->L.P_c);
+    epi.ld = h->Pp;
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, ROWK>(st, Hs_c + (long)Bp * Hp, Hp, at<T>(h, h->L.C_c), Hp, Mp,
+                                                        h->Pp, Hp, 1, epi)));
+    feat = at<T>(h, h->L.P_c);
+  }
   {
     StageTimer tm(h, RNNLM_STAGE_OUT_FWD, st);
     EpiOutFwd<T> epi;
@@ -409,7 +465,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     epi.zy = zy;
     epi.V = c.V;
     epi.ldz = ldz;
-    HIP_TRY((big_gemm<T, 4, 2, ROWK, ROWK, false>(st, at<T>(h, h->L.Wo_c), Hp, Hs_c + (long)Bp * Hp, Hp, Vp, Mp, Hp, 1, epi)));
+    HIP_TRY((big_gemm<T, 4, 2, ROWK, ROWK, false>(st, at<T>(h, h->L.Wo_c), h->Dp, feat, h->Dp, Vp, Mp, h->Dp, 1, epi)));
   }
   StageTimer tm(h, RNNLM_STAGE_STATS, st);
   hipLaunchKernelGGL(merge_stats_kernel, dim3(blocks_for(Mrows, 64)), dim3(1024), 0, st, at<float2>(h, h->L.stat),
@@ -592,26 +648,42 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     HIP_TRY(hipGetLastError());
   }
 
-  // dHs[m][j] = sum_v dz[v][m] Wo[v][j]   (contraction over the vocabulary, split-K)
+  // dHs[m][j] = sum_v dz[v][m] Wo[v][j]   (contraction over the vocabulary, split-K); compressed
+  // architecture: the same contraction with the tied matrix gives the gradient of the layer above the state
   {
-    int S = desired_splits(Mp, Hp, Vp / BK);
-    const long per = (long)Mp * Hp;
+    const int Dp = h->Dp;
+    float *dF32 = c.P > 0 ? at<float>(h, h->L.dP32) : dHs32;
+    int S = desired_splits(Mp, Dp, Vp / BK);
+    const long per = (long)Mp * Dp;
     if ((long)S * per > h->L.partElems) S = (int)(h->L.partElems / per);
     if (S < 1) S = 1;
     EpiPartial epi;
-    epi.part = (S == 1) ? dHs32 : at<float>(h, h->L.part32);
-    epi.ld = Hp;
+    epi.part = (S == 1) ? dF32 : at<float>(h, h->L.part32);
+    epi.ld = Dp;
     epi.split_stride = per;
     {
       StageTimer tm(h, RNNLM_STAGE_OUT_BWD_H, st);
-      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW, true>(st, ZT, ldz, Wo_c, Hp, Mp, Hp, Vp, S, epi)));
+      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW, true>(st, ZT, ldz, Wo_c, Dp, Mp, Dp, Vp, S, epi)));
     }
     if (S > 1) {
       StageTimer tm(h, RNNLM_STAGE_REDUCE, st);
       hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks_for(per / 4, 256)), dim3(256), 0, st,
-                         at<float>(h, h->L.part32), per, per, S, dHs32);
+                         at<float>(h, h->L.part32), per, per, S, dF32);
       HIP_TRY(hipGetLastError());
     }
+  }
+  if (c.P > 0) {
+    // through the layer above the state: dHs[m][j] = sum_p dp[m][p] C[p][j]
+    StageTimer tm(h, RNNLM_STAGE_PROJ, st);
+    const long n = (long)Mp * h->Pp;
+    T *dP_c = at<T>(h, h->L.dP_c);
+    hipLaunchKernelGGL(to_compute_kernel<T>, dim3(blocks_for(n, 256)), dim3(256), 0, st, at<float>(h, h->L.dP32), n, dP_c);
+    HIP_TRY(hipGetLastError());
+    EpiPartial epi;
+    epi.part = dHs32;
+    epi.ld = Hp;
+    epi.split_stride = 0;
+    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, KROW>(st, dP_c, h->Pp, at<T>(h, h->L.C_c), Hp, Mp, Hp, h->Pp, 1, epi)));
   }
   }
 
@@ -661,19 +733,48 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     int rc = nce_update<T>(h, Tn, *nce, u, st);
     if (rc) return rc;
   } else {
-    // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j], contracted transposed (tile rows = j, tile columns = v)
+    if (c.P > 0) {
+      // C[p][j] -= lr * sum_m dp[m][p] h[m][j], contracted transposed (tile rows = j, tile columns = p)
+      StageTimer tm(h, RNNLM_STAGE_PROJ, st);
+      EpiSgdT<T> epi;
+      epi.W = h->buf.C;
+      epi.out = u.C;
+      epi.Wc = u.refresh_copies ? at<T>(h, h->L.C_c) : nullptr;
+      epi.ldw = c.H;
+      epi.ldc = Hp;
+      epi.R = c.P;
+      epi.C = c.H;
+      epi.alpha = u.alpha;
+      epi.lr = u.lr;
+      HIP_TRY((launch_gemm<T, 64, 64, 2, 2, KROW, KROW>(st, Hs_c + (long)Bp * Hp, Hp, at<T>(h, h->L.dP_c), h->Pp, Hp,
+                                                        h->Pp, Mp, 1, epi)));
+    }
+    {
+    // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j], contracted transposed (tile rows = j, tile columns = v);
+    // compressed architecture: the output-side update of the tied matrix, E[v][p] -= lr * sum_m dz[v][m] p[m][p]
     StageTimer tm(h, RNNLM_STAGE_OUT_BWD_W, st);
     EpiSgdT<T> epi;
-    epi.W = h->buf.Wo;
-    epi.out = u.Wo;
+    epi.W = c.P > 0 ? h->buf.E : h->buf.Wo;
+    epi.out = c.P > 0 ? u.E : u.Wo;
     epi.Wc = u.refresh_copies ? Wo_c : nullptr;
-    epi.ldw = c.H;
-    epi.ldc = Hp;
+    epi.ldw = h->D;
+    epi.ldc = h->Dp;
     epi.R = c.V;
-    epi.C = c.H;
+    epi.C = h->D;
     epi.alpha = u.alpha;
     epi.lr = u.lr;
-    HIP_TRY((big_gemm<T, 2, 4, KROW, ROWK, true>(st, Hs_c + (long)Bp * Hp, Hp, ZT, ldz, Hp, Vp, Mp, 1, epi, -2)));
+    const T *feat = c.P > 0 ? at<T>(h, h->L.P_c) : Hs_c + (long)Bp * Hp;
+    HIP_TRY((big_gemm<T, 2, 4, KROW, ROWK, true>(st, feat, h->Dp, ZT, ldz, h->Dp, Vp, Mp, 1, epi, -2)));
+    }
+    if (c.P > 0) {
+      // through the layer below the state: dx[m][p] = sum_i da[m][i] A[i][p] (before A is updated)
+      StageTimer tm(h, RNNLM_STAGE_PROJ, st);
+      EpiPartial epi;
+      epi.part = at<float>(h, h->L.dX32);
+      epi.ld = h->Pp;
+      epi.split_stride = 0;
+      HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, KROW>(st, dA_c, Hp, at<T>(h, h->L.A_c), h->Pp, Mp, h->Pp, Hp, 1, epi)));
+    }
   }
   // E[w] -= lr * sum_{m: x[m] = w} dA[m]: on the side stream, behind the sort helpers already queued there,
   // next to the recurrent weight-gradient contraction of the main stream (joined at the end of this function;
@@ -682,14 +783,37 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     int rc = side_fork(h, 0, st);  // the side stream waits for everything queued so far
     if (rc) return rc;
     StageTimer tm(h, RNNLM_STAGE_EMB, h->side);
-    if (c.H % 4 == 0) {
-      hipLaunchKernelGGL(scatter_update_kernel<4>, dim3(Tn * c.B, (c.H + 1023) / 1024), dim3(1024), 0, h->side, dA32,
-                         Hp, c.H, c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr, u.e_compact_ld);
+    // plain: rows of dA, width H.  Compressed: rows of dx, width P, added on top of the output-side update the
+    // same matrix has just received (training: in the master; gradient export: in the caller's buffer), and
+    // the compute copy of the tied matrix follows.
+    const float *rows = c.P > 0 ? at<float>(h, h->L.dX32) : dA32;
+    const float *src = (c.P > 0 && !u.refresh_copies) ? u.E : h->buf.E;
+    const float e_alpha = (c.P > 0 && !u.refresh_copies) ? 1.0f : u.alpha;
+    T *Ec = (c.P > 0 && u.refresh_copies) ? Wo_c : nullptr;
+    const int W = h->D, Wp = h->Dp;
+    if (W % 4 == 0) {
+      hipLaunchKernelGGL((scatter_update_kernel<4, T>), dim3(Tn * c.B, (W + 1023) / 1024), dim3(1024), 0, h->side, rows,
+                         Wp, W, c.B, Bp, xp, perm, seg, p_nseg(h), src, u.E, e_alpha, u.lr, u.e_compact_ld, Ec, Wp);
     } else {
-      hipLaunchKernelGGL(scatter_update_kernel<1>, dim3(Tn * c.B, (c.H + 255) / 256), dim3(1024), 0, h->side, dA32,
-                         Hp, c.H, c.B, Bp, xp, perm, seg, p_nseg(h), h->buf.E, u.E, u.alpha, u.lr, u.e_compact_ld);
+      hipLaunchKernelGGL((scatter_update_kernel<1, T>), dim3(Tn * c.B, (W + 255) / 256), dim3(1024), 0, h->side, rows,
+                         Wp, W, c.B, Bp, xp, perm, seg, p_nseg(h), src, u.E, e_alpha, u.lr, u.e_compact_ld, Ec, Wp);
     }
     HIP_TRY(hipGetLastError());
+  }
+  if (c.P > 0) {
+    // A[i][p] -= lr * sum_m da[m][i] x[m][p], contracted transposed (tile rows = p, tile columns = i)
+    StageTimer tm(h, RNNLM_STAGE_PROJ, st);
+    EpiSgdT<T> epi;
+    epi.W = h->buf.A;
+    epi.out = u.A;
+    epi.Wc = u.refresh_copies ? at<T>(h, h->L.A_c) : nullptr;
+    epi.ldw = c.P;
+    epi.ldc = h->Pp;
+    epi.R = c.H;
+    epi.C = c.P;
+    epi.alpha = u.alpha;
+    epi.lr = u.lr;
+    HIP_TRY((launch_gemm<T, 64, 64, 2, 2, KROW, KROW>(st, at<T>(h, h->L.Xp_c), h->Pp, dA_c, Hp, h->Pp, Hp, Mp, 1, epi)));
   }
 
   // U[i][j] -= lr * sum_m dA[m][i] Hprev[m][j], contracted transposed (tile rows = j, tile columns = i)
@@ -750,6 +874,23 @@ int score_call(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float lnZ
   return RNNLM_OK;
 }
 
+template <typename T>
+int quantize_call(rnnlm_t *h, const rnnlm_quantized &q, hipStream_t st) {
+  const rnnlm_config &c = h->cfg;
+  hipLaunchKernelGGL(quantize_rows_kernel<T>, dim3(c.V), dim3(256), 0, st, h->buf.E, c.P, q.qE, q.sE,
+                     reinterpret_cast<T *>(h->ws + h->L.Wo_c), h->Pp);
+  hipLaunchKernelGGL(quantize_rows_kernel<T>, dim3(c.H), dim3(256), 0, st, h->buf.A, c.P, q.qA, q.sA,
+                     reinterpret_cast<T *>(h->ws + h->L.A_c), h->Pp);
+  hipLaunchKernelGGL(quantize_rows_kernel<T>, dim3(c.H), dim3(256), 0, st, h->buf.U, c.H, q.qU, q.sU,
+                     reinterpret_cast<T *>(h->ws + h->L.U_c), h->Hp);
+  hipLaunchKernelGGL(quantize_rows_kernel<T>, dim3(c.P), dim3(256), 0, st, h->buf.C, c.H, q.qC, q.sC,
+                     reinterpret_cast<T *>(h->ws + h->L.C_c), h->Hp);
+  hipLaunchKernelGGL(transpose_kernel<T>, dim3(h->Hp / 32, h->Hp / 32), dim3(256), 0, st,
+                     reinterpret_cast<T *>(h->ws + h->L.U_c), h->Hp, reinterpret_cast<T *>(h->ws + h->L.UT_c));
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
 bool window_args_ok(rnnlm_t *h, const int32_t *x, const int32_t *y, int T) {
   return h && x && y && T >= 1 && T <= h->cfg.T_max;
 }
@@ -770,17 +911,22 @@ int rnnlm_init(const rnnlm_config *cfg, const rnnlm_buffers *buf, rnnlm_t **out)
   if (!out) return RNNLM_ERR_ARG;
   *out = nullptr;
   if (!cfg_ok(cfg) || !buf) return RNNLM_ERR_ARG;
-  if (!buf->E || !buf->U || !buf->Wo || !buf->b || !buf->h_state || !buf->workspace) return RNNLM_ERR_ARG;
+  if (!buf->E || !buf->U || !buf->b || !buf->h_state || !buf->workspace) return RNNLM_ERR_ARG;
+  if (cfg->P > 0 ? (buf->Wo || !buf->A || !buf->C) : (!buf->Wo || buf->A || buf->C)) return RNNLM_ERR_ARG;
   if (reinterpret_cast<uintptr_t>(buf->workspace) & 255) return RNNLM_ERR_ARG;
   if ((reinterpret_cast<uintptr_t>(buf->E) | reinterpret_cast<uintptr_t>(buf->U) |
        reinterpret_cast<uintptr_t>(buf->Wo) | reinterpret_cast<uintptr_t>(buf->b) |
-       reinterpret_cast<uintptr_t>(buf->h_state)) & 15)
+       reinterpret_cast<uintptr_t>(buf->h_state) | reinterpret_cast<uintptr_t>(buf->A) |
+       reinterpret_cast<uintptr_t>(buf->C)) & 15)
     return RNNLM_ERR_ARG;
   rnnlm_t *h = new (std::nothrow) rnnlm_t;
   if (!h) return RNNLM_ERR_NOMEM;
   h->cfg = *cfg;
   h->buf = *buf;
   make_layout(*cfg, h->Hp, h->Vp, h->Bp, h->MpMax, h->nPart, h->KpMax, h->L);
+  h->Pp = (int)round_up(cfg->P, PAD_H);
+  h->D = cfg->P > 0 ? cfg->P : cfg->H;
+  h->Dp = cfg->P > 0 ? h->Pp : h->Hp;
   if (buf->workspace_bytes < h->L.total) {
     delete h;
     return RNNLM_ERR_ARG;
@@ -868,13 +1014,15 @@ int rnnlm_train_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T,
   if (!window_args_ok(h, x, y, T) || !(lr == lr)) return RNNLM_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   UpdateTargets u{h->buf.E, h->buf.U, h->buf.Wo, h->buf.b, 1.0f, lr, true, true};
+  u.A = h->buf.A;
+  u.C = h->buf.C;
   return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, logp, sum_logp, &u, true, st)
                                           : window_call<bf16_t>(h, x, y, T, logp, sum_logp, &u, true, st);
 }
 
 int rnnlm_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *dE, float *dU, float *dWo,
                      float *db, float *logp, void *stream) {
-  if (!window_args_ok(h, x, y, T) || !dE || !dU || !dWo || !db) return RNNLM_ERR_ARG;
+  if (!window_args_ok(h, x, y, T) || !dE || !dU || !dWo || !db || h->cfg.P > 0) return RNNLM_ERR_ARG;
   if ((reinterpret_cast<uintptr_t>(dE) | reinterpret_cast<uintptr_t>(dU) | reinterpret_cast<uintptr_t>(dWo) |
        reinterpret_cast<uintptr_t>(db)) & 15)
     return RNNLM_ERR_ARG;  // the update epilogues use 16-byte accesses
@@ -886,6 +1034,28 @@ int rnnlm_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, 
   UpdateTargets u{dE, dU, dWo, db, 0.0f, -1.0f, false, false};
   return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, logp, nullptr, &u, false, st)
                                           : window_call<bf16_t>(h, x, y, T, logp, nullptr, &u, false, st);
+}
+
+int rnnlm_grad_chunk_compressed(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *dE, float *dA,
+                                float *dU, float *dC, float *db, float *logp, void *stream) {
+  if (!window_args_ok(h, x, y, T) || !dE || !dA || !dU || !dC || !db || h->cfg.P <= 0) return RNNLM_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(dE) | reinterpret_cast<uintptr_t>(dA) | reinterpret_cast<uintptr_t>(dU) |
+       reinterpret_cast<uintptr_t>(dC) | reinterpret_cast<uintptr_t>(db)) & 15)
+    return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  // every entry of dE is written by the output-side contraction; the input rows are then added on top
+  UpdateTargets u{dE, dU, nullptr, db, 0.0f, -1.0f, false, false};
+  u.A = dA;
+  u.C = dC;
+  return (h->cfg.precision == RNNLM_FP32) ? window_call<float>(h, x, y, T, logp, nullptr, &u, false, st)
+                                          : window_call<bf16_t>(h, x, y, T, logp, nullptr, &u, false, st);
+}
+
+int rnnlm_quantize_weights(rnnlm_t *h, const rnnlm_quantized *q, void *stream) {
+  if (!h || !q || h->cfg.P <= 0) return RNNLM_ERR_ARG;
+  if (!q->qE || !q->sE || !q->qA || !q->sA || !q->qU || !q->sU || !q->qC || !q->sC) return RNNLM_ERR_ARG;
+  return (h->cfg.precision == RNNLM_FP32) ? quantize_call<float>(h, *q, (hipStream_t)stream)
+                                          : quantize_call<bf16_t>(h, *q, (hipStream_t)stream);
 }
 
 namespace {
@@ -927,7 +1097,7 @@ int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t
 
 int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lnZ, float *score,
                         void *stream) {
-  if (!window_args_ok(h, x, y, T) || !score || !(lnZ == lnZ)) return RNNLM_ERR_ARG;
+  if (!window_args_ok(h, x, y, T) || !score || !(lnZ == lnZ) || h->cfg.P > 0) return RNNLM_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   return (h->cfg.precision == RNNLM_FP32) ? score_call<float>(h, x, y, T, lnZ, score, st)
                                           : score_call<bf16_t>(h, x, y, T, lnZ, score, st);
@@ -1115,7 +1285,8 @@ int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, 
   hipLaunchKernelGGL(prep_tokens_kernel<float>, dim3(prep_blocks), dim3(256), 0, st, x, (const int32_t *)nullptr, T,
                      h->cfg.B, h->Bp, Mp, h->cfg.V, at<int32_t>(h, h->L.xp), (int32_t *)nullptr,
                      at<float>(h, h->L.lse), p_flags(h), (const float *)nullptr, 0, 0, (float *)nullptr,
-                     (unsigned *)nullptr, prep_blocks, (const float *)nullptr, (float *)nullptr);
+                     (unsigned *)nullptr, prep_blocks, (const float *)nullptr, (float *)nullptr,
+                     (const float *)nullptr, 0, (float *)nullptr);
   HIP_TRY(hipGetLastError());
   return sort_segments<float>(h, T, perm, seg_start, nseg, st);
 }

@@ -186,6 +186,14 @@ def make_weights(V: int, H: int, init: str, scale: float, seed: int):
     return E, U, Wo, b
 
 
+def make_compressed_weights(V: int, H: int, P: int, init: str, scale: float, seed: int):
+    """Returns fp32 (E[V][P], A[H][P], U[H][H], C[P][H], b[V]) of the compressed architecture; b is zero."""
+    f = (lambda shp, sd: uniform_weights(shp, -scale, scale, sd)) if init == "uniform" \
+        else (lambda shp, sd: normal_weights(shp, scale, sd))
+    return f((V, P), seed + 11), f((H, P), seed + 44), f((H, H), seed + 22), f((P, H), seed + 55), \
+        np.zeros(V, dtype=np.float32)
+
+
 def unigram_noise(tok: np.ndarray, V: int):
     """Noise distribution for a contrastive criterion: the add-one-smoothed unigram of a token array.
 
