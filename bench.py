@@ -11,7 +11,7 @@ streams that are already resident in HBM.  Prints ONE JSON line:
   cpu_baseline     the fp64 oracle timed on a bounded sample of the same workload on the host cores
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3] [--stages]
-                       [--criterion softmax|nce] [--noise K]
+                       [--criterion softmax|nce|score] [--noise K] [--optimizer sgd|rmsprop] [--arch plain|compressed]
 
 --criterion nce times the same window with the noise-contrastive output layer (the "next" row after the
 headline path): K shared noise words per window drawn from the smoothed unigram of the token array.
@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--optimizer", choices=["sgd", "rmsprop"], default="sgd",
                     help="sgd: the fused plain SGD step (headline metric); rmsprop: the rmsprop-scaled step "
                          "(smoothing 0.9995, one statistic per word for E and Wo), full softmax only")
+    ap.add_argument("--arch", choices=["plain", "compressed"], default="plain",
+                    help="compressed: the architecture of Sec. 5.3 (512-unit layers below and above the state, tied "
+                         "word matrix) on its word-prediction shape (config wp10k), full softmax + SGD")
     ap.add_argument("--streams", type=int, default=0, help="override the number of parallel streams B (scoring)")
     ap.add_argument("--noise", type=int, default=1024, help="noise words per window for --criterion nce")
     ap.add_argument("--calib-copy", action="store_true",
@@ -65,8 +68,15 @@ def main() -> int:
     import torch
     from paper_1502_00512_amd import binding, synth
 
+    comp = args.arch == "compressed"
+    if comp and (args.criterion != "softmax" or args.optimizer != "sgd"):
+        print("bench.py: --arch compressed runs with the full softmax and plain SGD only", file=sys.stderr)
+        return 2
+    if comp and args.config == "cfg3":
+        args.config = "wp10k"
     cfg = synth.CONFIGS[args.config]
     V, H, B, T = cfg.V, cfg.H, (args.streams or cfg.B), cfg.T
+    P = synth.COMPRESSED_P if comp else 0
     M = B * T
     precision = binding.RNNLM_BF16_FP32MASTER if cfg.precision == "bf16" else binding.RNNLM_FP32
     total_steps = args.steps + args.warmup
@@ -76,7 +86,11 @@ def main() -> int:
     N = cfg.N if need <= L_full else need * B + 1
     t0 = time.time()
     tok = synth.make_tokens(cfg, N)
-    E, U, Wo, b = synth.make_weights(V, H, cfg.init, cfg.init_scale, cfg.weight_seed)
+    if comp:
+        E, A_, U, C_, b = synth.make_compressed_weights(V, H, P, cfg.init, cfg.init_scale, cfg.weight_seed)
+        Wo = None
+    else:
+        E, U, Wo, b = synth.make_weights(V, H, cfg.init, cfg.init_scale, cfg.weight_seed)
     log(f"[bench] {cfg.name}: V={V} H={H} B={B} T={T} N={N} inputs generated in {time.time() - t0:.1f}s "
         f"tokens sha256 {synth.sha256_of(tok)[:16]}")
 
@@ -86,7 +100,10 @@ def main() -> int:
     if rms and score:
         print("bench.py: --criterion score has no optimiser", file=sys.stderr)
         return 2
-    g = binding.Rnnlm(E, U, Wo, b, B, T, precision, K_max=args.noise if nce else 0, rmsprop=rms, r_init=1e-4)
+    if comp:
+        g = binding.Rnnlm(E, U, None, b, B, T, precision, A=A_, C_=C_)
+    else:
+        g = binding.Rnnlm(E, U, Wo, b, B, T, precision, K_max=args.noise if nce else 0, rmsprop=rms, r_init=1e-4)
     rms_lr, rms_rho, rms_eps = cfg.lr * 1e-2, 0.9995, 1e-4
     dtok = torch.as_tensor(tok).cuda()
     if nce:
@@ -122,6 +139,8 @@ def main() -> int:
         gemm_stages = ["prep", "rnn_fwd", "nce_score"]
     if rms and not nce:
         gemm_stages = ["out_fwd", "out_bwd_h", "out_bwd_w", "rmsprop"]
+    if comp:
+        gemm_stages = ["rnn_fwd", "rnn_bwd", "out_fwd", "out_bwd_h", "out_bwd_w", "proj"]
 
     for k in range(args.warmup):
         step(k)
@@ -143,7 +162,7 @@ def main() -> int:
     gemm_ms = {}
     for n in gemm_stages:
         ms, cnt = g.rnnlm_profile_read(stage_ids[n])
-        gemm_ms[n] = ms / max(cnt, 1)
+        gemm_ms[n] = ms / max(cnt, 1) if n != "proj" else ms / args.steps   # proj: six launches per step, summed
     g.rnnlm_profile_enable(0)
 
     stage_ms = None
@@ -183,6 +202,21 @@ def main() -> int:
         extra["stage_ms_timed"] = {k: round(v, 4) for k, v in gemm_ms.items()}
         criterion = "forward-only unnormalised scoring of the given next words"
         metric = "scored words/sec (forward only, unnormalised output) at 1 MI355X"
+    elif comp:
+        flops_word = 6.0 * (V * P + 2.0 * P * H + H * H)
+        # algorithmic flops per launch: recurrent kernels 2 H^2 per position, output contractions 2 V P per position
+        work = {"rnn_fwd": 2.0 * H * H * M, "rnn_bwd": 2.0 * H * H * (M - B), "out_fwd": 2.0 * V * P * M,
+                "out_bwd_h": 2.0 * V * P * M, "out_bwd_w": 2.0 * V * P * M}
+        proj_ms = gemm_ms.pop("proj")
+        dominant = max(gemm_ms, key=gemm_ms.get)
+        achieved = work[dominant] / (gemm_ms[dominant] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": peak,
+                    "unit": "TFLOP/s", "frac": round(achieved / peak, 4), "traffic": None}
+        extra["stage_ms_timed"] = {k: round(v, 4) for k, v in gemm_ms.items()}
+        extra["stage_ms_timed"]["proj (six contractions through the inserted layers)"] = round(proj_ms, 4)
+        extra["P"] = P
+        criterion = f"compressed architecture (layers of {P} units below and above the state, tied word matrix), full softmax"
+        metric = "training words/sec (fwd+BPTT+SGD, compressed architecture) at 1 MI355X"
     elif nce:
         Kn = args.noise
         flops_word = 6.0 * H * (Kn + 1 + H)  # K+1 scored words per position instead of V
@@ -231,7 +265,9 @@ def main() -> int:
             metric = "training words/sec (fwd+BPTT+rmsprop-scaled SGD) at 1 MI355X"
 
     cpu = None
-    if not args.no_cpu_baseline and not score and not rms:
+    if comp and not args.no_cpu_baseline:
+        cpu = cpu_baseline_compressed(cfg, E, A_, U, C_, b, tok)
+    elif not args.no_cpu_baseline and not score and not rms:
         cpu = cpu_baseline(cfg, E, U, Wo, b, tok,
                            (synth.noise_words(thr, args.noise, cfg.data_seed + 7, 0), lnq, lnZ) if nce else None)
 
@@ -271,6 +307,25 @@ def measured_traffic(workload, kernel):
             return json.load(f)[workload][kernel]["bytes_per_launch"]
     except (OSError, KeyError, ValueError):
         return None
+
+
+def cpu_baseline_compressed(cfg, E, A, U, C, b, tok):
+    """The numpy fp64 oracle of the compressed architecture on whole training windows (about 10 s)."""
+    import numpy as np
+    from oracle import compressed as Cq
+    from oracle import oracle as O
+    B, T = cfg.B, cfg.T
+    x, y = O.stream_chunk(tok, B, T, 0)
+    m = Cq.CompressedModel(*(np.asarray(a, np.float64).copy() for a in (E, A, U, C, b)), np.zeros((B, cfg.H)))
+    total, reps = 0.0, 0
+    while total < 10.0 and reps < 8:
+        t0 = time.perf_counter()
+        Cq.train_chunk(m, x.astype(np.int64), y.astype(np.int64), cfg.lr)
+        total += time.perf_counter() - t0
+        reps += 1
+    return {"value": round(reps * B * T / total, 2), "unit": "words/s", "cores": os.cpu_count(), "kind": "oracle",
+            "sample": f"{reps} x one training window of {B} streams x {T} timesteps ({reps * B * T} words, {total:.1f} s; "
+                      "numpy fp64, its library's threads)"}
 
 
 def cpu_baseline(cfg, E, U, Wo, b, tok, nce=None):

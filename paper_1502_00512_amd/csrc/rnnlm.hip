@@ -764,7 +764,15 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     epi.alpha = u.alpha;
     epi.lr = u.lr;
     const T *feat = c.P > 0 ? at<T>(h, h->L.P_c) : Hs_c + (long)Bp * Hp;
-    HIP_TRY((big_gemm<T, 2, 4, KROW, ROWK, true>(st, feat, h->Dp, ZT, ldz, h->Dp, Vp, Mp, 1, epi, -2)));
+    if ((long)(h->Dp / BIG) * (Vp / BIG) < 128) {  // a narrow layer above the state: smaller tiles fill the chip
+      if constexpr (sizeof(T) == 2) {
+        HIP_TRY((launch_gemm_dma4<128, BIG, 2, 4, KROW, ROWK>(st, feat, h->Dp, ZT, ldz, h->Dp, Vp, Mp, 1, epi, -4)));
+      } else {
+        HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, ROWK>(st, feat, h->Dp, ZT, ldz, h->Dp, Vp, Mp, 1, epi, -2)));
+      }
+    } else {
+      HIP_TRY((big_gemm<T, 2, 4, KROW, ROWK, true>(st, feat, h->Dp, ZT, ldz, h->Dp, Vp, Mp, 1, epi, -2)));
+    }
     }
     if (c.P > 0) {
       // through the layer below the state: dx[m][p] = sum_i da[m][i] A[i][p] (before A is updated)

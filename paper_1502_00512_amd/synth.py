@@ -167,7 +167,10 @@ CONFIGS = {
     "cfg3": Config("cfg3", 64_000, 1024, 128, 20, 20_000_000, 1.05, 25.0, 0, "normal", 0.02, 0.05, "bf16", 0x5EED0003, 0x5EED1003),
     "cfg4": Config("cfg4", 100_000, 2048, 128, 20, 50_000_000, 1.0, None, 4096, "normal", 0.02, 0.02, "bf16", 0x5EED0004, 0x5EED1004),
     "cfg5": Config("cfg5", 100_000, 4096, 256, 32, 100_000_000, 1.0, 25.0, 0, "normal", 0.01, 0.01, "bf16", 0x5EED0005, 0x5EED1005),
+    # the word-prediction model of Sec. 5.3 (vocabulary 10K, nstate 1024; the 512-unit layers are COMPRESSED_P)
+    "wp10k": Config("wp10k", 10_000, 1024, 128, 20, 5_000_000, 1.05, 25.0, 0, "normal", 0.02, 0.05, "bf16", 0x5EED0006, 0x5EED1006),
 }
+COMPRESSED_P = 512
 
 
 def make_tokens(cfg: Config, N: int | None = None) -> np.ndarray:

@@ -205,3 +205,41 @@ def test_argument_checks():
         plain.rnnlm_quantize_weights() if False else binding._ok(
             plain.lib.rnnlm_quantize_weights(plain.handle, None, None), "rnnlm_quantize_weights")
     assert binding.rnnlm_workspace_bytes(300, 32, 2, 4, FP32, K_max=8, P=16) == 0   # not combined with NCE
+
+
+@pytest.mark.parametrize("precision", [FP32, BF16])
+def test_full_size_word_prediction_shape(precision):
+    """The shape Sec. 5.3 names (vocabulary 10K, nstate 1024, 512-unit layers), in the launch configuration
+    bench.py --arch compressed times (128 streams x 20): every output of one window against the oracle."""
+    cfg = synth.CONFIGS["wp10k"]
+    V, H, P, B, T = cfg.V, cfg.H, synth.COMPRESSED_P, cfg.B, cfg.T
+    E, A, U, C, b = synth.make_compressed_weights(V, H, P, cfg.init, cfg.init_scale, cfg.weight_seed)
+    g = binding.Rnnlm(E, U, None, b, B, T, precision, A=A, C_=C)
+    o = Cq.CompressedModel(*(np.asarray(a, np.float64).copy() for a in (E, A, U, C, b)), np.zeros((B, H)))
+    tok = synth.make_tokens(cfg, 200_000)
+    L = (tok.size - 1) // B
+    idx = np.arange(B)[None, :] * L + np.arange(T)[:, None]
+    x, y = tok[idx].astype(np.int32), tok[idx + 1].astype(np.int32)
+    ref = Cq.grad_chunk(o, x, y)
+    got = g.rnnlm_grad_chunk_compressed(dev(x), dev(y))
+    g.rnnlm_check()
+    if precision == FP32:
+        check_logp(got["logp"], ref["logp"])
+    else:
+        lp = got["logp"].cpu().numpy().astype(np.float64)
+        assert abs(lp.mean() - ref["logp"].mean()) <= 1e-2 * abs(ref["logp"].mean())
+        assert np.abs(lp - ref["logp"]).max() <= 2e-2 * np.abs(ref["logp"]).max()
+    for n in ("gE", "gA", "gU", "gC", "gb"):
+        check_grad(n, got[n], ref[n], rel=1e-3 if precision == FP32 else 3e-2)
+    # one training step: parameters follow the oracle's (a step is lr * gradient, so the gradient tolerance applies
+    # to the change), untouched... every row of the tied matrix is touched through its output role
+    lr = cfg.lr
+    before = {n: getattr(g, n).clone() for n in ("E", "A", "U", "C", "b")}
+    g.rnnlm_train_chunk(dev(x), dev(y), lr)
+    g.rnnlm_check()
+    tol = 1e-3 if precision == FP32 else 3e-2
+    for n in ("E", "A", "U", "C", "b"):
+        step = (getattr(g, n) - before[n]).cpu().numpy().astype(np.float64)
+        want = -lr * ref["g" + n]
+        assert np.abs(step - want).max() <= tol * np.abs(want).max() + 1e-7, n
+    assert np.abs(g.h_state.cpu().numpy() - ref["h_out"]).max() <= (1e-5 if precision == FP32 else 2e-2)
