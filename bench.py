@@ -318,7 +318,7 @@ def cpu_baseline_compressed(cfg, E, A, U, C, b, tok):
     x, y = O.stream_chunk(tok, B, T, 0)
     m = Cq.CompressedModel(*(np.asarray(a, np.float64).copy() for a in (E, A, U, C, b)), np.zeros((B, cfg.H)))
     total, reps = 0.0, 0
-    while total < 10.0 and reps < 8:
+    while total < 10.0 and reps < 64:
         t0 = time.perf_counter()
         Cq.train_chunk(m, x.astype(np.int64), y.astype(np.int64), cfg.lr)
         total += time.perf_counter() - t0
