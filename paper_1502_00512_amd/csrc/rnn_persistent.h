@@ -13,6 +13,7 @@
 #pragma once
 #include "common.h"
 #include "gemm.h"
+#include "gemm_dma.h"
 
 namespace rnnlm_dev {
 
@@ -178,14 +179,28 @@ __device__ inline f32x4_t load4<bf16_t>(const bf16_t *p) {
   return v;
 }
 
+// STAGED (bf16, XCD-local mode, KS a multiple of 4): the previous step's state reaches the MFMA operand
+// registers through LDS instead of straight from the L2.  Loaded straight into fragments, every lane asks for
+// 16 bytes of a different row, and the vector L1 handles such a wave instruction as 64 separate line
+// look-ups: at 16 instructions per wave and step that address path, not the L2 or the barrier, set the step
+// time (counters: the texture addresser busy 58 % of the kernel, 47 M tag look-ups for 0.6 GB).  Staged, each
+// wave copies its own [32 streams][64 k] blocks with direct global->LDS loads whose 64 lanes cover one
+// contiguous kilobyte of LDS and eight full 128-byte lines of memory (8 look-ups instead of 64), then reads
+// the fragments from LDS.  The block layout and its XOR swizzle are those of the 64-deep K-contiguous tile of
+// the contraction kernels (physical 16-byte chunk = logical ^ ((row >> 1) & 7)).  A wave reads only what it
+// copied itself, so the copy is ordered by that wave's own s_waitcnt; the buffer is reused every step.
+//
 // KS = 16-wide contraction steps per wave = Hp / (16 NWAVE).  BACKWARD = false: h_t = sigmoid(X_t + h_{t-1} U^T)
 // for t = 0..T-1.  BACKWARD = true: dA_t = (dHs_t + dA_{t+1} U) * h_t * (1 - h_t) for t = T-1..0.
 // XCD = true: XCD-local mode (see above); false: the grid spans the chip and uses agent-scope accesses.
-template <typename T, int KS, int NWAVE, bool BACKWARD, bool XCD>
+template <typename T, int KS, int NWAVE, bool BACKWARD, bool XCD, bool STAGED = false>
 __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPersistArgs a) {
+  static_assert(!STAGED || (XCD && sizeof(T) == 2 && KS % 4 == 0), "staged state loads: bf16, XCD-local, whole blocks");
+  constexpr int NBLK = KS / 4;  // [32][64] blocks of this wave's share of the state (STAGED)
   __shared__ __attribute__((aligned(16))) float red[NWAVE][16][64];
+  __shared__ __attribute__((aligned(1024))) char stage[STAGED ? NWAVE * NBLK * 4096 : 16];
   __shared__ int s_ticket;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nsb = a.Bp / 32;
   int sb, ub;
   unsigned nwg;
@@ -219,6 +234,27 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) w[kk] = load_frag_global<T, false>(Wp + kk * 16);
   }
+#if defined(__HIP_DEVICE_COMPILE__)
+  // STAGED: buffer resource over the whole state (gradient) buffer and this lane's offsets inside a block
+  typedef int i32x4_t __attribute__((ext_vector_type(4)));
+  i32x4_t rsrc = {0, 0, 0, 0};
+  int goff[4] = {0, 0, 0, 0};
+  int frag_off[4] = {0, 0, 0, 0};
+  if constexpr (STAGED) {
+    const unsigned long long base = reinterpret_cast<unsigned long long>(BACKWARD ? a.dAc : a.Hs);
+    rsrc[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)base);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((base >> 32) & 0xffffu));
+    rsrc[2] = __builtin_amdgcn_readfirstlane((int)((long)(a.T + 1) * slot * 2));
+    rsrc[3] = 0x00020000;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = i * 8 + (lane >> 3), pch = lane & 7;  // LDS chunk (r, pch) of the block <- memory chunk pch ^ swz(r)
+      goff[i] = (int)(((long)(sb * 32 + r) * Hp + kq) * 2 + ((pch ^ rowk_swz(r)) << 4));
+    }
+#pragma unroll
+    for (int st = 0; st < 4; ++st) frag_off[st] = lr * 128 + (((2 * st + (lane >> 5)) ^ rowk_swz(lr)) << 4);
+  }
+#endif
   // epilogue ownership (first 256 threads): thread -> accumulator element r = tid/16 of lanes
   // 4*(tid%16) .. +3, i.e. one stream and 4 consecutive hidden units
   const bool epi_thread = tid < 256;
@@ -247,8 +283,30 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
       const T *src = BACKWARD ? dAc + (long)(t + 1) * slot : Hs + (long)t * slot;
       const T *Ap = src + (long)(sb * 32 + lr) * Hp + kq + lk;
       typename FragT<T>::type f[KS];
+#if defined(__HIP_DEVICE_COMPILE__)
+      if constexpr (STAGED) {
+        char *sw = stage + wave * (NBLK * 4096);
+        const int soff = (int)((long)(BACKWARD ? t + 1 : t) * slot * 2);
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const unsigned lds_addr = (unsigned)(unsigned long long)(lds_void_ptr)(sw + b * 4096 + i * 1024);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :
+                         : "s"(lds_addr), "v"(goff[i]), "s"(rsrc), "s"(soff + b * 128)
+                         : "memory", "m0");
+          }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies have landed in LDS
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+          f[kk] = *reinterpret_cast<const bf16x8_t *>(sw + (kk >> 2) * 4096 + frag_off[kk & 3]);
+      } else
+#endif
+      {
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) f[kk] = load_frag_global<T, !XCD>(Ap + kk * 16);
+      }
 #pragma unroll
       for (int kk = 0; kk < KS; kk += 2) {
         mma16(acc, f[kk], w[kk]);

@@ -311,10 +311,16 @@ int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st
   // XCD-local mode: one group of Hp/32 workgroups per block of 32 streams, group x on XCD x
   const bool xcd = h->xcd_local && h->Bp / 32 <= NUM_XCD;
   const dim3 grid(xcd ? (unsigned)(NUM_XCD * (h->Hp / 32)) : (unsigned)((h->Bp / 32) * (h->Hp / 32)));
+  // bf16, XCD-local, 4 waves, whole [32][64] blocks per wave: the state goes through LDS (coalesced loads)
 #define RNNLM_LAUNCH_PERSIST(KS, NW)                                                                        \
   do {                                                                                                      \
-    if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true>), grid, dim3(64 * NW), 0, st, a); \
-    else hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, false>), grid, dim3(64 * NW), 0, st, a);    \
+    if constexpr (sizeof(T) == 2 && NW == 4 && KS % 4 == 0) {                                               \
+      if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true, true>), grid, dim3(64 * NW), 0, st, a); \
+      else hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, false>), grid, dim3(64 * NW), 0, st, a);  \
+    } else {                                                                                                \
+      if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true>), grid, dim3(64 * NW), 0, st, a); \
+      else hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, false>), grid, dim3(64 * NW), 0, st, a);    \
+    }                                                                                                       \
   } while (0)
   switch (h->Hp / 256) {
     case 1: RNNLM_LAUNCH_PERSIST(4, 4); break;
