@@ -189,18 +189,32 @@ __device__ inline f32x4_t load4<bf16_t>(const bf16_t *p) {
 // the fragments from LDS.  The block layout and its XOR swizzle are those of the 64-deep K-contiguous tile of
 // the contraction kernels (physical 16-byte chunk = logical ^ ((row >> 1) & 7)).  A wave reads only what it
 // copied itself, so the copy is ordered by that wave's own s_waitcnt; the buffer is reused every step.
+// STAGED = 1: all of a wave's blocks are resident at once (4 waves, 16 KB each).  STAGED = 2 (8 waves, two
+// workgroups per compute unit, so 64 KB each): a wave owns two 4 KB buffers and streams its blocks through
+// them (block b+2 is requested as soon as the fragments of block b are in registers), and the partial-sum
+// exchange buffer of the step's end lives in the same memory: a wave writes its partial tile over its own
+// first buffer, whose fragments it has consumed, and the next step's copies start only after the step
+// barrier, which every wave reaches after its reads of the exchange buffer.
 //
 // KS = 16-wide contraction steps per wave = Hp / (16 NWAVE).  BACKWARD = false: h_t = sigmoid(X_t + h_{t-1} U^T)
 // for t = 0..T-1.  BACKWARD = true: dA_t = (dHs_t + dA_{t+1} U) * h_t * (1 - h_t) for t = T-1..0.
 // XCD = true: XCD-local mode (see above); false: the grid spans the chip and uses agent-scope accesses.
-template <typename T, int KS, int NWAVE, bool BACKWARD, bool XCD, bool STAGED = false>
-__global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPersistArgs a) {
+// (8 waves: two workgroups share a compute unit when Hp = 2048, so a wave may use at most 128 registers.)
+template <typename T, int KS, int NWAVE, bool BACKWARD, bool XCD, int STAGED = 0>
+__global__ void __launch_bounds__(64 * NWAVE, NWAVE == 8 ? 4 : 1) rnn_persistent_kernel(const RnnPersistArgs a) {
   static_assert(!STAGED || (XCD && sizeof(T) == 2 && KS % 4 == 0), "staged state loads: bf16, XCD-local, whole blocks");
   constexpr int NBLK = KS / 4;  // [32][64] blocks of this wave's share of the state (STAGED)
-  __shared__ __attribute__((aligned(16))) float red[NWAVE][16][64];
-  __shared__ __attribute__((aligned(1024))) char stage[STAGED ? NWAVE * NBLK * 4096 : 16];
+  constexpr int WAVE_STAGE = STAGED == 1 ? NBLK * 4096 : 2 * 4096;  // bytes of staging per wave
+  static_assert(STAGED != 2 || NBLK >= 2, "streaming needs at least two blocks");
+  __shared__ __attribute__((aligned(16))) float red_own[STAGED == 2 ? 1 : NWAVE][16][64];
+  __shared__ __attribute__((aligned(1024))) char stage[STAGED ? NWAVE * WAVE_STAGE : 16];
   __shared__ int s_ticket;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // partial 32x32 tile of wave q (4 KB): its own array, or (STAGED = 2) the start of wave q's staging memory
+  auto red_at = [&](int q) -> float * {
+    if constexpr (STAGED == 2) return reinterpret_cast<float *>(stage + q * WAVE_STAGE);
+    else return &red_own[q][0][0];
+  };
   const int nsb = a.Bp / 32;
   int sb, ub;
   unsigned nwg;
@@ -285,22 +299,42 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
       typename FragT<T>::type f[KS];
 #if defined(__HIP_DEVICE_COMPILE__)
       if constexpr (STAGED) {
-        char *sw = stage + wave * (NBLK * 4096);
+        char *sw = stage + wave * WAVE_STAGE;
         const int soff = (int)((long)(BACKWARD ? t + 1 : t) * slot * 2);
-#pragma unroll
-        for (int b = 0; b < NBLK; ++b)
+        auto copy_block = [&](int b, char *dst) {  // block b of this wave's share -> 4 KB at dst
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const unsigned lds_addr = (unsigned)(unsigned long long)(lds_void_ptr)(sw + b * 4096 + i * 1024);
+            const unsigned lds_addr = (unsigned)(unsigned long long)(lds_void_ptr)(dst + i * 1024);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                          :
                          : "s"(lds_addr), "v"(goff[i]), "s"(rsrc), "s"(soff + b * 128)
                          : "memory", "m0");
           }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies have landed in LDS
+        };
+        if constexpr (STAGED == 1) {
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
-          f[kk] = *reinterpret_cast<const bf16x8_t *>(sw + (kk >> 2) * 4096 + frag_off[kk & 3]);
+          for (int b = 0; b < NBLK; ++b) copy_block(b, sw + b * 4096);
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies have landed in LDS
+#pragma unroll
+          for (int kk = 0; kk < KS; ++kk)
+            f[kk] = *reinterpret_cast<const bf16x8_t *>(sw + (kk >> 2) * 4096 + frag_off[kk & 3]);
+        } else {
+          copy_block(0, sw);
+          copy_block(1, sw + 4096);
+#pragma unroll
+          for (int b = 0; b < NBLK; ++b) {
+            // block b has landed when at most the 4 loads of block b+1 are outstanding (loads return in order)
+            if (b + 1 < NBLK) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            const char *buf = sw + (b & 1) * 4096;
+#pragma unroll
+            for (int st = 0; st < 4; ++st) f[b * 4 + st] = *reinterpret_cast<const bf16x8_t *>(buf + frag_off[st]);
+            if (b + 2 < NBLK) {
+              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the fragments are in registers: the buffer is free
+              copy_block(b + 2, sw + (b & 1) * 4096);
+            }
+          }
+        }
       } else
 #endif
       {
@@ -316,12 +350,12 @@ __global__ void __launch_bounds__(64 * NWAVE) rnn_persistent_kernel(const RnnPer
       for (int r = 0; r < 16; ++r) acc[r] += acc2[r];
     }
 #pragma unroll
-    for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[r];
+    for (int r = 0; r < 16; ++r) red_at(wave)[r * 64 + lane] = acc[r];
     __syncthreads();
-    f32x4_t s = *reinterpret_cast<const f32x4_t *>(&red[0][er][el]);
+    f32x4_t s = *reinterpret_cast<const f32x4_t *>(red_at(0) + er * 64 + el);
 #pragma unroll
     for (int q = 1; q < NWAVE; ++q) {
-      const f32x4_t p = *reinterpret_cast<const f32x4_t *>(&red[q][er][el]);
+      const f32x4_t p = *reinterpret_cast<const f32x4_t *>(red_at(q) + er * 64 + el);
 #pragma unroll
       for (int e = 0; e < 4; ++e) s[e] += p[e];
     }

@@ -289,6 +289,18 @@ int rnn_step_splits(const rnnlm_t *h) {
   return S >= 2 ? (int)S : 0;
 }
 
+// Workgroups of a kernel that one compute unit holds at once, as the runtime computes it (asked once).
+template <auto Kern>
+int blocks_per_cu(int threads) {
+  static int n = -1;
+  if (n < 0) {
+    int v = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, Kern, threads, 0) != hipSuccess) v = 0;
+    n = v;
+  }
+  return n;
+}
+
 template <typename T, bool BACKWARD>
 int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st) {
   RnnPersistArgs a;
@@ -311,11 +323,15 @@ int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st
   // XCD-local mode: one group of Hp/32 workgroups per block of 32 streams, group x on XCD x
   const bool xcd = h->xcd_local && h->Bp / 32 <= NUM_XCD;
   const dim3 grid(xcd ? (unsigned)(NUM_XCD * (h->Hp / 32)) : (unsigned)((h->Bp / 32) * (h->Hp / 32)));
-  // bf16, XCD-local, 4 waves, whole [32][64] blocks per wave: the state goes through LDS (coalesced loads)
+  // bf16, XCD-local, whole [32][64] blocks per wave: the state goes through LDS (coalesced loads), provided
+  // the runtime confirms that a whole group of Hp/32 such workgroups fits the 32 compute units of an XCD
 #define RNNLM_LAUNCH_PERSIST(KS, NW)                                                                        \
   do {                                                                                                      \
-    if constexpr (sizeof(T) == 2 && NW == 4 && KS % 4 == 0) {                                               \
-      if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true, true>), grid, dim3(64 * NW), 0, st, a); \
+    if constexpr (sizeof(T) == 2 && KS % 4 == 0) {                                                          \
+      constexpr int SM = NW == 4 ? 1 : 2;                                                                   \
+      if (xcd && 32 * blocks_per_cu<rnn_persistent_kernel<T, KS, NW, BACKWARD, true, SM>>(64 * NW) >= h->Hp / 32)   \
+        hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true, SM>), grid, dim3(64 * NW), 0, st, a);  \
+      else if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true>), grid, dim3(64 * NW), 0, st, a); \
       else hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, false>), grid, dim3(64 * NW), 0, st, a);  \
     } else {                                                                                                \
       if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true>), grid, dim3(64 * NW), 0, st, a); \

@@ -226,7 +226,10 @@ def test_token_out_of_range_is_reported_not_faulted():
 
 # the last two: 1024 < H <= 2048 (8-wave persistent recurrent kernel) and H > 2048 (per-step launches)
 BF16_SHAPES = [(3000, 256, 32, 4), (2049, 130, 5, 9), (5000, 384, 64, 6), (1000, 1100, 8, 3), (700, 2100, 4, 2),
-               (600, 2200, 256, 2)]  # last: wide hidden layer, 256 streams: per-step launches split over the contraction
+               (600, 2200, 256, 2),  # wide hidden layer, 256 streams: per-step launches split over the contraction
+               # the persistent recurrent kernel's LDS-staged variants: 4 waves with 3 blocks per wave (Hp = 768),
+               # 8 waves streaming 3 and 4 blocks per wave (Hp = 1536, 2048; several blocks of 32 streams)
+               (900, 700, 6, 4), (900, 1500, 40, 3), (800, 2048, 70, 3)]
 
 
 @pytest.mark.parametrize("V,H,B,T", BF16_SHAPES)
