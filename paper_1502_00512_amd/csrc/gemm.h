@@ -742,6 +742,72 @@ struct EpiSgdT : EpiZeroInit {
   }
 };
 
+// Fused SGD on a weight-gradient contraction computed in the matrix's own orientation: tile rows = weight
+// rows, tile columns = weight columns, so the 32 lanes that share an accumulator register hold 32 consecutive
+// columns of one weight row: every 4-byte access of a half-wave falls into one 128-byte line (two lines per
+// wave instruction).  The transposed form above moves 16 bytes per lane but spreads a wave instruction over
+// 32 weight rows, i.e. 32 lines, and the vector memory path then spends its time on line look-ups; for the
+// large output matrix that made the epilogue several times longer than its traffic needs.  Same contract as
+// EpiSgdT otherwise (out = alpha*W - lr*acc on the R x C valid entries, optional compute copy Wc).
+template <typename T>
+struct EpiSgd : EpiZeroInit {
+  const float *W;
+  float *out;
+  T *Wc;
+  long ldw, ldc;
+  int R, C;
+  float alpha, lr;
+  template <int BM, int BN>
+  static constexpr int lds_bytes() { return 0; }
+  template <int BM, int BN, int TM, int TN, int NT>
+  __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
+    const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
+    const int lc = lane & 31;
+    if (row0 + 32 * TM <= R && col0 + 32 * TN <= C) {
+      // interior: no checks; the master values of a whole 32-row block of the wave tile (TN x 16 loads per
+      // lane) are requested before any is used (W and out alias when training in place)
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        float w[TN][16];
+        if (alpha != 0.0f) {
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              w[j][r] = W[(long)(row0 + i * 32 + RNNLM_ACC_ROW(r, lane)) * ldw + col0 + j * 32 + lc];
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const long row = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
+            const int col = col0 + j * 32 + lc;
+            const float nv = ((alpha != 0.0f) ? alpha * w[j][r] : 0.0f) - lr * acc[i][j][r];
+            out[row * ldw + col] = nv;
+            if (Wc) Wc[row * ldc + col] = from_f32<T>(nv);
+          }
+      }
+      return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = col0 + j * 32 + lc;
+        if (col >= C) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const long row = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
+          if (row >= R) continue;
+          const float w = (alpha != 0.0f) ? alpha * W[row * ldw + col] : 0.0f;
+          const float nv = w - lr * acc[i][j][r];
+          out[row * ldw + col] = nv;
+          if (Wc) Wc[row * ldc + col] = from_f32<T>(nv);
+        }
+      }
+  }
+};
+
 // Recurrent backward step: dA = (dH_out + dA_next U) * h * (1 - h).  Rows = streams, cols = units.
 template <typename T>
 struct EpiRnnBwd : EpiZeroInit {

@@ -775,6 +775,22 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j], contracted transposed (tile rows = j, tile columns = v);
     // compressed architecture: the output-side update of the tied matrix, E[v][p] -= lr * sum_m dz[v][m] p[m][p]
     StageTimer tm(h, RNNLM_STAGE_OUT_BWD_W, st);
+    if (sizeof(T) == 2 && c.P == 0) {
+      // bf16 path: contracted in the matrix's own orientation (tile rows = v, tile columns = j), whose update
+      // epilogue touches two 128-byte lines per wave instruction instead of 32
+      EpiSgd<T> e2;
+      e2.W = h->buf.Wo;
+      e2.out = u.Wo;
+      e2.Wc = u.refresh_copies ? Wo_c : nullptr;
+      e2.ldw = c.H;
+      e2.ldc = Hp;
+      e2.R = c.V;
+      e2.C = c.H;
+      e2.alpha = u.alpha;
+      e2.lr = u.lr;
+      if constexpr (sizeof(T) == 2)
+        HIP_TRY((big_gemm<T, 2, 4, ROWK, KROW, true>(st, ZT, ldz, Hs_c + (long)Bp * Hp, Hp, Vp, Hp, Mp, 1, e2, 2)));
+    } else {
     EpiSgdT<T> epi;
     epi.W = c.P > 0 ? h->buf.E : h->buf.Wo;
     epi.out = c.P > 0 ? u.E : u.Wo;
@@ -794,6 +810,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
       }
     } else {
       HIP_TRY((big_gemm<T, 2, 4, KROW, ROWK, true>(st, feat, h->Dp, ZT, ldz, h->Dp, Vp, Mp, 1, epi, -2)));
+    }
     }
     }
     if (c.P > 0) {
