@@ -368,7 +368,9 @@ __device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c
 // bf16: a lane holds one column and runs of 4 consecutive rows.  Neighbouring lanes swap one packed
 // pair so that each lane owns two adjacent columns of one row (one dword), the tile is assembled in
 // LDS (which the main loop no longer needs; four regions, one per quarter of the rows) and leaves as
-// 16-byte row-contiguous stores.
+// 16-byte row-contiguous stores, marked nontemporal: the tile is hundreds of megabytes per launch, is read
+// once by the next kernel, and ordinary stores cost the contraction 6 % (they displace the operand panels
+// the other workgroups of the XCD are re-reading from its L2).
 template <int BM, int BN, int TM, int TN, int NT>
 __device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c, bf16_t *out, long ld) {
   constexpr int PITCH = StageGeom<BN>::PITCH;
@@ -416,7 +418,7 @@ __device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c
       const int row = k * RPI + r_lo;
       const char *quarter = c.q[(k * RPI) / QR];
       const u32x4_t v = *reinterpret_cast<const u32x4_t *>(quarter + ((k * RPI) % QR + r_lo) * PITCH + ch * 16);
-      *reinterpret_cast<u32x4_t *>(out + (long)(c.tile_row0 + row) * ld + c.tile_col0 + ch * 8) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(out + (long)(c.tile_row0 + row) * ld + c.tile_col0 + ch * 8));
     }
   } else {
 #pragma unroll 4
@@ -424,7 +426,7 @@ __device__ inline void store_tile(const f32x16_t (&val)[TM][TN], const EpiCtx &c
       const int row = idx / CPR, ch = idx % CPR;
       const char *quarter = quarter_ptr(c, row / QR);
       const u32x4_t v = *reinterpret_cast<const u32x4_t *>(quarter + (row % QR) * PITCH + ch * 16);
-      *reinterpret_cast<u32x4_t *>(out + (long)(c.tile_row0 + row) * ld + c.tile_col0 + ch * 8) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t *>(out + (long)(c.tile_row0 + row) * ld + c.tile_col0 + ch * 8));
     }
   }
 }

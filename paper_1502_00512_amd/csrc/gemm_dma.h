@@ -134,7 +134,10 @@ constexpr int dma_stage_bytes() {
   return loop > epi ? loop : epi;
 }
 
-template <int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi>
+// PERSIST: the grid is one workgroup per compute unit and each walks the work items id, id + grid, ... (the
+// grid is a multiple of 8, so a workgroup stays on the XCD whose chunk of tiles it walks): the next tile's
+// first loads are issued while the previous tile's stores drain, and no workgroup is relaunched per tile.
+template <int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi, bool PERSIST = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma_kernel(const GemmShape g, const Epi epi) {
 #if defined(__HIP_DEVICE_COMPILE__)
   constexpr int NT = WGM * WGN * 64;
@@ -147,8 +150,10 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma_kernel(const GemmShape
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WGM, wn = wave / WGM;
+  const int nwork = g.perXcd * NUM_XCD;
+  for (int wid = blockIdx.x; wid < nwork; wid += PERSIST ? (int)gridDim.x : nwork) {
   int tile_m, tile_n, split;
-  if (!map_workgroup(g, blockIdx.x, split, tile_m, tile_n)) return;  // uniform for the workgroup
+  if (!map_workgroup(g, wid, split, tile_m, tile_n)) continue;  // uniform for the workgroup
   const int kb0 = split * g.kBlocksPerSplit;
   const int kb1 = min(kb0 + g.kBlocksPerSplit, g.kBlocks);
   const int nk = kb1 - kb0;
@@ -249,10 +254,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma_kernel(const GemmShape
   ctx.tid = tid;
   ctx.split = split;
   epi.template run<BM, BN, TM, TN, NT>(acc, ctx);
+  if (PERSIST) {
+    // the epilogue's LDS reads have returned (lgkmcnt 0; its global stores may still be in flight: vmcnt and
+    // expcnt are left alone) before anyone's next loads overwrite the stages
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_s_barrier();
+  }
+  }
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
-template <int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi>
+template <int BM, int BN, int WGM, int WGN, int LA, int LB, bool PERSIST = false, class Epi>
 inline hipError_t launch_gemm_dma(hipStream_t stream, const void *A, long lda, const void *B, long ldb, long Mg,
                                   long Ng, long K, int splits, const Epi &epi, int band = 4) {
   constexpr int BK = 64;
@@ -279,8 +291,10 @@ inline hipError_t launch_gemm_dma(hipStream_t stream, const void *A, long lda, c
   g.perXcd = (int)((total + NUM_XCD - 1) / NUM_XCD);
   g.bandOverN = band < 0;
   g.band = band < 0 ? -band : band;
-  hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, LA, LB, Epi>), dim3((unsigned)(g.perXcd * NUM_XCD)),
-                     dim3(WGM * WGN * 64), 0, stream, g, epi);
+  unsigned grid = (unsigned)(g.perXcd * NUM_XCD);
+  if (PERSIST && grid > 256u) grid = 256u;  // one workgroup per compute unit
+  hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, LA, LB, Epi, PERSIST>), dim3(grid), dim3(WGM * WGN * 64), 0,
+                     stream, g, epi);
   return hipGetLastError();
 }
 

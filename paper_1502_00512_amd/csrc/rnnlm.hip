@@ -487,7 +487,13 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     epi.zy = zy;
     epi.V = c.V;
     epi.ldz = ldz;
-    HIP_TRY((big_gemm<T, 4, 2, ROWK, ROWK, false>(st, at<T>(h, h->L.Wo_c), h->Dp, feat, h->Dp, Vp, Mp, h->Dp, 1, epi)));
+    if constexpr (sizeof(T) == 2) {
+      // thousands of short tiles: one persistent workgroup per compute unit walks them
+      HIP_TRY((launch_gemm_dma<BIG, BIG, 4, 2, ROWK, ROWK, true>(st, at<T>(h, h->L.Wo_c), h->Dp, feat, h->Dp, Vp, Mp,
+                                                                 h->Dp, 1, epi)));
+    } else {
+      HIP_TRY((big_gemm<T, 4, 2, ROWK, ROWK, false>(st, at<T>(h, h->L.Wo_c), h->Dp, feat, h->Dp, Vp, Mp, h->Dp, 1, epi)));
+    }
   }
   StageTimer tm(h, RNNLM_STAGE_STATS, st);
   hipLaunchKernelGGL(merge_stats_kernel, dim3(blocks_for(Mrows, 64)), dim3(1024), 0, st, at<float2>(h, h->L.stat),
