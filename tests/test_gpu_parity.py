@@ -229,7 +229,8 @@ BF16_SHAPES = [(3000, 256, 32, 4), (2049, 130, 5, 9), (5000, 384, 64, 6), (1000,
                (600, 2200, 256, 2),  # wide hidden layer, 256 streams: per-step launches split over the contraction
                # the persistent recurrent kernel's LDS-staged variants: 4 waves with 3 blocks per wave (Hp = 768),
                # 8 waves streaming 3 and 4 blocks per wave (Hp = 1536, 2048; several blocks of 32 streams)
-               (900, 700, 6, 4), (900, 1500, 40, 3), (800, 2048, 70, 3)]
+               (900, 700, 6, 4), (900, 1500, 40, 3), (800, 2048, 70, 3),
+               (700, 256, 7, 1)]  # a single position: nothing flows back through time
 
 
 @pytest.mark.parametrize("V,H,B,T", BF16_SHAPES)
@@ -266,10 +267,12 @@ def test_bf16_training_tracks_oracle():
     g.rnnlm_check()
 
 
-def test_grid_barrier_timeout_is_reported():
+@pytest.mark.parametrize("precision", [FP32, BF16])
+def test_grid_barrier_timeout_is_reported(precision):
     """With a spin limit of one poll the grid barriers of the persistent recurrent kernel expire: the
-    kernels still run to their end and the next check reports the condition."""
-    g, _ = make_pair(1000, 256, 64, 6, FP32, seed=5)
+    kernels still run to their end and the next check reports the condition (fp32: operands straight from
+    memory; bf16: the LDS-staged variant)."""
+    g, _ = make_pair(1000, 256, 64, 6, precision, seed=5)
     tok = tokens(1000, 2000, 3)
     x, y = O.stream_chunk(tok, 64, 6, 0)
     g.rnnlm_set_barrier_spin_limit(1)
