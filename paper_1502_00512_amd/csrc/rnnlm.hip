@@ -778,8 +778,9 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
                                                         h->Pp, Mp, 1, epi)));
     }
     {
-    // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j], contracted transposed (tile rows = j, tile columns = v);
-    // compressed architecture: the output-side update of the tied matrix, E[v][p] -= lr * sum_m dz[v][m] p[m][p]
+    // Wo[v][j] -= lr * sum_m dz[v][m] Hs[m][j]: bf16 in the matrix's own orientation, fp32 and the compressed
+    // architecture contracted transposed (tile rows = j, tile columns = v); compressed architecture: the
+    // output-side update of the tied matrix, E[v][p] -= lr * sum_m dz[v][m] p[m][p]
     StageTimer tm(h, RNNLM_STAGE_OUT_BWD_W, st);
     if (sizeof(T) == 2 && c.P == 0) {
       // bf16 path: contracted in the matrix's own orientation (tile rows = v, tile columns = j), whose update
