@@ -56,6 +56,9 @@ def main() -> int:
                          "word matrix) on its word-prediction shape (config wp10k), full softmax + SGD")
     ap.add_argument("--streams", type=int, default=0, help="override the number of parallel streams B (scoring)")
     ap.add_argument("--noise", type=int, default=1024, help="noise words per window for --criterion nce")
+    ap.add_argument("--shortlist", type=int, default=0,
+                    help="--criterion score: score this many candidate words per position (Sec. 5.3 ranks a shortlist "
+                         "of 100) instead of the one given next word")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (counter calibration for profiler runs)")
     args = ap.parse_args()
@@ -69,8 +72,9 @@ def main() -> int:
     from paper_1502_00512_amd import binding, synth
 
     comp = args.arch == "compressed"
-    if comp and (args.criterion != "softmax" or args.optimizer != "sgd"):
-        print("bench.py: --arch compressed runs with the full softmax and plain SGD only", file=sys.stderr)
+    if comp and (args.criterion == "nce" or args.optimizer != "sgd"):
+        print("bench.py: --arch compressed runs with the full softmax and plain SGD, or --criterion score",
+              file=sys.stderr)
         return 2
     if comp and args.config == "cfg3":
         args.config = "wp10k"
@@ -117,6 +121,10 @@ def main() -> int:
     y = torch.empty(T, B, dtype=torch.int32, device="cuda")
     sum_logp = torch.zeros(1, dtype=torch.float64, device="cuda")
     scores = torch.empty(T, B, dtype=torch.float32, device="cuda")
+    if args.shortlist:
+        # candidates: seeded uniform ids (which words are on the list does not change the work)
+        cand = torch.as_tensor(np.random.default_rng(cfg.data_seed).integers(0, V, (T, B, args.shortlist)).astype(np.int32)).cuda()
+        scores = torch.empty(T, B, args.shortlist, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
     def step(k):
@@ -126,6 +134,8 @@ def main() -> int:
                                             sum_logp, stream)
         elif nce:
             g.rnnlm_nce_train_chunk(x, y, dnoise[k % total_steps], dlnq, lnZ, cfg.lr, None, sum_logp, stream)
+        elif score and args.shortlist:
+            g.rnnlm_forward_score_shortlist(x, cand, float(np.log(V)), scores, stream)
         elif score:
             g.rnnlm_forward_score(x, y, float(np.log(V)), scores, stream)
         elif rms:
@@ -139,7 +149,7 @@ def main() -> int:
         gemm_stages = ["prep", "rnn_fwd", "nce_score"]
     if rms and not nce:
         gemm_stages = ["out_fwd", "out_bwd_h", "out_bwd_w", "rmsprop"]
-    if comp:
+    if comp and not score:
         gemm_stages = ["rnn_fwd", "rnn_bwd", "out_fwd", "out_bwd_h", "out_bwd_w", "proj"]
 
     for k in range(args.warmup):
@@ -202,7 +212,12 @@ def main() -> int:
         extra["stage_ms_timed"] = {k: round(v, 4) for k, v in gemm_ms.items()}
         criterion = "forward-only unnormalised scoring of the given next words"
         metric = "scored words/sec (forward only, unnormalised output) at 1 MI355X"
-    elif comp:
+        if args.shortlist:
+            criterion = f"forward-only unnormalised scoring of a shortlist of {args.shortlist} candidate words per position"
+            metric = "positions/sec (forward only, shortlist of candidates scored per position) at 1 MI355X"
+        if comp:
+            criterion = f"compressed architecture (P={P}), " + criterion
+    elif comp and not score:
         flops_word = 6.0 * (V * P + 2.0 * P * H + H * H)
         # algorithmic flops per launch: recurrent kernels 2 H^2 per position, output contractions 2 V P per position
         work = {"rnn_fwd": 2.0 * H * H * M, "rnn_bwd": 2.0 * H * H * (M - B), "out_fwd": 2.0 * V * P * M,
@@ -265,7 +280,7 @@ def main() -> int:
             metric = "training words/sec (fwd+BPTT+rmsprop-scaled SGD) at 1 MI355X"
 
     cpu = None
-    if comp and not args.no_cpu_baseline:
+    if comp and not score and not args.no_cpu_baseline:
         cpu = cpu_baseline_compressed(cfg, E, A_, U, C_, b, tok)
     elif not args.no_cpu_baseline and not score and not rms:
         cpu = cpu_baseline(cfg, E, U, Wo, b, tok,

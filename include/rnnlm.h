@@ -187,6 +187,15 @@ int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t
 int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lnZ, float *score,
                         void *stream);
 
+/* rnnlm_forward_score for a shortlist of C candidate next words per position (Sec. 5.3 predicts the next
+ * word from a shortlist of candidates supplied by a pruned n-gram and ranks them by the network's output):
+ * score[t][s][c] = Wo[cand[t][s][c]].h_t + b[cand[t][s][c]] - lnZ (compressed architecture: the tied matrix
+ * applied to the layer above the state), unnormalised, no pass over the vocabulary.  Starts from h_state and
+ * advances it.  x: dev int32[T][B]; cand: dev int32[T][B][C], 1 <= C <= 65536, ids in [0,V) (checked like
+ * token ids); score: dev float[T][B][C].  Works for both architectures, as does rnnlm_forward_score. */
+int rnnlm_forward_score_shortlist(rnnlm_t *h, const int32_t *x, const int32_t *cand, int32_t C, int32_t T, float lnZ,
+                                  float *score, void *stream);
+
 /* ---- Compressed architecture (Sec. 5.3: word prediction under a memory limit) ---------------------------
  * Sec. 5.3 shrinks the network by inserting layers of 512 units below and above the hidden state, tying the
  * input-side and output-side word matrices as each other's transpose, and quantising all weights, trained
@@ -197,7 +206,7 @@ int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t 
  * rnnlm_forward_logprob, rnnlm_train_chunk, rnnlm_perplexity, rnnlm_stream_chunk and the state calls work on
  * this model unchanged (the tied matrix receives the sum of its input-side and output-side gradients; the
  * output-side part is applied first); rnnlm_grad_chunk_compressed exports its gradients.  The
- * noise-contrastive, rmsprop and rnnlm_forward_score calls and rnnlm_grad_chunk return RNNLM_ERR_ARG. */
+ * noise-contrastive and rmsprop calls and rnnlm_grad_chunk return RNNLM_ERR_ARG; the two scoring calls work. */
 
 /* rnnlm_grad_chunk for the compressed architecture: gradients of the window's mean negative
  * log-likelihood into dE: dev float[V][P] (both roles of the tied matrix added), dA: dev float[H][P],

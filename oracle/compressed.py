@@ -86,6 +86,27 @@ def forward_logprob(m: CompressedModel, x: np.ndarray, y: np.ndarray) -> np.ndar
     return logp
 
 
+def forward_score_shortlist(m: CompressedModel, x: np.ndarray, cand: np.ndarray, lnZ: float = 0.0) -> np.ndarray:
+    """Unnormalised scores E[c].p_t + b[c] - lnZ of the candidate words cand[T][B][C] (Sec. 5.3 ranks a
+    shortlist of candidates); advances m.h.  forward_score(m, x, y) is the case of one candidate."""
+    T, B = x.shape
+    if cand.shape[:2] != (T, B) or cand.min() < 0 or cand.max() >= m.E.shape[0]:
+        raise ValueError("oracle: bad argument")
+    score = np.zeros(cand.shape)
+    h = m.h
+    for t in range(T):
+        h = 1.0 / (1.0 + np.exp(-(m.E[x[t]] @ m.A.T + h @ m.U.T)))
+        p = h @ m.C.T
+        for s in range(B):
+            score[t, s] = m.E[cand[t, s]] @ p[s] + m.b[cand[t, s]] - lnZ
+    m.h = h.copy()
+    return score
+
+
+def forward_score(m: CompressedModel, x: np.ndarray, y: np.ndarray, lnZ: float = 0.0) -> np.ndarray:
+    return forward_score_shortlist(m, x, y[:, :, None], lnZ)[:, :, 0]
+
+
 def grad_chunk(m: CompressedModel, x: np.ndarray, y: np.ndarray):
     """Gradient of the window's mean negative log-likelihood with respect to E, A, U, C, b at the given
     parameters; the carried state is a constant (the chain stops at the window start).  m is not modified.

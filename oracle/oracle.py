@@ -255,6 +255,19 @@ def forward_score(m: Model, x, y, lnZ=0.0):
     return score
 
 
+def forward_score_shortlist(m: Model, x, cand, lnZ=0.0):
+    """Unnormalised scores of a shortlist of candidate next words, score[T][B][C] for cand[T][B][C] (Sec. 5.3
+    ranks the candidates a pruned n-gram proposes); one forward_score pass per candidate column from the same
+    starting state; advances m.h."""
+    T, B, Cn = cand.shape
+    score = np.empty((T, B, Cn), np.float64)
+    h0 = m.h.copy()
+    for c in range(Cn):
+        m.h = h0.copy()
+        score[:, :, c] = forward_score(m, x, np.ascontiguousarray(cand[:, :, c]), lnZ)
+    return score
+
+
 def perplexity(m: Model, tok: np.ndarray, T: int):
     """(PPL, scored) over all full windows of T positions, B streams from a zero state."""
     ppl = C.c_double(0.0)

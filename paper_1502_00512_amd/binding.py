@@ -23,7 +23,7 @@ SYMBOLS = [
     "rnnlm_profile_enable", "rnnlm_profile_read", "rnnlm_set_barrier_spin_limit", "rnnlm_measure_peaks",
     "rnnlm_nce_train_chunk", "rnnlm_nce_grad_chunk", "rnnlm_forward_score",
     "rnnlm_train_chunk_rmsprop", "rnnlm_nce_train_chunk_rmsprop",
-    "rnnlm_grad_chunk_compressed", "rnnlm_quantize_weights",
+    "rnnlm_grad_chunk_compressed", "rnnlm_quantize_weights", "rnnlm_forward_score_shortlist",
 ]
 
 STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce",
@@ -92,6 +92,7 @@ def load():
     lib.rnnlm_nce_train_chunk_rmsprop.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, f32, f32, f32,
                                                   C.POINTER(rnnlm_rmsprop_state), vp, vp, vp]
     lib.rnnlm_forward_score.argtypes = [vp, vp, vp, i32, f32, vp, vp]
+    lib.rnnlm_forward_score_shortlist.argtypes = [vp, vp, vp, i32, i32, f32, vp, vp]
     lib.rnnlm_grad_chunk_compressed.argtypes = [vp, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.rnnlm_quantize_weights.argtypes = [vp, C.POINTER(rnnlm_quantized), vp]
     lib.rnnlm_profile_enable.argtypes = [vp, C.c_uint32]
@@ -274,6 +275,15 @@ class Rnnlm:
             score = torch.empty(T, self.B, dtype=torch.float32, device=self.device)
         _ok(self.lib.rnnlm_forward_score(self.handle, _ptr(x), _ptr(y), T, lnZ, _ptr(score), _stream(stream)),
             "rnnlm_forward_score")
+        return score
+
+    def rnnlm_forward_score_shortlist(self, x, cand, lnZ: float = 0.0, score=None, stream=None):
+        import torch
+        T, C_ = x.shape[0], cand.shape[2]
+        if score is None:
+            score = torch.empty(T, self.B, C_, dtype=torch.float32, device=self.device)
+        _ok(self.lib.rnnlm_forward_score_shortlist(self.handle, _ptr(x), _ptr(cand), C_, T, lnZ, _ptr(score),
+                                                   _stream(stream)), "rnnlm_forward_score_shortlist")
         return score
 
     def rnnlm_nce_train_chunk(self, x, y, noise, lnq, lnZ: float, lr: float, J=None, sum_J=None, stream=None):

@@ -91,6 +91,33 @@ __global__ void __launch_bounds__(256) nce_target_score_kernel(const T *__restri
   }
 }
 
+// Scores of a shortlist of C candidate words per position (Sec. 5.3 ranks a shortlist of candidates):
+// out[(t*B + s)*C + c] = Wc[cand].F[row] + b[cand] - shift, F = what the output layer reads (ld = width
+// Dp).  One wave per (position, candidate); ids outside [0, V) are clamped and raise flags[0].
+template <typename T>
+__global__ void __launch_bounds__(256) score_candidates_kernel(const T *__restrict__ F, const T *__restrict__ Wc, int Dp,
+                                                               const int32_t *__restrict__ cand, int C, int V,
+                                                               const float *__restrict__ b, float shift, long total,
+                                                               int B, int Bp, int32_t *__restrict__ flags,
+                                                               float *__restrict__ out) {
+  const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (item >= total) return;
+  const long pos = item / C;  // compact position index t*B + s
+  const long row = (pos / B) * Bp + (pos % B);
+  int w = cand[item];
+  if (w < 0 || w >= V) {
+    if (lane == 0) flags[0] = 1;
+    w = min(max(w, 0), V - 1);
+  }
+  const T *frow = F + row * Dp, *wrow = Wc + (long)w * Dp;
+  float acc = 0.0f;
+  for (int c = lane; c < Dp; c += 64) acc = fmaf(to_f32(frow[c]), to_f32(wrow[c]), acc);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+  if (lane == 0) out[item] = acc + b[w] - shift;
+}
+
 // Elementwise pass over one padded position (one workgroup per row of the score matrix S[Mp][Kp]):
 // dS[row][j] = sigmoid(S + off[j]) * scale in the contraction operand type (0 for padding rows and
 // columns), the position's loss J, and the target coefficient ct[row] = -(1 - sigmoid(dt)) * scale.

@@ -389,7 +389,7 @@ int sort_segments(rnnlm_t *h, int Tn, int32_t *perm, int32_t *seg, int32_t *nseg
 // started on the side stream as soon as the padded ids exist (joined in backward_window).
 template <typename T>
 int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *logp_out, bool advance_state,
-                   bool with_output, hipStream_t st, bool sort_inputs = false) {
+                   bool with_output, hipStream_t st, bool sort_inputs = false, bool need_feat = false) {
   const rnnlm_config &c = h->cfg;
   const int Hp = h->Hp, Bp = h->Bp, Vp = h->Vp;
   const int Mrows = Tn * Bp;
@@ -465,7 +465,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
       HIP_TRY((launch_gemm<T, 32, 64, 1, 2, ROWK, ROWK>(st, A_, Hp, B_, Hp, Bp, Hp, Hp, 1, epi)));
     }
   }
-  if (!with_output) return RNNLM_OK;  // the noise-contrastive calls score the hidden states themselves
+  if (!with_output && !(need_feat && c.P > 0)) return RNNLM_OK;  // the noise-contrastive calls score the hidden states themselves
   const T *feat = Hs_c + (long)Bp * Hp;  // what the output layer reads: the states, or the layer above them
   if (c.P > 0) {
     StageTimer tm(h, RNNLM_STAGE_PROJ, st);
@@ -477,6 +477,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
                                                         h->Pp, Hp, 1, epi)));
     feat = at<T>(h, h->L.P_c);
   }
+  if (!with_output) return RNNLM_OK;  // the scoring calls only wanted the layer above the states
   {
     StageTimer tm(h, RNNLM_STAGE_OUT_FWD, st);
     EpiOutFwd<T> epi;
@@ -916,14 +917,32 @@ int window_call(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float *l
 
 template <typename T>
 int score_call(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float lnZ, float *score, hipStream_t st) {
-  int rc = forward_window<T>(h, x, y, Tn, nullptr, true, false, st);
+  int rc = forward_window<T>(h, x, y, Tn, nullptr, true, false, st, false, true);
   if (rc) return rc;
   const int Mrows = Tn * h->Bp;
   StageTimer tm(h, RNNLM_STAGE_NCE_SCORE, st);
+  // what the output layer reads: the states, or (compressed architecture) the layer above them
+  const T *feat = h->cfg.P > 0 ? at<T>(h, h->L.P_c) : at<T>(h, h->L.Hs_c) + (long)h->Bp * h->Hp;
   // the per-position scratch of the log-probability path holds the padded result
-  hipLaunchKernelGGL(nce_target_score_kernel<T>, dim3(blocks_for(Mrows, 4)), dim3(256), 0, st,
-                     at<T>(h, h->L.Hs_c) + (long)h->Bp * h->Hp, at<T>(h, h->L.Wo_c), h->Hp, at<int32_t>(h, h->L.yp),
-                     h->buf.b, (const float *)nullptr, lnZ, Mrows, h->cfg.B, h->Bp, at<float>(h, h->L.zy), score);
+  hipLaunchKernelGGL(nce_target_score_kernel<T>, dim3(blocks_for(Mrows, 4)), dim3(256), 0, st, feat,
+                     at<T>(h, h->L.Wo_c), h->Dp, at<int32_t>(h, h->L.yp), h->buf.b, (const float *)nullptr, lnZ, Mrows,
+                     h->cfg.B, h->Bp, at<float>(h, h->L.zy), score);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
+// Forward pass, then the scores of C candidate words per position (no targets: y = nullptr).
+template <typename T>
+int shortlist_call(rnnlm_t *h, const int32_t *x, const int32_t *cand, int C, int Tn, float lnZ, float *score,
+                   hipStream_t st) {
+  int rc = forward_window<T>(h, x, nullptr, Tn, nullptr, true, false, st, false, true);
+  if (rc) return rc;
+  StageTimer tm(h, RNNLM_STAGE_NCE_SCORE, st);
+  const T *feat = h->cfg.P > 0 ? at<T>(h, h->L.P_c) : at<T>(h, h->L.Hs_c) + (long)h->Bp * h->Hp;
+  const long total = (long)Tn * h->cfg.B * C;
+  hipLaunchKernelGGL(score_candidates_kernel<T>, dim3(blocks_for(total, 4)), dim3(256), 0, st, feat,
+                     at<T>(h, h->L.Wo_c), h->Dp, cand, C, h->cfg.V, h->buf.b, lnZ, total, h->cfg.B, h->Bp, p_flags(h),
+                     score);
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
 }
@@ -1151,10 +1170,19 @@ int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t
 
 int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lnZ, float *score,
                         void *stream) {
-  if (!window_args_ok(h, x, y, T) || !score || !(lnZ == lnZ) || h->cfg.P > 0) return RNNLM_ERR_ARG;
+  if (!window_args_ok(h, x, y, T) || !score || !(lnZ == lnZ)) return RNNLM_ERR_ARG;
   hipStream_t st = (hipStream_t)stream;
   return (h->cfg.precision == RNNLM_FP32) ? score_call<float>(h, x, y, T, lnZ, score, st)
                                           : score_call<bf16_t>(h, x, y, T, lnZ, score, st);
+}
+
+int rnnlm_forward_score_shortlist(rnnlm_t *h, const int32_t *x, const int32_t *cand, int32_t C, int32_t T, float lnZ,
+                                  float *score, void *stream) {
+  if (!h || !x || !cand || !score || T < 1 || T > h->cfg.T_max || C < 1 || C > 65536 || !(lnZ == lnZ))
+    return RNNLM_ERR_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  return (h->cfg.precision == RNNLM_FP32) ? shortlist_call<float>(h, x, cand, C, T, lnZ, score, st)
+                                          : shortlist_call<bf16_t>(h, x, cand, C, T, lnZ, score, st);
 }
 
 namespace {

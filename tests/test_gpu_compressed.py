@@ -180,13 +180,45 @@ def test_quantised_weights(precision):
     g.rnnlm_check()
 
 
+@pytest.mark.parametrize("precision", [FP32, BF16])
+def test_scoring_and_shortlist(precision):
+    """Unnormalised scores of given next words and of a shortlist of candidates per position (Sec. 5.3 ranks a
+    shortlist), chained over two calls."""
+    V, H, P, B, T, Cn = 1500, 128, 64, 5, 6, 37
+    g, o = make_pair(V, H, P, B, T, precision, seed=13, scale=0.3)
+    r = np.random.default_rng(7)
+    tol = dict(rel=1e-4, abs_=1e-5) if precision == FP32 else None
+    for k in range(2):
+        x, y = window(V, B, T, 130 + k)
+        cand = r.integers(0, V, (T, B, Cn)).astype(np.int32)
+        cand[:, :, 0] = y                      # the true next word is on the list
+        h0 = g.h_state.clone()
+        o2 = o.copy()
+        ref1 = Cq.forward_score(o2, x, y, 0.7)
+        got1 = g.rnnlm_forward_score(dev(x), dev(y), 0.7)
+        g.h_state.copy_(h0)
+        ref = Cq.forward_score_shortlist(o, x, cand, 0.7)
+        got = g.rnnlm_forward_score_shortlist(dev(x), dev(cand), 0.7)
+        if precision == FP32:
+            check_logp(got1, ref1, **tol)
+            check_logp(got, ref, **tol)
+        else:
+            scale = np.abs(ref).max()
+            assert np.abs(got.cpu().numpy() - ref).max() <= 2e-2 * scale
+            assert np.abs(got1.cpu().numpy() - ref1).max() <= 2e-2 * scale
+        assert torch.equal(got[:, :, 0], got1)  # same arithmetic for the same word
+    g.rnnlm_check()
+    bad = torch.full((T, B, 2), V, dtype=torch.int32, device="cuda")
+    g.rnnlm_forward_score_shortlist(dev(x), bad)
+    with pytest.raises(binding.RnnlmError):
+        g.rnnlm_check()                        # candidate ids are checked like token ids
+
+
 def test_argument_checks():
     g, _ = make_pair(300, 32, 16, 2, 4, FP32)
     x, y = window(300, 2, 4, 1)
     with pytest.raises(binding.RnnlmError):
         g.rnnlm_grad_chunk(dev(x), dev(y))                 # the plain export does not fit this model
-    with pytest.raises(binding.RnnlmError):
-        g.rnnlm_forward_score(dev(x), dev(y))
     E, U, Wo, b = synth.make_weights(300, 32, "uniform", 0.1, 1)
     with pytest.raises(binding.RnnlmError):                # A without the compressed layout of E
         bad = binding.Rnnlm.__new__(binding.Rnnlm)

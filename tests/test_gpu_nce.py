@@ -288,3 +288,25 @@ def test_forward_score_matches_the_normalised_path_up_to_the_log_partition():
         lp = g.rnnlm_forward_logprob(dev(x), dev(y))
         parts.append((s - lp).cpu().numpy())
     assert np.abs(parts[0] - parts[1]).max() < 1e-4
+
+
+def test_forward_score_shortlist_plain_architecture():
+    """Scores of a shortlist of candidate next words per position on the plain architecture, fp32 and bf16,
+    against one oracle scoring pass per candidate column."""
+    V, H, B, T, Cn = 1200, 96, 6, 5, 19
+    E, U, Wo, b = synth.make_weights(V, H, "uniform", 0.3, 17)
+    b = synth.uniform_weights((V,), -0.2, 0.2, 18)
+    tok = synth.zipf_tokens(B * T + B + 1, V, 1.1, 19)
+    x, y = O.stream_chunk(tok, B, T, 0)
+    cand = np.random.default_rng(5).integers(0, V, (T, B, Cn)).astype(np.int32)
+    cand[:, :, 3] = y
+    ref = O.forward_score_shortlist(O.Model.from_weights(E, U, Wo, b, B), x, cand, 1.1)
+    for precision, tol in ((binding.RNNLM_FP32, 1e-4), (binding.RNNLM_BF16_FP32MASTER, 2e-2)):
+        g = binding.Rnnlm(E, U, Wo, b, B, T, precision)
+        got = g.rnnlm_forward_score_shortlist(torch.as_tensor(x).cuda(), torch.as_tensor(cand).cuda(), 1.1)
+        single = binding.Rnnlm(E, U, Wo, b, B, T, precision).rnnlm_forward_score(
+            torch.as_tensor(x).cuda(), torch.as_tensor(y).cuda(), 1.1)
+        g.rnnlm_check()
+        assert np.abs(got.cpu().numpy() - ref).max() <= tol * max(1.0, np.abs(ref).max())
+        assert torch.equal(got[:, :, 3], single)
+

@@ -161,6 +161,26 @@ def test_zero_word_matrix_gives_the_uniform_distribution():
     assert n == 100 and ppl == pytest.approx(12.0, rel=1e-13)
 
 
+def test_shortlist_scores_normalise_to_the_pinned_distribution():
+    """With every word on the shortlist, score - logsumexp(score) is the normalised log-probability of the
+    pinned forward pass, whatever lnZ; a single candidate is the scoring call of one word."""
+    m = rand_cmodel(9, 5, 3, 2, 81)
+    x, y = rand_tokens(9, 4, 2, 82)
+    allw = np.broadcast_to(np.arange(9), (4, 2, 9)).copy()
+    a, b_ = m.copy(), m.copy()
+    sc = Cq.forward_score_shortlist(a, x, allw, lnZ=1.7)
+    lp = Cq.forward_logprob(b_, x, y)
+    mx = sc.max(axis=2, keepdims=True)
+    lse = mx[:, :, 0] + np.log(np.exp(sc - mx).sum(axis=2))
+    picked = np.take_along_axis(sc, y[:, :, None], axis=2)[:, :, 0]
+    assert picked - lse == pytest.approx(lp, rel=1e-12, abs=1e-13)
+    assert np.array_equal(a.h, b_.h)
+    assert Cq.forward_score(m.copy(), x, y, 1.7) == pytest.approx(picked, rel=1e-14)
+    perm = np.random.default_rng(3).permutation(9)           # the order of the candidates does not matter
+    sc2 = Cq.forward_score_shortlist(m.copy(), x, allw[:, :, perm], lnZ=1.7)
+    assert sc2 == pytest.approx(sc[:, :, perm], rel=1e-14)
+
+
 # ---- quantiser -------------------------------------------------------------------------------------
 
 def test_quantiser_on_hand_picked_rows():

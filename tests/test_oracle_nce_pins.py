@@ -324,3 +324,23 @@ def test_score_advances_state_like_the_normalised_pass_and_chains():
     c = m.copy()
     parts = np.concatenate([O.forward_score(c, x[t:t + 1], y[t:t + 1], 0.3) for t in range(T)])
     assert parts == pytest.approx(whole, rel=1e-13)
+
+
+def test_shortlist_scores_normalise_to_the_pinned_distribution():
+    """With every word on the shortlist, score - logsumexp(score) is the pinned normalised log-probability,
+    whatever lnZ; the order of the candidates does not matter; the state advances as in a forward pass."""
+    m = rand_model(8, 4, 2, 91, scale=0.6, h_scale=1.0)
+    x, y = rand_tokens(8, 5, 2, 92)
+    allw = np.ascontiguousarray(np.broadcast_to(np.arange(8, dtype=np.int32), (5, 2, 8)))
+    a, b_ = m.copy(), m.copy()
+    sc = O.forward_score_shortlist(a, x, allw, lnZ=0.9)
+    lp = O.forward_logprob(b_, x, y)
+    mx = sc.max(axis=2, keepdims=True)
+    lse = mx[:, :, 0] + np.log(np.exp(sc - mx).sum(axis=2))
+    picked = np.take_along_axis(sc, y[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    assert picked - lse == pytest.approx(lp, rel=1e-12, abs=1e-13)
+    assert np.array_equal(a.h, b_.h)
+    perm = np.random.default_rng(4).permutation(8)
+    sc2 = O.forward_score_shortlist(m.copy(), x, np.ascontiguousarray(allw[:, :, perm]), lnZ=0.9)
+    assert sc2 == pytest.approx(sc[:, :, perm], rel=1e-14)
+
