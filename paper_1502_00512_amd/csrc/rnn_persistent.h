@@ -189,32 +189,24 @@ __device__ inline f32x4_t load4<bf16_t>(const bf16_t *p) {
 // the fragments from LDS.  The block layout and its XOR swizzle are those of the 64-deep K-contiguous tile of
 // the contraction kernels (physical 16-byte chunk = logical ^ ((row >> 1) & 7)).  A wave reads only what it
 // copied itself, so the copy is ordered by that wave's own s_waitcnt; the buffer is reused every step.
-// STAGED = 1: all of a wave's blocks are resident at once (4 waves, 16 KB each).  STAGED = 2 (8 waves, two
-// workgroups per compute unit, so 64 KB each): a wave owns two 4 KB buffers and streams its blocks through
-// them (block b+2 is requested as soon as the fragments of block b are in registers), and the partial-sum
-// exchange buffer of the step's end lives in the same memory: a wave writes its partial tile over its own
-// first buffer, whose fragments it has consumed, and the next step's copies start only after the step
-// barrier, which every wave reaches after its reads of the exchange buffer.
+// All of a wave's blocks are resident at once (4 waves, up to 16 KB each); 1024 < Hp <= 2048 takes the wide
+// kernel further down.
 //
 // KS = 16-wide contraction steps per wave = Hp / (16 NWAVE).  BACKWARD = false: h_t = sigmoid(X_t + h_{t-1} U^T)
 // for t = 0..T-1.  BACKWARD = true: dA_t = (dHs_t + dA_{t+1} U) * h_t * (1 - h_t) for t = T-1..0.
 // XCD = true: XCD-local mode (see above); false: the grid spans the chip and uses agent-scope accesses.
 // (8 waves: two workgroups share a compute unit when Hp = 2048, so a wave may use at most 128 registers.)
-template <typename T, int KS, int NWAVE, bool BACKWARD, bool XCD, int STAGED = 0>
+template <typename T, int KS, int NWAVE, bool BACKWARD, bool XCD, bool STAGED = false>
 __global__ void __launch_bounds__(64 * NWAVE, NWAVE == 8 ? 4 : 1) rnn_persistent_kernel(const RnnPersistArgs a) {
-  static_assert(!STAGED || (XCD && sizeof(T) == 2 && KS % 4 == 0), "staged state loads: bf16, XCD-local, whole blocks");
+  static_assert(!STAGED || (XCD && sizeof(T) == 2 && KS % 4 == 0 && NWAVE == 4),
+                "staged state loads: bf16, XCD-local, 4 waves, whole blocks");
   constexpr int NBLK = KS / 4;  // [32][64] blocks of this wave's share of the state (STAGED)
-  constexpr int WAVE_STAGE = STAGED == 1 ? NBLK * 4096 : 2 * 4096;  // bytes of staging per wave
-  static_assert(STAGED != 2 || NBLK >= 2, "streaming needs at least two blocks");
-  __shared__ __attribute__((aligned(16))) float red_own[STAGED == 2 ? 1 : NWAVE][16][64];
+  constexpr int WAVE_STAGE = NBLK * 4096;  // bytes of staging per wave
+  __shared__ __attribute__((aligned(16))) float red_own[NWAVE][16][64];
   __shared__ __attribute__((aligned(1024))) char stage[STAGED ? NWAVE * WAVE_STAGE : 16];
   __shared__ int s_ticket;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // partial 32x32 tile of wave q (4 KB): its own array, or (STAGED = 2) the start of wave q's staging memory
-  auto red_at = [&](int q) -> float * {
-    if constexpr (STAGED == 2) return reinterpret_cast<float *>(stage + q * WAVE_STAGE);
-    else return &red_own[q][0][0];
-  };
+  auto red_at = [&](int q) -> float * { return &red_own[q][0][0]; };  // partial 32x32 tile of wave q
   const int nsb = a.Bp / 32;
   int sb, ub;
   unsigned nwg;
@@ -311,30 +303,12 @@ __global__ void __launch_bounds__(64 * NWAVE, NWAVE == 8 ? 4 : 1) rnn_persistent
                          : "memory", "m0");
           }
         };
-        if constexpr (STAGED == 1) {
 #pragma unroll
-          for (int b = 0; b < NBLK; ++b) copy_block(b, sw + b * 4096);
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies have landed in LDS
+        for (int b = 0; b < NBLK; ++b) copy_block(b, sw + b * 4096);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies have landed in LDS
 #pragma unroll
-          for (int kk = 0; kk < KS; ++kk)
-            f[kk] = *reinterpret_cast<const bf16x8_t *>(sw + (kk >> 2) * 4096 + frag_off[kk & 3]);
-        } else {
-          copy_block(0, sw);
-          copy_block(1, sw + 4096);
-#pragma unroll
-          for (int b = 0; b < NBLK; ++b) {
-            // block b has landed when at most the 4 loads of block b+1 are outstanding (loads return in order)
-            if (b + 1 < NBLK) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            const char *buf = sw + (b & 1) * 4096;
-#pragma unroll
-            for (int st = 0; st < 4; ++st) f[b * 4 + st] = *reinterpret_cast<const bf16x8_t *>(buf + frag_off[st]);
-            if (b + 2 < NBLK) {
-              asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the fragments are in registers: the buffer is free
-              copy_block(b + 2, sw + (b & 1) * 4096);
-            }
-          }
-        }
+        for (int kk = 0; kk < KS; ++kk)
+          f[kk] = *reinterpret_cast<const bf16x8_t *>(sw + (kk >> 2) * 4096 + frag_off[kk & 3]);
       } else
 #endif
       {
@@ -387,6 +361,161 @@ __global__ void __launch_bounds__(64 * NWAVE, NWAVE == 8 ? 4 : 1) rnn_persistent
       else grid_barrier(counter, (unsigned)(step + 1) * nwg, a.spin_limit, a.flags);
     }
   }
+}
+
+// Wide variant for 1024 < Hp <= 2048 (bf16, XCD-local mode, KS a multiple of 4): a workgroup of 8 waves owns
+// 32 streams x 64 hidden units (two 32-unit tiles), so a group is Hp/64 workgroups, ONE per compute unit of
+// its XCD: the previous state is copied into LDS once per compute unit and step (128 KB at Hp = 2048, all of
+// a wave's blocks resident), each fragment read from LDS feeds two MFMAs, and the weights of both tiles stay
+// in registers (128 per wave).  The partial-sum exchange buffer lives in the staging memory: a wave writes
+// its two partial tiles over the start of its own region once its fragments are consumed, and the next
+// step's copies start only after the step barrier, which every wave reaches after its reads of the exchange
+// buffer.  Same arithmetic order per output as the 32-unit kernels (waves' partials added 0..7).
+template <int KS, bool BACKWARD>
+__global__ void __launch_bounds__(512, 2) rnn_persistent_wide_kernel(const RnnPersistArgs a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  typedef bf16_t T;
+  constexpr int NWAVE = 8, UT = 2;
+  static_assert(KS % 4 == 0 && KS >= 8, "whole [32][64] blocks, at least 8 KB of staging per wave");
+  constexpr int NBLK = KS / 4;
+  constexpr int WAVE_STAGE = NBLK * 4096;
+  __shared__ __attribute__((aligned(1024))) char stage[NWAVE * WAVE_STAGE];
+  __shared__ int s_ticket;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nsb = a.Bp / 32;
+  const int x = xcc_id();
+  if (x >= nsb) return;  // no group lives on this XCD
+  if (threadIdx.x == 0)
+    s_ticket = (int)__hip_atomic_fetch_add(a.counter + 9 + x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  const int sb = x, ub = s_ticket;
+  const unsigned nwg = (unsigned)(a.Hp / 64);
+  if (ub >= (int)nwg) return;  // surplus workgroup
+  unsigned *counter = a.counter + 1 + x;
+  const int Hp = a.Hp, Bp = a.Bp;
+  const long slot = (long)Bp * Hp;
+  const int kq = wave * (KS * 16);
+  const int lr = lane & 31, lk = (lane >> 5) * 8;
+
+  bf16x8_t w[UT][KS];
+#pragma unroll
+  for (int u = 0; u < UT; ++u) {
+    const T *Wp = static_cast<const T *>(a.W) + (long)(ub * 64 + u * 32 + lr) * Hp + kq + lk;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) w[u][kk] = load_frag_global<T, false>(Wp + kk * 16);
+  }
+  typedef int i32x4_t __attribute__((ext_vector_type(4)));
+  i32x4_t rsrc;
+  int goff[4], frag_off[4];
+  {
+    const unsigned long long base = reinterpret_cast<unsigned long long>(BACKWARD ? a.dAc : a.Hs);
+    rsrc[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)base);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((base >> 32) & 0xffffu));
+    rsrc[2] = __builtin_amdgcn_readfirstlane((int)((long)(a.T + 1) * slot * 2));
+    rsrc[3] = 0x00020000;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int r = i * 8 + (lane >> 3), pch = lane & 7;
+      goff[i] = (int)(((long)(sb * 32 + r) * Hp + kq) * 2 + ((pch ^ rowk_swz(r)) << 4));
+    }
+#pragma unroll
+    for (int st = 0; st < 4; ++st) frag_off[st] = lr * 128 + (((2 * st + (lane >> 5)) ^ rowk_swz(lr)) << 4);
+  }
+  // epilogue ownership: threads 0..255 the first unit tile, 256..511 the second; inside a tile as in the
+  // 32-unit kernels (accumulator element r = t/16 of lanes 4*(t%16) .. +3: one stream, 4 consecutive units)
+  const int eu = tid >> 8, t8 = tid & 255;
+  const int er = (t8 >> 4) & 15, el = (t8 & 15) * 4;
+  const int erow = sb * 32 + ((er >> 2) << 3) + ((el >> 5) << 2) + (er & 3);
+  const int ecol = ub * 64 + eu * 32 + (el & 31);
+  const bool row_ok = erow < a.B;
+  T *Hs = static_cast<T *>(a.Hs);
+  T *dAc = static_cast<T *>(a.dAc);
+  char *sw = stage + wave * WAVE_STAGE;
+
+  for (int step = 0; step < a.T; ++step) {
+    const int t = BACKWARD ? a.T - 1 - step : step;
+    const long eidx = (long)t * slot + (long)erow * Hp + ecol;
+    f32x4_t xin = {0.f, 0.f, 0.f, 0.f};
+    f32x4_t hcur = {0.f, 0.f, 0.f, 0.f};
+    if (row_ok) {
+      xin = *reinterpret_cast<const f32x4_t *>(a.X + eidx);
+      if (BACKWARD) hcur = load4<T>(Hs + slot + eidx);
+    }
+    f32x16_t acc[UT], acc2[UT];
+#pragma unroll
+    for (int u = 0; u < UT; ++u)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[u][r] = acc2[u][r] = 0.0f;
+    const bool contract = !(BACKWARD && step == 0);
+    if (contract) {
+      const int soff = (int)((long)(BACKWARD ? t + 1 : t) * slot * 2);
+#pragma unroll
+      for (int b = 0; b < NBLK; ++b)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const unsigned lds_addr = (unsigned)(unsigned long long)(lds_void_ptr)(sw + b * 4096 + i * 1024);
+          asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                       :
+                       : "s"(lds_addr), "v"(goff[i]), "s"(rsrc), "s"(soff + b * 128)
+                       : "memory", "m0");
+        }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies have landed in LDS
+#pragma unroll
+      for (int kk = 0; kk < KS; kk += 2) {
+        const bf16x8_t f0 = *reinterpret_cast<const bf16x8_t *>(sw + (kk >> 2) * 4096 + frag_off[kk & 3]);
+        const bf16x8_t f1 = *reinterpret_cast<const bf16x8_t *>(sw + ((kk + 1) >> 2) * 4096 + frag_off[(kk + 1) & 3]);
+#pragma unroll
+        for (int u = 0; u < UT; ++u) {
+          mma16(acc[u], f0, w[u][kk]);
+          mma16(acc2[u], f1, w[u][kk + 1]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < UT; ++u)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[u][r] += acc2[u][r];
+    }
+    // every fragment this wave read is consumed: its staging memory now carries its partial tiles
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int u = 0; u < UT; ++u) {
+      float *red = reinterpret_cast<float *>(sw + u * 4096);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[r * 64 + lane] = acc[u][r];
+    }
+    __syncthreads();
+    f32x4_t s = *reinterpret_cast<const f32x4_t *>(reinterpret_cast<const float *>(stage + eu * 4096) + er * 64 + el);
+#pragma unroll
+    for (int q = 1; q < NWAVE; ++q) {
+      const f32x4_t p = *reinterpret_cast<const f32x4_t *>(
+          reinterpret_cast<const float *>(stage + q * WAVE_STAGE + eu * 4096) + er * 64 + el);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[e] += p[e];
+    }
+    f32x4_t o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool ok = row_ok && (ecol + e) < a.H;
+      if (!BACKWARD) {
+        o[e] = ok ? sigmoidf_(s[e] + xin[e]) : 0.0f;
+      } else {
+        o[e] = ok ? (xin[e] + s[e]) * hcur[e] * (1.0f - hcur[e]) : 0.0f;
+      }
+    }
+    if (!BACKWARD) {
+      store4_plain(Hs + slot + eidx, o);
+      if (a.h_state && step == a.T - 1 && row_ok) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (ecol + e < a.H) a.h_state[(long)erow * a.H + ecol + e] = o[e];
+      }
+    } else {
+      *reinterpret_cast<f32x4_t *>(a.dA32 + eidx) = o;
+      store4_plain(dAc + eidx, o);
+    }
+    if (step + 1 < a.T) xcd_barrier(counter, (unsigned)(step + 1) * nwg, a.spin_limit, a.flags);
+  }
+#endif
 }
 
 // Records which XCD each workgroup of the launch runs on.

@@ -323,20 +323,25 @@ int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st
   // XCD-local mode: one group of Hp/32 workgroups per block of 32 streams, group x on XCD x
   const bool xcd = h->xcd_local && h->Bp / 32 <= NUM_XCD;
   const dim3 grid(xcd ? (unsigned)(NUM_XCD * (h->Hp / 32)) : (unsigned)((h->Bp / 32) * (h->Hp / 32)));
-  // bf16, XCD-local, whole [32][64] blocks per wave: the state goes through LDS (coalesced loads), provided
-  // the runtime confirms that a whole group of Hp/32 such workgroups fits the 32 compute units of an XCD
+  // bf16, XCD-local, whole [32][64] blocks per wave: the state goes through LDS (coalesced loads): 4 waves keep
+  // their blocks resident; 8 waves (1024 < Hp <= 2048) take the wide kernel, 64 units per workgroup and one
+  // workgroup per compute unit, provided the runtime confirms that it fits one
 #define RNNLM_LAUNCH_PERSIST(KS, NW)                                                                        \
   do {                                                                                                      \
-    if constexpr (sizeof(T) == 2 && KS % 4 == 0) {                                                          \
-      constexpr int SM = NW == 4 ? 1 : 2;                                                                   \
-      if (xcd && 32 * blocks_per_cu<rnn_persistent_kernel<T, KS, NW, BACKWARD, true, SM>>(64 * NW) >= h->Hp / 32)   \
-        hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true, SM>), grid, dim3(64 * NW), 0, st, a);  \
-      else if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true>), grid, dim3(64 * NW), 0, st, a); \
-      else hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, false>), grid, dim3(64 * NW), 0, st, a);  \
-    } else {                                                                                                \
-      if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true>), grid, dim3(64 * NW), 0, st, a); \
-      else hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, false>), grid, dim3(64 * NW), 0, st, a);    \
+    if constexpr (sizeof(T) == 2 && KS % 4 == 0 && NW == 8) {                                               \
+      if (xcd && blocks_per_cu<rnn_persistent_wide_kernel<KS, BACKWARD>>(512) >= 1) {                       \
+        hipLaunchKernelGGL((rnn_persistent_wide_kernel<KS, BACKWARD>), dim3(NUM_XCD * (h->Hp / 64)), dim3(512), 0, st, a); \
+        break;                                                                                              \
+      }                                                                                                     \
     }                                                                                                       \
+    if constexpr (sizeof(T) == 2 && KS % 4 == 0 && NW == 4) {                                               \
+      if (xcd && 32 * blocks_per_cu<rnn_persistent_kernel<T, KS, NW, BACKWARD, true, true>>(64 * NW) >= h->Hp / 32) { \
+        hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true, true>), grid, dim3(64 * NW), 0, st, a); \
+        break;                                                                                              \
+      }                                                                                                     \
+    }                                                                                                       \
+    if (xcd) hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, true>), grid, dim3(64 * NW), 0, st, a); \
+    else hipLaunchKernelGGL((rnn_persistent_kernel<T, KS, NW, BACKWARD, false>), grid, dim3(64 * NW), 0, st, a);    \
   } while (0)
   switch (h->Hp / 256) {
     case 1: RNNLM_LAUNCH_PERSIST(4, 4); break;
