@@ -129,6 +129,26 @@ hipError_t big_gemm(hipStream_t st, const void *A, long lda, const void *B, long
   }
 }
 
+// The mid-sized contractions (128x128 output tiles: noise-panel products, the layers of the compressed
+// architecture): bf16 operands take the direct global->LDS kernels (the ring when an operand is K-major), fp32
+// the register-staged one.
+template <typename T, int LA, int LB, class Epi>
+hipError_t mid_gemm(hipStream_t st, const void *A, long lda, const void *B, long ldb, long Mg, long Ng, long K,
+                    int splits, const Epi &epi, int band = 4) {
+  // the direct-load kernels address a K-major operand's k blocks with a 32-bit scalar offset
+  const bool fits = !((LA == KROW && K * lda * 2 >= (1L << 31)) || (LB == KROW && K * ldb * 2 >= (1L << 31)) ||
+                      lda * 2 * 128 >= (1L << 31) || ldb * 2 * 128 >= (1L << 31));
+  if constexpr (sizeof(T) == 2 && (LA == KROW || LB == KROW)) {
+    if (fits) return launch_gemm_dma4<128, 128, 2, 2, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
+    return launch_gemm<T, 128, 128, 2, 2, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
+  } else if constexpr (sizeof(T) == 2) {
+    if (fits) return launch_gemm_dma<128, 128, 2, 2, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
+    return launch_gemm<T, 128, 128, 2, 2, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
+  } else {
+    return launch_gemm<T, 128, 128, 2, 2, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
+  }
+}
+
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 bool cfg_ok(const rnnlm_config *c) {
@@ -434,7 +454,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     epi.part = X32;
     epi.ld = Hp;
     epi.split_stride = 0;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, ROWK>(st, at<T>(h, h->L.Xp_c), h->Pp, at<T>(h, h->L.A_c), h->Pp, Mp,
+    HIP_TRY((mid_gemm<T, ROWK, ROWK>(st, at<T>(h, h->L.Xp_c), h->Pp, at<T>(h, h->L.A_c), h->Pp, Mp,
                                                         Hp, h->Pp, 1, epi)));
   }
 
@@ -478,7 +498,7 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     epi.out32 = nullptr;
     epi.outc = at<T>(h, h->L.P_c);
     epi.ld = h->Pp;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, ROWK>(st, Hs_c + (long)Bp * Hp, Hp, at<T>(h, h->L.C_c), Hp, Mp,
+    HIP_TRY((mid_gemm<T, ROWK, ROWK>(st, Hs_c + (long)Bp * Hp, Hp, at<T>(h, h->L.C_c), Hp, Mp,
                                                         h->Pp, Hp, 1, epi)));
     feat = at<T>(h, h->L.P_c);
   }
@@ -567,7 +587,7 @@ int nce_forward(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
     epi.part = S;
     epi.ld = Kp;
     epi.split_stride = 0;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, ROWK>(st, Hs1, Hp, Wn, Hp, Mp, Kp, Hp, 1, epi)));
+    HIP_TRY((mid_gemm<T, ROWK, ROWK>(st, Hs1, Hp, Wn, Hp, Mp, Kp, Hp, 1, epi)));
   }
   StageTimer tm(h, RNNLM_STAGE_NCE_GRAD, st);
   hipLaunchKernelGGL(nce_grad_kernel<T>, dim3(Mp), dim3(256), 0, st, S, Kp, K, at<float>(h, h->L.noff),
@@ -592,7 +612,7 @@ int nce_backward_h(rnnlm_t *h, int Tn, const NceCall &n, hipStream_t st) {
   epi.part = dHs32;
   epi.ld = Hp;
   epi.split_stride = 0;
-  HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, KROW>(st, at<T>(h, h->L.dS_c), Kp, at<T>(h, h->L.Wn_c), Hp, Mp, Hp, Kp,
+  HIP_TRY((mid_gemm<T, ROWK, KROW>(st, at<T>(h, h->L.dS_c), Kp, at<T>(h, h->L.Wn_c), Hp, Mp, Hp, Kp,
                                                       1, epi)));
   hipLaunchKernelGGL(nce_target_dhs_kernel<T>, dim3(Mrows), dim3(256), 0, st, at<T>(h, h->L.Wo_c), Hp,
                      at<int32_t>(h, h->L.yp), at<float>(h, h->L.nct), dHs32);
@@ -621,7 +641,7 @@ int nce_update(rnnlm_t *h, int Tn, const NceCall &n, const UpdateTargets &u, hip
     epi.part = (S == 1) ? G : at<float>(h, h->L.part32);
     epi.ld = Hp;
     epi.split_stride = per;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, at<T>(h, h->L.dS_c), Kp, Hs1, Hp, Kp, Hp, Mp, (int)S, epi)));
+    HIP_TRY((mid_gemm<T, KROW, KROW>(st, at<T>(h, h->L.dS_c), Kp, Hs1, Hp, Kp, Hp, Mp, (int)S, epi)));
     if (S > 1) {
       hipLaunchKernelGGL(splitk_reduce_kernel, dim3(blocks_for(per / 4, 256)), dim3(256), 0, st,
                          at<float>(h, h->L.part32), per, per, (int)S, G);
@@ -717,7 +737,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     epi.part = dHs32;
     epi.ld = Hp;
     epi.split_stride = 0;
-    HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, KROW>(st, dP_c, h->Pp, at<T>(h, h->L.C_c), Hp, Mp, Hp, h->Pp, 1, epi)));
+    HIP_TRY((mid_gemm<T, ROWK, KROW>(st, dP_c, h->Pp, at<T>(h, h->L.C_c), Hp, Mp, Hp, h->Pp, 1, epi)));
   }
   }
 
@@ -833,7 +853,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
       epi.part = at<float>(h, h->L.dX32);
       epi.ld = h->Pp;
       epi.split_stride = 0;
-      HIP_TRY((launch_gemm<T, 128, 128, 2, 2, ROWK, KROW>(st, dA_c, Hp, at<T>(h, h->L.A_c), h->Pp, Mp, h->Pp, Hp, 1, epi)));
+      HIP_TRY((mid_gemm<T, ROWK, KROW>(st, dA_c, Hp, at<T>(h, h->L.A_c), h->Pp, Mp, h->Pp, Hp, 1, epi)));
     }
   }
   // E[w] -= lr * sum_{m: x[m] = w} dA[m]: on the side stream, behind the sort helpers already queued there,
