@@ -10,8 +10,12 @@ streams that are already resident in HBM.  Prints ONE JSON line:
                    contractions), timed live with HIP events on the kernel's stream
   cpu_baseline     the fp64 oracle timed on a bounded sample of the same workload on the host cores
 
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg3] [--stages]
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config all|cfg3|cfg4|cfg5] [--stages]
                        [--criterion softmax|nce|score] [--noise K] [--optimizer sgd|rmsprop] [--arch plain|compressed]
+
+--config all (the default, full softmax + SGD only): the headline line is cfg5, the largest single-GPU
+configuration; the same line carries the objects "cfg3" and "cfg4" with the same measurements of the two
+other configurations the metric's target names (each timed with the same --steps / --warmup).
 
 --criterion nce times the same window with the noise-contrastive output layer (the "next" row after the
 headline path): K shared noise words per window drawn from the smoothed unigram of the token array.
@@ -40,9 +44,10 @@ def log(*a):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="cfg3")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="all",
+                    help="all: headline cfg5 plus sub-objects cfg3 and cfg4; or one configuration of synth.CONFIGS")
     ap.add_argument("--stages", action="store_true", help="also time every stage (adds event overhead)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--criterion", choices=["softmax", "nce", "score"], default="softmax",
@@ -52,12 +57,12 @@ def main() -> int:
                     help="sgd: the fused plain SGD step (headline metric); rmsprop: the rmsprop-scaled step "
                          "(smoothing 0.9995, one statistic per word for E and Wo), full softmax only")
     ap.add_argument("--arch", choices=["plain", "compressed"], default="plain",
-                    help="compressed: the architecture of Sec. 5.3 (512-unit layers below and above the state, tied "
+                    help="compressed: the architecture of Sec. 5.4 (512-unit layers below and above the state, tied "
                          "word matrix) on its word-prediction shape (config wp10k), full softmax + SGD")
     ap.add_argument("--streams", type=int, default=0, help="override the number of parallel streams B (scoring)")
     ap.add_argument("--noise", type=int, default=1024, help="noise words per window for --criterion nce")
     ap.add_argument("--shortlist", type=int, default=0,
-                    help="--criterion score: score this many candidate words per position (Sec. 5.3 ranks a shortlist "
+                    help="--criterion score: score this many candidate words per position (Sec. 5.4 ranks a shortlist "
                          "of 100) instead of the one given next word")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run three 256 MiB device-to-device copies (counter calibration for profiler runs)")
@@ -67,18 +72,38 @@ def main() -> int:
               file=sys.stderr)
         return 2
 
-    import numpy as np
-    import torch
-    from paper_1502_00512_amd import binding, synth
-
     comp = args.arch == "compressed"
     if comp and (args.criterion == "nce" or args.optimizer != "sgd"):
         print("bench.py: --arch compressed runs with the full softmax and plain SGD, or --criterion score",
               file=sys.stderr)
         return 2
-    if comp and args.config == "cfg3":
-        args.config = "wp10k"
-    cfg = synth.CONFIGS[args.config]
+    if args.optimizer == "rmsprop" and args.criterion == "score":
+        print("bench.py: --criterion score has no optimiser", file=sys.stderr)
+        return 2
+    plain_headline = not comp and args.criterion == "softmax" and args.optimizer == "sgd"
+    if args.config == "all":
+        args.config = "cfg5" if plain_headline else ("wp10k" if comp else "cfg3")
+        others = ["cfg3", "cfg4"] if plain_headline else []
+    else:
+        others = []
+    res = run_config(args, args.config, headline=True)
+    for name in others:
+        sub = run_config(args, name, headline=False)
+        res[name] = {k: sub[k] for k in ("value", "unit", "ms_per_step", "whole_path_mfma_frac", "output_gemms_mfma_frac",
+                                         "gemm_ms", "roofline", "loss_first_last", "config")}
+    print(json.dumps(res), flush=True)
+    return 0
+
+
+def run_config(args, config_name, headline):
+    """Times args.steps training windows of one configuration (after args.warmup untimed ones) and returns
+    the result object; headline = False skips the CPU baseline and the peak measurement."""
+    import numpy as np
+    import torch
+    from paper_1502_00512_amd import binding, synth
+
+    comp = args.arch == "compressed"
+    cfg = synth.CONFIGS[config_name]
     V, H, B, T = cfg.V, cfg.H, (args.streams or cfg.B), cfg.T
     P = synth.COMPRESSED_P if comp else 0
     M = B * T
@@ -101,9 +126,6 @@ def main() -> int:
     nce = args.criterion == "nce"
     score = args.criterion == "score"
     rms = args.optimizer == "rmsprop"
-    if rms and score:
-        print("bench.py: --criterion score has no optimiser", file=sys.stderr)
-        return 2
     if comp:
         g = binding.Rnnlm(E, U, None, b, B, T, precision, A=A_, C_=C_)
     else:
@@ -197,7 +219,7 @@ def main() -> int:
         torch.cuda.synchronize()
 
     # what the box sustains (for context next to the published peaks)
-    measured = g.rnnlm_measure_peaks(stream)
+    measured = g.rnnlm_measure_peaks(stream) if headline else None
 
     words_per_s = args.steps * M / dt
     peak = PEAK_BF16_TFLOPS if cfg.precision == "bf16" else PEAK_FP32_TFLOPS
@@ -280,7 +302,9 @@ def main() -> int:
             metric = "training words/sec (fwd+BPTT+rmsprop-scaled SGD) at 1 MI355X"
 
     cpu = None
-    if comp and not score and not args.no_cpu_baseline:
+    if not headline:
+        pass
+    elif comp and not score and not args.no_cpu_baseline:
         cpu = cpu_baseline_compressed(cfg, E, A_, U, C_, b, tok)
     elif not args.no_cpu_baseline and not score and not rms:
         cpu = cpu_baseline(cfg, E, U, Wo, b, tok,
@@ -305,13 +329,15 @@ def main() -> int:
         "loss_first_last": [round(first_loss, 4), round(last_loss, 4)],
         "roofline": roofline,
         "cpu_baseline": cpu,
-        "measured_peaks": {k: round(v, 1) for k, v in measured.items()},
+        "measured_peaks": {k: round(v, 1) for k, v in measured.items()} if measured else None,
     }
     res.update(extra)
     if stage_ms is not None:
         res["stage_ms"] = stage_ms
-    print(json.dumps(res), flush=True)
-    return 0
+    g.close()
+    del g, dtok
+    torch.cuda.empty_cache()
+    return res
 
 
 def measured_traffic(workload, kernel):

@@ -1,8 +1,8 @@
 /*
  * rnnlm.h - C ABI of the MI355X (gfx950) Elman RNN language-model training step.
  *
- * The model is the "standard RNN architecture" without hidden bias units of Sec. 4.1 of
- * "Scaling Recurrent Neural Network Language Models":
+ * The model is the plain Elman recurrent network without hidden bias units that Sec. 4.1 of the paper
+ * on scaling recurrent neural network language models describes:
  *     h_t = sigmoid(E[w_t] + U h_{t-1}),   z_t = Wo h_t + b,
  *     log P(w | history) = z_t[w] - log sum_v exp(z_t[v])   (explicitly normalised, Sec. 4.2)
  * trained on B = "noffset" token streams read from B points of one corpus, each with its
@@ -71,7 +71,7 @@ typedef struct {
                         not used (no workspace is set aside for them), >= 0, at most 65536 */
   int32_t rmsprop;   /* 1: rnnlm_train_chunk_rmsprop may be called (adds gradient buffers of the size of Wo, U
                         and b to the workspace); 0: it may not */
-  int32_t P;         /* 0: the plain architecture above.  > 0: the compressed architecture of Sec. 5.3 with
+  int32_t P;         /* 0: the plain architecture above.  > 0: the compressed architecture of Sec. 5.4 with
                         layers of P units below and above the state and tied word matrices (see "Compressed
                         architecture" below); requires K_max = 0 and rmsprop = 0 */
 } rnnlm_config;
@@ -187,7 +187,7 @@ int rnnlm_nce_grad_chunk(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t
 int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float lnZ, float *score,
                         void *stream);
 
-/* rnnlm_forward_score for a shortlist of C candidate next words per position (Sec. 5.3 predicts the next
+/* rnnlm_forward_score for a shortlist of C candidate next words per position (Sec. 5.4 predicts the next
  * word from a shortlist of candidates supplied by a pruned n-gram and ranks them by the network's output):
  * score[t][s][c] = Wo[cand[t][s][c]].h_t + b[cand[t][s][c]] - lnZ (compressed architecture: the tied matrix
  * applied to the layer above the state), unnormalised, no pass over the vocabulary.  Starts from h_state and
@@ -196,8 +196,8 @@ int rnnlm_forward_score(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t 
 int rnnlm_forward_score_shortlist(rnnlm_t *h, const int32_t *x, const int32_t *cand, int32_t C, int32_t T, float lnZ,
                                   float *score, void *stream);
 
-/* ---- Compressed architecture (Sec. 5.3: word prediction under a memory limit) ---------------------------
- * Sec. 5.3 shrinks the network by inserting layers of 512 units below and above the hidden state, tying the
+/* ---- Compressed architecture (Sec. 5.4: word prediction under a memory limit) ---------------------------
+ * Sec. 5.4 shrinks the network by inserting layers of 512 units below and above the hidden state, tying the
  * input-side and output-side word matrices as each other's transpose, and quantising all weights, trained
  * end to end.  It gives no formulas; the readings taken (cfg.P > 0 selects this model):
  *     x_t = E[w_t] (P values),  h_t = sigmoid(A x_t + U h_{t-1}),  p_t = C h_t,  z_t = E p_t + b
@@ -215,7 +215,7 @@ int rnnlm_forward_score_shortlist(rnnlm_t *h, const int32_t *x, const int32_t *c
 int rnnlm_grad_chunk_compressed(rnnlm_t *h, const int32_t *x, const int32_t *y, int32_t T, float *dE, float *dA,
                                 float *dU, float *dC, float *db, float *logp, void *stream);
 
-/* 8-bit weights of the compressed architecture (Sec. 5.3 quantises all the weights; the scheme is a
+/* 8-bit weights of the compressed architecture (Sec. 5.4 quantises all the weights; the scheme is a
  * reading): symmetric, linear, one scale per matrix row, scale = max|row| / 127 (1 for an all-zero row),
  * code = round-half-to-even(w / scale) in [-127, 127], both computed in fp32.  Caller-owned device
  * arrays: codes int8 [rows][cols] of the matrix, scales float [rows]. */
@@ -262,6 +262,16 @@ int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, 
  * raises the flag that rnnlm_check reports as RNNLM_ERR_TIMEOUT and lets the kernel run to its end
  * (default 2^18, about a second).  For tests of that error path: polls = 1 makes waits expire at once. */
 int rnnlm_set_barrier_spin_limit(rnnlm_t *h, uint32_t polls);
+
+/* How the workgroups of a persistent recurrent kernel hand the state h_t (backward: the gradient dA_t) to one
+ * another between the steps of a window (Sec. 4.2: the state-to-state work of all streams is done together).
+ * AUTO (default): the XCD-local exchange when the placement probe at init allows it and there are at most 8
+ * blocks of 32 streams, else the chip-wide one.  CHIP_WIDE: always agent-scope accesses and one counter for the
+ * whole grid.  XCD_LOCAL: like AUTO, but RNNLM_ERR_ARG when the XCD-local exchange is not available for this
+ * handle.  Both exchanges compute the same values in the same order: results are bitwise equal (tested).  Has
+ * no effect on shapes that run one launch per step. */
+typedef enum { RNNLM_EXCHANGE_AUTO = 0, RNNLM_EXCHANGE_CHIP_WIDE = 1, RNNLM_EXCHANGE_XCD_LOCAL = 2 } rnnlm_exchange;
+int rnnlm_set_recurrent_exchange(rnnlm_t *h, int32_t mode);
 
 /* Measures what this machine sustains, for reports next to the published peaks (HOST outputs): a register-
  * resident bf16 MFMA loop with hash-random operands and with constant operands (TFLOP/s; the two differ

@@ -1,9 +1,9 @@
-"""fp64 numpy oracle of the compressed architecture of Sec. 5.3 (word prediction under a memory limit).
+"""fp64 numpy oracle of the compressed architecture of Sec. 5.4 (word prediction under a memory limit).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the cpu_baseline leg of the
 benchmark.  It shares nothing with the HIP path.
 
-Sec. 5.3 compresses the recurrent network by (1) inserting layers of 512 units below and above the hidden
+Sec. 5.4 compresses the recurrent network by (1) inserting layers of 512 units below and above the hidden
 state, (2) tying the input-side and output-side word matrices as each other's transpose, (3) quantising
 all weights, and trains the result end to end.  The section gives no formulas; the readings taken here
 (stated again where the HIP path documents them):
@@ -87,7 +87,7 @@ def forward_logprob(m: CompressedModel, x: np.ndarray, y: np.ndarray) -> np.ndar
 
 
 def forward_score_shortlist(m: CompressedModel, x: np.ndarray, cand: np.ndarray, lnZ: float = 0.0) -> np.ndarray:
-    """Unnormalised scores E[c].p_t + b[c] - lnZ of the candidate words cand[T][B][C] (Sec. 5.3 ranks a
+    """Unnormalised scores E[c].p_t + b[c] - lnZ of the candidate words cand[T][B][C] (Sec. 5.4 ranks a
     shortlist of candidates); advances m.h.  forward_score(m, x, y) is the case of one candidate."""
     T, B = x.shape
     if cand.shape[:2] != (T, B) or cand.min() < 0 or cand.max() >= m.E.shape[0]:

@@ -256,7 +256,7 @@ def forward_score(m: Model, x, y, lnZ=0.0):
 
 
 def forward_score_shortlist(m: Model, x, cand, lnZ=0.0):
-    """Unnormalised scores of a shortlist of candidate next words, score[T][B][C] for cand[T][B][C] (Sec. 5.3
+    """Unnormalised scores of a shortlist of candidate next words, score[T][B][C] for cand[T][B][C] (Sec. 5.4
     ranks the candidates a pruned n-gram proposes); one forward_score pass per candidate column from the same
     starting state; advances m.h."""
     T, B, Cn = cand.shape

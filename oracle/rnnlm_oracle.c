@@ -6,9 +6,9 @@
  * table or helper with the HIP library, and neither includes the other.
  *
  * What it computes (plain definitions, loops only, no blocking or fusion):
- *   - the "standard RNN architecture" without hidden bias units of Sec. 4.1:
+ *   - the plain Elman recurrent network without hidden bias units of Sec. 4.1:
  *       a_t = E[w_t] + U h_{t-1},  h_t = 1/(1+exp(-a_t)),
- *     a distribution "over all words in a given vocabulary" from h_t (Sec. 4.1),
+ *     whose output is a probability for every word of the vocabulary given h_t (Sec. 4.1),
  *     explicitly normalised as Sec. 4.2 does when reporting perplexity:
  *       z = Wo h_t + b,  log P(w | history) = z_w - log sum_v exp(z_v);
  *   - noffset = B token streams read from B different points of one corpus, each

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(HERE, "librnnlm_hip.so")
 
 RNNLM_FP32 = 0
 RNNLM_BF16_FP32MASTER = 1
+RNNLM_EXCHANGE_AUTO, RNNLM_EXCHANGE_CHIP_WIDE, RNNLM_EXCHANGE_XCD_LOCAL = 0, 1, 2
 
 SYMBOLS = [
     "rnnlm_workspace_bytes", "rnnlm_init", "rnnlm_free", "rnnlm_stream_chunk", "rnnlm_forward_logprob",
@@ -24,6 +25,7 @@ SYMBOLS = [
     "rnnlm_nce_train_chunk", "rnnlm_nce_grad_chunk", "rnnlm_forward_score",
     "rnnlm_train_chunk_rmsprop", "rnnlm_nce_train_chunk_rmsprop",
     "rnnlm_grad_chunk_compressed", "rnnlm_quantize_weights", "rnnlm_forward_score_shortlist",
+    "rnnlm_set_recurrent_exchange",
 ]
 
 STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce",
@@ -84,6 +86,7 @@ def load():
     lib.rnnlm_check.argtypes = [vp, vp]
     lib.rnnlm_sort_segments.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     lib.rnnlm_set_barrier_spin_limit.argtypes = [vp, C.c_uint32]
+    lib.rnnlm_set_recurrent_exchange.argtypes = [vp, i32]
     lib.rnnlm_measure_peaks.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     f32 = C.c_float
     lib.rnnlm_nce_train_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, f32, vp, vp, vp]
@@ -133,7 +136,7 @@ def rnnlm_workspace_bytes(V, H, B, T_max, precision, device=0, K_max=0, rmsprop=
 class Rnnlm:
     """Owns the torch tensors (masters, state, workspace) and the library handle.
 
-    Plain architecture: E[V][H], U, Wo[V][H], b.  Compressed architecture (Sec. 5.3): pass Wo=None and
+    Plain architecture: E[V][H], U, Wo[V][H], b.  Compressed architecture (Sec. 5.4): pass Wo=None and
     A[H][P], C[P][H]; then E is the tied word matrix [V][P]."""
 
     def __init__(self, E, U, Wo, b, B: int, T_max: int, precision: int, device: int = 0, K_max: int = 0,
@@ -312,6 +315,9 @@ class Rnnlm:
 
     def rnnlm_set_barrier_spin_limit(self, polls: int):
         _ok(self.lib.rnnlm_set_barrier_spin_limit(self.handle, polls), "rnnlm_set_barrier_spin_limit")
+
+    def rnnlm_set_recurrent_exchange(self, mode: int):
+        _ok(self.lib.rnnlm_set_recurrent_exchange(self.handle, mode), "rnnlm_set_recurrent_exchange")
 
     def rnnlm_measure_peaks(self, stream=None):
         r, c, g = C.c_double(0), C.c_double(0), C.c_double(0)

@@ -500,7 +500,7 @@ __global__ void to_compute_kernel(const float *__restrict__ src, long n, T *__re
   for (; i < n; i += stride) dst[i] = from_f32<T>(src[i]);
 }
 
-// 8-bit row-wise quantisation (Sec. 5.3 quantises all the weights; the scheme is a reading): one workgroup
+// 8-bit row-wise quantisation (Sec. 5.4 quantises all the weights; the scheme is a reading): one workgroup
 // per row r of W[R][C]: scale = max|row| / 127 (1 for an all-zero row), code = round-half-to-even(w / scale)
 // clipped to [-127, 127], all in fp32 with correctly rounded division; the compute copy Wc[r][ldc] receives
 // code * scale.  max is order-independent, so the result does not depend on the reduction tree.

@@ -91,7 +91,7 @@ __global__ void __launch_bounds__(256) nce_target_score_kernel(const T *__restri
   }
 }
 
-// Scores of a shortlist of C candidate words per position (Sec. 5.3 ranks a shortlist of candidates):
+// Scores of a shortlist of C candidate words per position (Sec. 5.4 ranks a shortlist of candidates):
 // out[(t*B + s)*C + c] = Wc[cand].F[row] + b[cand] - shift, F = what the output layer reads (ld = width
 // Dp).  One wave per (position, candidate); ids outside [0, V) are clamped and raise flags[0].
 template <typename T>

@@ -34,9 +34,9 @@ struct RnnPersistArgs {
 // Coherence between workgroups on different XCDs (each XCD has its own L2): everything one step writes
 // and the next step reads (the state h, the gradient dA) moves with agent-scope relaxed atomic
 // accesses of 64 bits, which carry the agent-scope cache policy on the access itself.  That avoids
-// bulk L2 write-back / invalidate operations at every barrier; ordering comes from waiting for the
-// stores (workgroup-scope fence) before the barrier's arrival atomic, and from the poll loop's
-// control dependency before the loads.
+// bulk L2 write-back / invalidate operations at every barrier; ordering comes from every wave waiting
+// for the acknowledgement of its own stores (s_waitcnt vmcnt(0)) before the workgroup barrier that
+// precedes the arrival atomic, and from the poll loop's control dependency before the loads.
 // XCD-local mode.  The workgroups that exchange state with one another are exactly those of one block
 // of 32 streams.  When such a group runs on ONE accelerator die (XCD) they share its L2, and the step
 // barrier and the state exchange need nothing beyond that L2: plain stores (the vector L1 is
@@ -48,9 +48,17 @@ struct RnnPersistArgs {
 // after a probe launch has shown that an 8*n grid lands n workgroups on each XCD.
 __device__ inline int xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | 20) & 15; }  // HW_REG_XCC_ID[3:0]
 
+// Release half of a step barrier, executed by every wave: a workgroup-scope release fence only drains the
+// LDS/scalar counter on this target, so the wave also waits until each of its vector-memory stores has been
+// acknowledged (vmcnt counts stores as well as loads here); only then may the workgroup signal its arrival.
+__device__ inline void wait_own_stores() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+}
+
 __device__ inline void xcd_barrier(unsigned *counter, unsigned target, unsigned spin_limit, int32_t *flags) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have reached the L2
-  __syncthreads();
+  wait_own_stores();  // this wave's state stores are in the XCD's L2
+  __syncthreads();    // ... and so are those of every other wave of the workgroup
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned spins = 0;
@@ -68,7 +76,7 @@ __device__ inline void xcd_barrier(unsigned *counter, unsigned target, unsigned 
 }
 
 __device__ inline void grid_barrier(unsigned *counter, unsigned target, unsigned spin_limit, int32_t *flags) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // this wave's stores have completed
+  wait_own_stores();  // this wave's agent-scope state stores have been acknowledged
   __syncthreads();
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

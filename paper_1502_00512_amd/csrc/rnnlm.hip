@@ -59,6 +59,7 @@ struct rnnlm {
   hipStream_t side = nullptr;
   hipEvent_t ev_fork[2] = {nullptr, nullptr}, ev_join[2] = {nullptr, nullptr};
   bool xcd_local = false;        // the probe at init saw round-robin placement over 8 XCDs
+  int exchange_mode = RNNLM_EXCHANGE_AUTO;  // how the persistent recurrent kernels exchange state between workgroups
   unsigned spin_limit = 1u << 18;  // polls of a grid barrier before giving up (about a second)
   uint32_t prof_mask = 0;
   std::vector<EventPair> prof_pool;
@@ -341,7 +342,7 @@ int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st
   // the 17 counters are zero here: cleared by the token-preparation kernel (forward) and by the
   // log-probability sum (backward), which always run before this launch on the same stream
   // XCD-local mode: one group of Hp/32 workgroups per block of 32 streams, group x on XCD x
-  const bool xcd = h->xcd_local && h->Bp / 32 <= NUM_XCD;
+  const bool xcd = h->xcd_local && h->exchange_mode != RNNLM_EXCHANGE_CHIP_WIDE && h->Bp / 32 <= NUM_XCD;
   const dim3 grid(xcd ? (unsigned)(NUM_XCD * (h->Hp / 32)) : (unsigned)((h->Bp / 32) * (h->Hp / 32)));
   // bf16, XCD-local, whole [32][64] blocks per wave: the state goes through LDS (coalesced loads): 4 waves keep
   // their blocks resident; 8 waves (1024 < Hp <= 2048) take the wide kernel, 64 units per workgroup and one
@@ -1052,8 +1053,11 @@ int rnnlm_init(const rnnlm_config *cfg, const rnnlm_buffers *buf, rnnlm_t **out)
         hipMemsetAsync(dev, 0, sizeof(host), nullptr) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
       rc = RNNLM_ERR_HIP;
     } else {
-      bool rr = true;
-      for (int i = 0; i < N; ++i) rr = rr && host[i] == i % NUM_XCD;
+      // round-robin from whatever XCD the dispatcher had reached: block i on XCD (first + i) mod 8.  The start
+      // rotates from launch to launch (it continues where the previous grid ended); what the XCD-local kernels
+      // need is only that a grid of 8 n workgroups puts exactly n on every XCD, which any rotation gives.
+      bool rr = host[0] >= 0 && host[0] < NUM_XCD;
+      for (int i = 0; i < N; ++i) rr = rr && host[i] == (host[0] + i) % NUM_XCD;
       h->xcd_local = rr;
     }
   }
@@ -1401,6 +1405,16 @@ int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, 
 int rnnlm_set_barrier_spin_limit(rnnlm_t *h, uint32_t polls) {
   if (!h || polls == 0) return RNNLM_ERR_ARG;
   h->spin_limit = polls;
+  return RNNLM_OK;
+}
+
+int rnnlm_set_recurrent_exchange(rnnlm_t *h, int32_t mode) {
+  if (!h) return RNNLM_ERR_ARG;
+  if (mode != RNNLM_EXCHANGE_AUTO && mode != RNNLM_EXCHANGE_CHIP_WIDE && mode != RNNLM_EXCHANGE_XCD_LOCAL)
+    return RNNLM_ERR_ARG;
+  // the XCD-local exchange needs the placement the probe at init looks for and at most one block of 32 streams per XCD
+  if (mode == RNNLM_EXCHANGE_XCD_LOCAL && !(h->xcd_local && h->Bp / 32 <= NUM_XCD)) return RNNLM_ERR_ARG;
+  h->exchange_mode = mode;
   return RNNLM_OK;
 }
 

@@ -14,6 +14,8 @@ with id 0 reserved for the sentence marker where the configuration names one.
 from __future__ import annotations
 
 import hashlib
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 
 import numpy as np
@@ -21,6 +23,20 @@ import numpy as np
 _GOLDEN = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
+
+
+def _chunked(n: int, fill, step: int = 1 << 22) -> None:
+    """fill(a, m) for every chunk [a, a+m) of range(n).  Element i is a pure function of (seed, i), so the
+    chunks are independent: large arrays are filled by a few threads (numpy releases the interpreter lock
+    inside its loops); the result does not depend on the number of threads."""
+    starts = range(0, n, step)
+    workers = min(16, os.cpu_count() or 1, len(starts))
+    if workers <= 1:
+        for a in starts:
+            fill(a, min(step, n - a))
+        return
+    with ThreadPoolExecutor(workers) as ex:
+        list(ex.map(lambda a: fill(a, min(step, n - a)), starts))
 
 
 def counter_u64(seed: int, start: int, count: int) -> np.ndarray:
@@ -85,10 +101,10 @@ def zipf_tokens(N: int, V: int, s: float, seed: int, sentence_lambda: float | No
         base = 1
     thr = zipf_thresholds(R, s)
     tok = np.empty(N, dtype=np.int32)
-    step = 1 << 22
-    for a in range(0, N, step):
-        n = min(step, N - a)
+
+    def fill(a, n):
         tok[a:a + n] = sample_from_thresholds(thr, counter_u64(seed, a, n)) + base
+    _chunked(N, fill)
     if markov_contexts > 0:
         K = markov_contexts
         rng_a = counter_u64(seed ^ 0xA5A5A5A5, 0, K)
@@ -122,10 +138,10 @@ def _uniform01(seed: int, start: int, count: int) -> np.ndarray:
 def uniform_weights(shape, lo: float, hi: float, seed: int) -> np.ndarray:
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.float32)
-    step = 1 << 22
-    for a in range(0, n, step):
-        m = min(step, n - a)
+
+    def fill(a, m):
         out[a:a + m] = (lo + (hi - lo) * _uniform01(seed, a, m)).astype(np.float32)
+    _chunked(n, fill)
     return out.reshape(shape)
 
 
@@ -133,12 +149,12 @@ def normal_weights(shape, std: float, seed: int) -> np.ndarray:
     """Box-Muller on pairs of counter words, fp64 then stored as fp32."""
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.float32)
-    step = 1 << 22
-    for a in range(0, n, step):
-        m = min(step, n - a)
+
+    def fill(a, m):
         u1 = _uniform01(seed, 2 * a, m)
         u2 = _uniform01(seed ^ 0x7777777, 2 * a, m)
         out[a:a + m] = (std * np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)).astype(np.float32)
+    _chunked(n, fill)
     return out.reshape(shape)
 
 
@@ -167,7 +183,7 @@ CONFIGS = {
     "cfg3": Config("cfg3", 64_000, 1024, 128, 20, 20_000_000, 1.05, 25.0, 0, "normal", 0.02, 0.05, "bf16", 0x5EED0003, 0x5EED1003),
     "cfg4": Config("cfg4", 100_000, 2048, 128, 20, 50_000_000, 1.0, None, 4096, "normal", 0.02, 0.02, "bf16", 0x5EED0004, 0x5EED1004),
     "cfg5": Config("cfg5", 100_000, 4096, 256, 32, 100_000_000, 1.0, 25.0, 0, "normal", 0.01, 0.01, "bf16", 0x5EED0005, 0x5EED1005),
-    # the word-prediction model of Sec. 5.3 (vocabulary 10K, nstate 1024; the 512-unit layers are COMPRESSED_P)
+    # the word-prediction model of Sec. 5.4 (vocabulary 10K, nstate 1024; the 512-unit layers are COMPRESSED_P)
     "wp10k": Config("wp10k", 10_000, 1024, 128, 20, 5_000_000, 1.05, 25.0, 0, "normal", 0.02, 0.05, "bf16", 0x5EED0006, 0x5EED1006),
 }
 COMPRESSED_P = 512

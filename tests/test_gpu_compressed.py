@@ -1,4 +1,4 @@
-"""GPU parity of the compressed architecture (Sec. 5.3: layers of P units below and above the state, tied
+"""GPU parity of the compressed architecture (Sec. 5.4: layers of P units below and above the state, tied
 word matrix, 8-bit weights), called through the C ABI, against the fp64 numpy oracle on the same seeded
 inputs.  Tolerances as for the plain architecture: fp32 log-probs |d| <= 1e-4*|ref| + 1e-6, gradients per
 tensor 1e-3 of the tensor's scale (max and l2); bf16: mean loss 1e-2, gradients 3e-2.  Quantiser codes are
@@ -182,7 +182,7 @@ def test_quantised_weights(precision):
 
 @pytest.mark.parametrize("precision", [FP32, BF16])
 def test_scoring_and_shortlist(precision):
-    """Unnormalised scores of given next words and of a shortlist of candidates per position (Sec. 5.3 ranks a
+    """Unnormalised scores of given next words and of a shortlist of candidates per position (Sec. 5.4 ranks a
     shortlist), chained over two calls."""
     V, H, P, B, T, Cn = 1500, 128, 64, 5, 6, 37
     g, o = make_pair(V, H, P, B, T, precision, seed=13, scale=0.3)
@@ -241,7 +241,7 @@ def test_argument_checks():
 
 @pytest.mark.parametrize("precision", [FP32, BF16])
 def test_full_size_word_prediction_shape(precision):
-    """The shape Sec. 5.3 names (vocabulary 10K, nstate 1024, 512-unit layers), in the launch configuration
+    """The shape Sec. 5.4 names (vocabulary 10K, nstate 1024, 512-unit layers), in the launch configuration
     bench.py --arch compressed times (128 streams x 20): every output of one window against the oracle."""
     cfg = synth.CONFIGS["wp10k"]
     V, H, P, B, T = cfg.V, cfg.H, synth.COMPRESSED_P, cfg.B, cfg.T

@@ -140,8 +140,8 @@ def test_train_chunks_fp32(V, H, B, T, K):
         g.rnnlm_train_chunk(x, y, lr, logp, s)
         xr, yr = O.stream_chunk(tok, B, T, k)
         ref, sref = O.train_chunk(o, xr, yr, lr)
-        check_logp(logp, ref, rel=2e-4)
-        assert abs(s.item() - sref) <= 2e-4 * abs(sref)
+        check_logp(logp, ref)
+        assert abs(s.item() - sref) <= 1e-4 * abs(sref)
     for name, a, c in (("E", g.E, o.E), ("U", g.U, o.U), ("Wo", g.Wo, o.Wo), ("b", g.b, o.b), ("h", g.h_state, o.h)):
         d = np.abs(a.cpu().numpy() - c).max()
         assert d <= 1e-4 * max(1.0, np.abs(c).max()), (name, d)
@@ -311,13 +311,10 @@ def test_measure_peaks_is_sane_and_leaves_the_model_alone():
 
 # ---- full-size checks, in the launch configuration bench.py times -------------------------------------
 
-def _cfg_pair(name, T=None, weights="config"):
+def _cfg_pair(name, T=None):
     cfg = synth.CONFIGS[name]
     T = cfg.T if T is None else T
-    if weights == "config":
-        E, U, Wo, b = synth.make_weights(cfg.V, cfg.H, cfg.init, cfg.init_scale, cfg.weight_seed)
-    else:  # cheaper generator for the largest shapes, same scale
-        E, U, Wo, b = synth.make_weights(cfg.V, cfg.H, "uniform", cfg.init_scale * 1.7, cfg.weight_seed)
+    E, U, Wo, b = synth.make_weights(cfg.V, cfg.H, cfg.init, cfg.init_scale, cfg.weight_seed)
     precision = BF16 if cfg.precision == "bf16" else FP32
     g = binding.Rnnlm(E, U, Wo, b, cfg.B, cfg.T, precision)
     return cfg, T, g, (E, U, Wo, b)
@@ -367,24 +364,56 @@ def test_cfg3_full_size_bf16_window():
     g.rnnlm_check()
 
 
-@pytest.mark.parametrize("name,streams", [("cfg4", (0, 77, 127)), ("cfg5", (0, 200, 255))])
-def test_large_configs_sampled_streams(name, streams):
-    """cfg4 / cfg5 at full shape: the oracle scores three whole streams of the first window one by one
-    (streams are independent in the forward pass); the GPU's log-probs for those streams must give the
-    same perplexity within 1e-2.  Properties that hold at any size: finite results, bias gradient sums to
-    zero, rows of the embedding gradient for ids not in the window are zero."""
-    cfg, T, g, (E, U, Wo, b) = _cfg_pair(name, weights="uniform")
-    tok = synth.make_tokens(cfg, 4_000_000)
+def test_cfg4_full_size_bf16_window():
+    """cfg4 (V=100,000 H=2048 B=128 T=20, bf16 operands, the configuration's own N(0, 0.02) weights and
+    structured token stream): one whole window, all 2560 positions, against the oracle: window perplexity
+    within 1e-2, every position's log-probability, every gradient tensor within 2e-2 of its scale, and the
+    SGD step itself."""
+    cfg, T, g, (E, U, Wo, b) = _cfg_pair("cfg4")
+    o = O.Model.from_weights(E, U, Wo, b, cfg.B)
+    tok = synth.make_tokens(cfg, 2_000_000)
     x, y = O.stream_chunk(tok, cfg.B, T, 0)
     r = g.rnnlm_grad_chunk(dev(x), dev(y))
+    ref = O.grad_chunk(o, x, y)
+    ppl_g = math.exp(-r["logp"].double().mean().item())
+    ppl_r = math.exp(-ref["logp"].mean())
+    assert abs(ppl_g / ppl_r - 1) < 1e-2, (ppl_g, ppl_r)
+    assert np.abs(r["logp"].cpu().numpy() - ref["logp"]).max() < 5e-2
+    for kk in ("gE", "gU", "gWo", "gb"):
+        check_grad(kk, r[kk], ref[kk], rel=2e-2)
+    assert abs(r["gb"].double().sum().item()) < 1e-4
+    Wo0, b0, U0 = g.Wo.clone(), g.b.clone(), g.U.clone()
+    g.rnnlm_train_chunk(dev(x), dev(y), cfg.lr)
+    assert torch.allclose(g.Wo, Wo0 - cfg.lr * r["gWo"], rtol=0, atol=1e-7)
+    assert torch.allclose(g.b, b0 - cfg.lr * r["gb"], rtol=0, atol=1e-7)
+    assert torch.allclose(g.U, U0 - cfg.lr * r["gU"], rtol=0, atol=1e-7)
+    assert np.abs(g.h_state.cpu().numpy() - ref["h_next"]).max() < 2e-2
+    g.rnnlm_check()
+
+
+@pytest.fixture(scope="module")
+def cfg5_weights():
+    cfg = synth.CONFIGS["cfg5"]
+    return synth.make_weights(cfg.V, cfg.H, cfg.init, cfg.init_scale, cfg.weight_seed)
+
+
+def test_cfg5_full_size_window_log_probabilities(cfg5_weights, capsys):
+    """cfg5 (V=100,000 H=4096 B=256 T=32, bf16 operands, the configuration's own N(0, 0.01) weights and token
+    stream) in the launch configuration bench.py times: every one of the window's 8192 log-probabilities against
+    the oracle (window perplexity within 1e-2).  Streams are independent within a window, so the oracle scores
+    them in four groups of 64 (one call each, with a progress line in between: a whole-window call is silent
+    for minutes).  The window's gradients are checked by properties that hold at any size here, and entry by
+    entry in the next test."""
+    cfg = synth.CONFIGS["cfg5"]
+    E, U, Wo, b = cfg5_weights
+    T, B = cfg.T, cfg.B
+    g = binding.Rnnlm(E, U, Wo, b, B, T, BF16)
+    tok = synth.make_tokens(cfg, 4_000_000)
+    x, y = O.stream_chunk(tok, B, T, 0)
+    r = g.rnnlm_grad_chunk(dev(x), dev(y))
+    g.rnnlm_check()
     got = r["logp"].cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all()
-    E64, U64, Wo64, b64 = (np.asarray(a, np.float64) for a in (E, U, Wo, b))
-    for s in streams:
-        o1 = O.Model(E64, U64, Wo64, b64, np.zeros((1, cfg.H)))
-        ref = O.forward_logprob(o1, np.ascontiguousarray(x[:, s:s + 1]), np.ascontiguousarray(y[:, s:s + 1]))[:, 0]
-        assert abs(math.exp(-got[:, s].mean()) / math.exp(-ref.mean()) - 1) < 1e-2
-        assert np.abs(got[:, s] - ref).max() < 5e-2
     assert abs(r["gb"].double().sum().item()) < 1e-4
     for kk in ("gE", "gU", "gWo", "gb"):
         assert torch.isfinite(r[kk]).all()
@@ -392,4 +421,182 @@ def test_large_configs_sampled_streams(name, streams):
     seen[dev(x).long().flatten()] = True
     assert not r["gE"][~seen].any()
     assert r["gE"][seen].abs().sum() > 0
+    assert r["gWo"].double().sum(dim=0).abs().max().item() < 1e-4   # each column of gWo sums to zero over the vocabulary
+    del r, g
+    torch.cuda.empty_cache()
+    E64, U64, Wo64, b64 = (np.asarray(a, np.float64) for a in (E, U, Wo, b))
+    ref = np.empty((T, B))
+    G = 64
+    for s0 in range(0, B, G):
+        og = O.Model(E64, U64, Wo64, b64, np.zeros((G, cfg.H)))
+        ref[:, s0:s0 + G] = O.forward_logprob(og, np.ascontiguousarray(x[:, s0:s0 + G]),
+                                              np.ascontiguousarray(y[:, s0:s0 + G]))
+        with capsys.disabled():
+            print(f"[cfg5 window] oracle scored streams {s0}..{s0 + G - 1}", flush=True)
+    assert abs(math.exp(-got.mean()) / math.exp(-ref.mean()) - 1) < 1e-2
+    assert np.abs(got - ref).max() < 5e-2
+
+
+def test_cfg5_full_size_gradients_replicated_streams(cfg5_weights):
+    """cfg5 at full shape (256 streams x 32 positions, the configuration's weights), every entry of all four
+    gradient tensors against the oracle.  The fp64 oracle needs minutes for 256 different streams of this
+    size, so the window carries 16 different streams of the configuration's token array, each 16 times
+    (stream s reads what stream s mod 16 reads).  Streams are independent within a window and the loss is
+    their mean, so log-probabilities repeat and the window's gradient equals that of the 16 distinct streams
+    alone (the oracle's stream-independence pin), which the oracle computes; the HIP path does the full
+    256-stream work: it cannot tell."""
+    cfg = synth.CONFIGS["cfg5"]
+    E, U, Wo, b = cfg5_weights
+    T, B, D = cfg.T, cfg.B, 16
+    g = binding.Rnnlm(E, U, Wo, b, B, T, BF16)
+    tok = synth.make_tokens(cfg, 4_000_000)
+    xd, yd = O.stream_chunk(tok, D, T, 0)
+    x = np.ascontiguousarray(np.tile(xd, (1, B // D)))
+    y = np.ascontiguousarray(np.tile(yd, (1, B // D)))
+    r = g.rnnlm_grad_chunk(dev(x), dev(y))
     g.rnnlm_check()
+    o = O.Model.from_weights(E, U, Wo, b, D)
+    ref = O.grad_chunk(o, xd, yd)
+    got = r["logp"].cpu().numpy().astype(np.float64)
+    want = np.tile(ref["logp"], (1, B // D))
+    assert abs(math.exp(-got.mean()) / math.exp(-want.mean()) - 1) < 1e-2
+    assert np.abs(got - want).max() < 5e-2
+    for kk in ("gU", "gb", "gE", "gWo"):
+        check_grad(kk, r[kk], ref[kk], rel=2e-2)
+
+
+def test_bf16_training_tracks_oracle_at_cfg3_model_size():
+    """The 50-window drift check at cfg3's model (V=64,000 H=1024, its N(0, 0.02) weights, its token
+    stream and learning rate) with a smaller window (32 streams x 10 positions instead of 128 x 20, which
+    keeps the oracle's 50 training windows under a minute): both sides train on their own from identical
+    weights; window perplexity agrees within 1e-2 at the first and at the last window."""
+    cfg = synth.CONFIGS["cfg3"]
+    B, T, K = 32, 10, 50
+    E, U, Wo, b = synth.make_weights(cfg.V, cfg.H, cfg.init, cfg.init_scale, cfg.weight_seed)
+    g = binding.Rnnlm(E, U, Wo, b, B, T, BF16)
+    o = O.Model.from_weights(E, U, Wo, b, B)
+    tok = synth.make_tokens(cfg, 1_000_000)
+    dtok = dev(tok)
+    logp = torch.empty(T, B, device="cuda")
+    ratios = []
+    for k in range(K):
+        x, y = g.rnnlm_stream_chunk(dtok, k, T)
+        g.rnnlm_train_chunk(x, y, cfg.lr, logp)
+        ref, _ = O.train_chunk(o, *O.stream_chunk(tok, B, T, k), cfg.lr)
+        ratios.append(math.exp(-logp.double().mean().item()) / math.exp(-ref.mean()))
+    assert abs(ratios[0] - 1) < 1e-2 and abs(ratios[-1] - 1) < 1e-2, (ratios[0], ratios[-1])
+    assert max(abs(r - 1) for r in ratios) < 2e-2
+    g.rnnlm_check()
+
+
+# ---- the two state exchanges of the persistent recurrent kernels ---------------------------------------
+
+@pytest.mark.parametrize("precision,V,H,B,T,K", [
+    (BF16, 64000, 1024, 128, 20, 200),   # cfg3's shape: 4-wave kernels, state staged through LDS
+    (BF16, 2000, 2048, 128, 20, 60),     # cfg4's hidden size: the wide kernel, one workgroup per compute unit
+    (BF16, 1500, 1536, 70, 5, 40),       # ragged streams, 1024 < H < 2048
+    (FP32, 1000, 256, 64, 6, 60),        # fp32: operands straight from memory
+])
+def test_state_exchange_modes_agree_bitwise(precision, V, H, B, T, K):
+    """The XCD-local exchange (plain stores and loads through one XCD's L2) against the chip-wide one
+    (agent-scope accesses): two models train the same K windows side by side, one per mode; the carried
+    state and the recurrent matrix are compared after every window (first mismatch stops the test), all
+    parameters at the end.  Both modes add the same numbers in the same order, so any difference would be
+    a stale or torn read of exchanged state."""
+    init = ("normal", 0.02) if precision == BF16 else ("uniform", 0.1)
+    E, U, Wo, b = synth.make_weights(V, H, init[0], init[1], 77)
+    tok = synth.zipf_tokens(K * B * T + B + 1, V, 1.05, 78, 25.0)
+    models = []
+    for mode in (binding.RNNLM_EXCHANGE_XCD_LOCAL, binding.RNNLM_EXCHANGE_CHIP_WIDE):
+        m = binding.Rnnlm(E, U, Wo, b, B, T, precision)
+        try:
+            m.rnnlm_set_recurrent_exchange(mode)
+        except binding.RnnlmError:
+            pytest.skip("this device does not place workgroups round-robin over 8 XCDs: no XCD-local exchange")
+        models.append(m)
+    dtok = dev(tok)
+    lr = 0.05
+    for k in range(K):
+        x, y = models[0].rnnlm_stream_chunk(dtok, k, T)
+        for m in models:
+            m.rnnlm_train_chunk(x, y, lr)
+        assert torch.equal(models[0].h_state, models[1].h_state), f"state differs after window {k}"
+        assert torch.equal(models[0].U, models[1].U), f"U differs after window {k}"
+    for n in ("E", "Wo", "b"):
+        assert torch.equal(getattr(models[0], n), getattr(models[1], n)), n
+    for m in models:
+        m.rnnlm_check()
+    with pytest.raises(binding.RnnlmError):
+        models[0].rnnlm_set_recurrent_exchange(3)
+
+
+# ---- error reporting and checkpoint-style use ------------------------------------------------------------
+
+def test_nonfinite_sum_is_reported():
+    """A NaN in the recurrent matrix reaches every hidden state and so every log-probability:
+    rnnlm_perplexity returns RNNLM_ERR_NONFINITE, a training call raises the flag that the next rnnlm_check
+    reports, and the flag is cleared by that check."""
+    V, H, B, T = 600, 64, 4, 5
+    E, U, Wo, b = synth.make_weights(V, H, "uniform", 0.1, 5)
+    U[0, 0] = np.nan
+    g = binding.Rnnlm(E, U, Wo, b, B, T, FP32)
+    tok = tokens(V, 300, 3)
+    with pytest.raises(binding.RnnlmError) as e:
+        g.rnnlm_perplexity(dev(tok), T)
+    assert e.value.status == -3
+    g.rnnlm_check()
+    x, y = O.stream_chunk(tok, B, T, 0)
+    g.rnnlm_train_chunk(dev(x), dev(y), 0.0)
+    with pytest.raises(binding.RnnlmError) as e:
+        g.rnnlm_check()
+    assert e.value.status == -3
+    g.rnnlm_check()
+
+
+@pytest.mark.parametrize("precision", [FP32, BF16])
+def test_sync_compute_copies_after_overwriting_masters(precision):
+    """The caller overwrites the fp32 masters (as when loading a checkpoint) and calls
+    rnnlm_sync_compute_copies: the next window is scored with the new weights, bit for bit like a model
+    initialised with them."""
+    V, H, B, T = 1200, 200, 9, 6
+    g, _ = make_pair(V, H, B, T, precision, seed=61, scale=0.2)
+    E2, U2, Wo2, b2 = synth.make_weights(V, H, "uniform", 0.3, 62)
+    b2 = synth.uniform_weights((V,), -0.4, 0.4, 63)
+    fresh = binding.Rnnlm(E2, U2, Wo2, b2, B, T, precision)
+    tok = tokens(V, 500, 9)
+    x, y = O.stream_chunk(tok, B, T, 0)
+    g.rnnlm_forward_logprob(dev(x), dev(y))            # stale copies and a non-zero state first
+    for dst, src in ((g.E, E2), (g.U, U2), (g.Wo, Wo2), (g.b, b2)):
+        dst.copy_(torch.as_tensor(src))
+    g.rnnlm_sync_compute_copies()
+    g.rnnlm_reset_state()
+    a = g.rnnlm_forward_logprob(dev(x), dev(y))
+    c = fresh.rnnlm_forward_logprob(dev(x), dev(y))
+    assert torch.equal(a, c)
+    if precision == FP32:
+        o = O.Model.from_weights(E2, U2, Wo2, b2, B)
+        check_logp(a, O.forward_logprob(o, x, y))
+    g.rnnlm_check()
+
+
+@pytest.mark.parametrize("precision", [FP32, BF16])
+def test_save_and_reload_equals_continuous_training(precision):
+    """Training 3 + 3 windows without a break equals training 3 windows, saving masters and state to the
+    host, loading them into a new handle and training the other 3: bitwise (the compute copies a handle
+    builds from the masters are the ones the fused updates keep)."""
+    V, H, B, T = 1800, 256, 32, 6
+    E, U, Wo, b = synth.make_weights(V, H, "uniform", 0.1, 71)
+    tok = tokens(V, 7 * B * T + B + 1, 72)
+    dtok = dev(tok)
+    a = binding.Rnnlm(E, U, Wo, b, B, T, precision)
+    for k in range(3):
+        a.rnnlm_train_chunk(*a.rnnlm_stream_chunk(dtok, k, T), 0.1)
+    saved = [t.cpu().numpy().copy() for t in (a.E, a.U, a.Wo, a.b, a.h_state)]
+    for k in range(3, 6):
+        a.rnnlm_train_chunk(*a.rnnlm_stream_chunk(dtok, k, T), 0.1)
+    c = binding.Rnnlm(*saved[:4], B, T, precision)
+    c.h_state.copy_(torch.as_tensor(saved[4]))
+    for k in range(3, 6):
+        c.rnnlm_train_chunk(*c.rnnlm_stream_chunk(dtok, k, T), 0.1)
+    for n in ("E", "U", "Wo", "b", "h_state"):
+        assert torch.equal(getattr(a, n), getattr(c, n)), n

@@ -1,4 +1,4 @@
-"""Pins of the compressed-architecture oracle (Sec. 5.3: 512-unit layers below and above the state, tied
+"""Pins of the compressed-architecture oracle (Sec. 5.4: 512-unit layers below and above the state, tied
 word matrices, quantised weights) against things other than itself (CPU only): the already pinned plain
 oracle through the exact factorisation E' = E A^T, Wo' = E C, a hand-computed example, finite differences,
 library autograd on an independently written forward pass, and hand-picked rows for the quantiser."""
@@ -211,7 +211,7 @@ def test_quantiser_error_bound_range_and_stability():
 
 
 def test_quantised_model_of_the_papers_shape_fits_the_stated_size():
-    """Sec. 5.3: vocabulary 10K, nstate 1024, 512-unit layers, tied word matrices, at 10 MB.  One byte per
+    """Sec. 5.4: vocabulary 10K, nstate 1024, 512-unit layers, tied word matrices, at 10 MB.  One byte per
     weight plus one fp32 scale per row plus the fp32 bias."""
     V, H, P = 10_000, 1024, 512
     weights = V * P + H * P + H * H + P * H
