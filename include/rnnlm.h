@@ -258,6 +258,18 @@ int rnnlm_check(rnnlm_t *h, void *stream);
 int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, int32_t *seg_start, int32_t *nseg,
                         void *stream);
 
+/* rnnlm_sort_segments for callers that cannot allocate device memory and hold no handle with a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the
+ * padded id list they need in a static device array of the library instead of the caller's workspace.  The
+ * call allocates and frees nothing (no handle, no workspace; the static array, about 0.5 MB per GPU, exists
+ * from library load to process end) and runs on the CURRENT device, which must be the stream's.
+ * x: dev int32[T][B]; V: ids must lie in [0, V) (others are clamped, and *range_flag, dev int32 or NULL, is set
+ * to 1, else 0); perm: dev int32[B*T]; seg_start: dev int32[B*T+1]; nseg: dev int32.  Limit: T * round_up(B, 32),
+ * rounded up to a multiple of 256, must not exceed 65536 positions, else RNNLM_ERR_ARG.  All calls on one GPU
+ * share the one array: calls that overlap in time on the same GPU (different streams or threads) race. */
+int rnnlm_sort_segments_static(const int32_t *x, int32_t T, int32_t B, int32_t V, int32_t *perm, int32_t *seg_start,
+                               int32_t *nseg, int32_t *range_flag, void *stream);
+
 /* Number of polls a grid-wide barrier of the persistent recurrent kernels waits before it gives up,
  * raises the flag that rnnlm_check reports as RNNLM_ERR_TIMEOUT and lets the kernel run to its end
  * (default 2^18, about a second).  For tests of that error path: polls = 1 makes waits expire at once. */

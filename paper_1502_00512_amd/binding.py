@@ -25,7 +25,7 @@ SYMBOLS = [
     "rnnlm_nce_train_chunk", "rnnlm_nce_grad_chunk", "rnnlm_forward_score",
     "rnnlm_train_chunk_rmsprop", "rnnlm_nce_train_chunk_rmsprop",
     "rnnlm_grad_chunk_compressed", "rnnlm_quantize_weights", "rnnlm_forward_score_shortlist",
-    "rnnlm_set_recurrent_exchange",
+    "rnnlm_set_recurrent_exchange", "rnnlm_sort_segments_static",
 ]
 
 STAGES = ["prep", "rnn_fwd", "out_fwd", "stats", "softmax_grad", "out_bwd_h", "rnn_bwd", "out_bwd_w", "rec_w", "emb", "reduce",
@@ -87,6 +87,7 @@ def load():
     lib.rnnlm_sort_segments.argtypes = [vp, vp, i32, vp, vp, vp, vp]
     lib.rnnlm_set_barrier_spin_limit.argtypes = [vp, C.c_uint32]
     lib.rnnlm_set_recurrent_exchange.argtypes = [vp, i32]
+    lib.rnnlm_sort_segments_static.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.rnnlm_measure_peaks.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     f32 = C.c_float
     lib.rnnlm_nce_train_chunk.argtypes = [vp, vp, vp, i32, vp, i32, vp, f32, f32, vp, vp, vp]
@@ -131,6 +132,12 @@ def _stream(stream):
 def rnnlm_workspace_bytes(V, H, B, T_max, precision, device=0, K_max=0, rmsprop=0, P=0) -> int:
     cfg = rnnlm_config(V, H, B, T_max, precision, device, K_max, rmsprop, P)
     return int(load().rnnlm_workspace_bytes(C.byref(cfg)))
+
+
+def rnnlm_sort_segments_static(x, V: int, perm, seg_start, nseg, range_flag=None, stream=None):
+    """The handle-free call: x int32[T][B] and the three outputs are device tensors the caller allocated."""
+    _ok(load().rnnlm_sort_segments_static(_ptr(x), x.shape[0], x.shape[1], V, _ptr(perm), _ptr(seg_start), _ptr(nseg),
+                                          _ptr(range_flag), _stream(stream)), "rnnlm_sort_segments_static")
 
 
 class Rnnlm:

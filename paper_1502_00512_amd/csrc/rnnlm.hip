@@ -6,6 +6,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1400,6 +1401,72 @@ int rnnlm_sort_segments(rnnlm_t *h, const int32_t *x, int32_t T, int32_t *perm, 
                      (const float *)nullptr, 0, (float *)nullptr);
   HIP_TRY(hipGetLastError());
   return sort_segments<float>(h, T, perm, seg_start, nseg, st);
+}
+
+// ---- the entry point that allocates nothing ----------------------------------------------------------------
+namespace {
+constexpr int STATIC_MAX_POSITIONS = 65536;  // padded window positions the static scratch holds
+struct StaticScratch {
+  int32_t xp[STATIC_MAX_POSITIONS];  // padded, range-checked ids
+  float lse[STATIC_MAX_POSITIONS];   // the token-preparation kernel marks padded positions here
+  int32_t flags[64];                 // [0]: an id was out of range
+};
+constexpr int STATIC_MAX_DEVICES = 64;
+}  // namespace
+// One copy per GPU, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress: kernels get the address that call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticScratch)];
+namespace {
+std::mutex static_mutex;
+StaticScratch *static_ptr[STATIC_MAX_DEVICES] = {nullptr};
+
+// Address of the current device's copy of the scratch array (asked once per device, with that device current).
+int static_scratch(StaticScratch **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return RNNLM_ERR_HIP;
+  if (dev < 0 || dev >= STATIC_MAX_DEVICES) return RNNLM_ERR_ARG;
+  std::lock_guard<std::mutex> lock(static_mutex);
+  if (!static_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RNNLM_ERR_HIP;
+    static_ptr[dev] = static_cast<StaticScratch *>(p);
+  }
+  *out = static_ptr[dev];
+  return RNNLM_OK;
+}
+
+// Hands the range flag to the caller (when asked for) and clears it for the next call.
+__global__ void static_flag_kernel(int32_t *flags, int32_t *range_flag) {
+  if (threadIdx.x == 0) {
+    if (range_flag) *range_flag = flags[0] ? 1 : 0;
+    flags[0] = 0;
+  }
+}
+}  // namespace
+
+int rnnlm_sort_segments_static(const int32_t *x, int32_t T, int32_t B, int32_t V, int32_t *perm, int32_t *seg_start,
+                               int32_t *nseg, int32_t *range_flag, void *stream) {
+  if (!x || !perm || !seg_start || !nseg || T < 1 || B < 1 || V < 1) return RNNLM_ERR_ARG;
+  const long Bp = round_up(B, PAD_B);
+  const long Mp = round_up((long)T * Bp, PAD_M);
+  if (Mp > STATIC_MAX_POSITIONS) return RNNLM_ERR_ARG;  // beyond what the static scratch holds
+  StaticScratch *sc = nullptr;
+  int rc = static_scratch(&sc);
+  if (rc) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const int M = T * B;
+  const int prep_blocks = (int)blocks_for(Mp, 256);
+  // the array keeps the previous call's contents: the flag starts at zero, the ids of all Mp positions are rewritten
+  hipLaunchKernelGGL(fill_kernel<int32_t>, dim3(1), dim3(64), 0, st, sc->flags, 64L, 0);
+  hipLaunchKernelGGL(prep_tokens_kernel<float>, dim3(prep_blocks), dim3(256), 0, st, x, (const int32_t *)nullptr, T, B,
+                     (int)Bp, (int)Mp, V, sc->xp, (int32_t *)nullptr, sc->lse, sc->flags, (const float *)nullptr, 0, 0,
+                     (float *)nullptr, (unsigned *)nullptr, prep_blocks, (const float *)nullptr, (float *)nullptr,
+                     (const float *)nullptr, 0, (float *)nullptr);
+  hipLaunchKernelGGL(rank_sort_kernel, dim3(blocks_for(M, 64)), dim3(1024), 0, st, sc->xp, M, B, (int)Bp, perm);
+  hipLaunchKernelGGL(segment_kernel, dim3(1), dim3(1024), 0, st, sc->xp, perm, M, B, (int)Bp, seg_start, nseg);
+  hipLaunchKernelGGL(static_flag_kernel, dim3(1), dim3(64), 0, st, sc->flags, range_flag);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
 }
 
 int rnnlm_set_barrier_spin_limit(rnnlm_t *h, uint32_t polls) {
