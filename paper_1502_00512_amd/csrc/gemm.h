@@ -765,32 +765,105 @@ struct EpiSgd : EpiZeroInit {
   __device__ inline void run(f32x16_t (&acc)[TM][TN], const EpiCtx &c) const {
     const int row0 = c.tile_row0 + c.wrow, col0 = c.tile_col0 + c.wcol, lane = c.lane;
     const int lc = lane & 31;
-    if (row0 + 32 * TM <= R && col0 + 32 * TN <= C) {
-      // interior: no checks; the master values of a whole 32-row block of the wave tile (TN x 16 loads per
-      // lane) are requested before any is used (W and out alias when training in place)
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        float w[TN][16];
-        if (alpha != 0.0f) {
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-              w[j][r] = W[(long)(row0 + i * 32 + RNNLM_ACC_ROW(r, lane)) * ldw + col0 + j * 32 + lc];
-        }
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (row0 + 32 * TM <= R && col0 + 32 * TN <= C && (ldc & 1) == 0) {
+      // Interior wave tile: no checks.  What bounds this epilogue is memory latency (a compute unit moves 640 KB
+      // per tile; its matrix cores idle meanwhile), so the master values of TWO 32-row blocks are in flight at
+      // any time: block i + 2 is requested as soon as block i has been stored.  All accesses go through buffer
+      // resources based at the wave tile's origin: one lane-dependent offset register serves every access and
+      // the row part is a scalar, which leaves the registers for the 2 x TN x 16 values in flight (with pointer
+      // arithmetic the addresses alone would not fit).  W and out are the same array when training in place:
+      // buffer accesses are kept in program order.  The copy in the compute type leaves as packed pairs:
+      // neighbouring lanes swap one value so that each lane owns two adjacent columns of one row.
+      // (the wave tile's origin is the same for all lanes: say so, or every access becomes a loop over lanes)
+      const long origin = (long)__builtin_amdgcn_readfirstlane(row0) * ldw + __builtin_amdgcn_readfirstlane(col0);
+      const long origin_c = (long)__builtin_amdgcn_readfirstlane(row0) * ldc + __builtin_amdgcn_readfirstlane(col0);
+      auto uniform = [](auto *p) {
+        const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+        const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+        const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+        return reinterpret_cast<decltype(p)>(((unsigned long long)hi << 32) | lo);
+      };
+      const __amdgpu_buffer_rsrc_t rw =
+          __builtin_amdgcn_make_buffer_rsrc(uniform(const_cast<float *>(W) + origin), 0, 0x7fffffff, 0x00020000);
+      const __amdgpu_buffer_rsrc_t ro =
+          __builtin_amdgcn_make_buffer_rsrc(uniform(out + origin), 0, 0x7fffffff, 0x00020000);
+      const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
+          uniform(Wc ? Wc + origin_c : reinterpret_cast<T *>(out + origin)), 0, 0x7fffffff, 0x00020000);
+      const int half = lane >> 5;
+      const int voff = (int)((half * 4 * ldw + lc) * 4);  // this lane's byte offset inside a 32-row block
+      const bool odd = lane & 1;
+      const int voffc = (int)(((half * 4 + (odd ? 1 : 0)) * ldc + (lc & ~1)) * (long)sizeof(T));
+      const int ldw4 = (int)(ldw * 4), ldcb = (int)(ldc * (long)sizeof(T));
+      auto request = [&](int i, float (&w)[TN][16]) {
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
+          for (int r = 0; r < 16; ++r)
+            w[j][r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                          rw, voff, (i * 32 + 8 * (r >> 2) + (r & 3)) * ldw4 + j * 128, 0));
+      };
+      auto apply = [&](int i, const float (&w)[TN][16]) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          float nv[16];
+#pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const long row = row0 + i * 32 + RNNLM_ACC_ROW(r, lane);
-            const int col = col0 + j * 32 + lc;
-            const float nv = ((alpha != 0.0f) ? alpha * w[j][r] : 0.0f) - lr * acc[i][j][r];
-            out[row * ldw + col] = nv;
-            if (Wc) Wc[row * ldc + col] = from_f32<T>(nv);
+            nv[r] = ((alpha != 0.0f) ? alpha * w[j][r] : 0.0f) - lr * acc[i][j][r];
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, nv[r]), ro, voff,
+                                                  (i * 32 + 8 * (r >> 2) + (r & 3)) * ldw4 + j * 128, 0);
           }
+          if (Wc) {
+            if constexpr (sizeof(T) == 2) {
+              typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+#pragma unroll
+              for (int q = 0; q < 8; ++q) {  // rows 2q, 2q+1 of this lane's 16: even lanes keep 2q, odd lanes 2q+1
+                union {
+                  bf16x2_t h;
+                  unsigned u;
+                } pk;
+                pk.h[0] = (bf16_t)nv[2 * q];
+                pk.h[1] = (bf16_t)nv[2 * q + 1];
+                const unsigned mine = pk.u;
+                const unsigned theirs = (unsigned)__builtin_amdgcn_mov_dpp((int)mine, 0xB1, 0xF, 0xF, true);  // lane ^ 1
+                const unsigned word = odd ? ((theirs >> 16) | (mine & 0xffff0000u)) : ((mine & 0xffffu) | (theirs << 16));
+                const int r0 = 2 * q;
+                __builtin_amdgcn_raw_buffer_store_b32(word, rc, voffc,
+                                                      (i * 32 + 8 * (r0 >> 2) + (r0 & 3)) * ldcb + j * 32 * (int)sizeof(T), 0);
+              }
+            } else {
+#pragma unroll
+              for (int r = 0; r < 16; ++r)
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, nv[r]), rc, (int)((half * 4 * ldc + lc) * 4),
+                                                      (i * 32 + 8 * (r >> 2) + (r & 3)) * ldcb + j * 128, 0);
+            }
+          }
+        }
+      };
+      if (alpha != 0.0f) {
+        static_assert(TM % 2 == 0, "two row blocks in flight");
+        float wa[TN][16], wb[TN][16];
+        request(0, wa);
+        request(1, wb);
+#pragma unroll
+        for (int i = 0; i < TM; i += 2) {
+          apply(i, wa);
+          if (i + 2 < TM) request(i + 2, wa);
+          apply(i + 1, wb);
+          if (i + 3 < TM) request(i + 3, wb);
+        }
+      } else {
+        float wz[TN][16];
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) wz[j][r] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) apply(i, wz);
       }
       return;
     }
+#endif
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -413,82 +413,113 @@ __global__ void segment_kernel(const int32_t *__restrict__ xp, const int32_t *__
 
 // ---- a10: segmented embedding update, atomic-free and order-fixed -------------------------------
 //   out[w][:] = alpha*E[w][:] - lr * sum_{m in run of w} dA[m][:]
-// blockIdx.x = run index (exits when >= *nseg), blockIdx.y = block of COLS columns.  The run's members
-// are dealt round-robin to PARTS partial sums (each accumulated in ascending m, position indices
-// fetched four at a time so the row loads are independent), which are then added in order
-// 0..PARTS-1: a fixed summation tree, so results are bitwise reproducible.
-// VEC = 4: a lane owns 4 consecutive columns (H % 4 == 0); VEC = 1: any H.
+// blockIdx.x = run index (exits when >= *nseg), blockIdx.y = block of 256*VEC columns; a thread owns VEC
+// consecutive columns.  The run's members are dealt round-robin to PARTS partial sums (member i of the run goes
+// to sum i mod PARTS, each sum accumulated in ascending m), which are then added in order 0..PARTS-1: a fixed
+// summation tree, so results are bitwise reproducible.  All PARTS sums live in the thread's registers: a group
+// of 16 members is 16 independent row loads in flight, and the small workgroups (no LDS, no barrier) leave
+// eight of them resident per compute unit, which is what a pass made of dependent memory round trips (run
+// bounds -> position -> rows) needs: it is bound by latency times occupancy, not by bandwidth.
+// VEC = 4: H % 4 == 0; VEC = 1: any H.
 // Ec (may be nullptr): compute copy [.][ldc] of the updated matrix, refreshed with the new row (the tied word
 // matrix of the compressed architecture is an operand of the output layer as well).
 template <int VEC, typename T>
-__global__ void __launch_bounds__(1024) scatter_update_kernel(const float *__restrict__ dA, int Hp, int H, int B,
-                                                              int Bp, const int32_t *__restrict__ xp,
-                                                              const int32_t *__restrict__ perm,
-                                                              const int32_t *__restrict__ seg_start,
-                                                              const int32_t *__restrict__ nseg,
-                                                              const float *__restrict__ E, float *__restrict__ out,
-                                                              float alpha, float lr, int compact_ld,
-                                                              T *__restrict__ Ec, int ldc) {
-  constexpr int PARTS = 4, LANES = 256;
-  __shared__ float sh[PARTS][LANES * VEC];
+__global__ void __launch_bounds__(256) scatter_update_kernel(const float *__restrict__ dA, int Hp, int H, int B,
+                                                             int Bp, const int32_t *__restrict__ xp,
+                                                             const int32_t *__restrict__ perm,
+                                                             const int32_t *__restrict__ seg_start,
+                                                             const int32_t *__restrict__ nseg,
+                                                             const float *__restrict__ E, float *__restrict__ out,
+                                                             float alpha, float lr, int compact_ld,
+                                                             T *__restrict__ Ec, int ldc) {
+  constexpr int PARTS = 4, GROUP = 4 * PARTS;
   const int g = blockIdx.x;
   if (g >= *nseg) return;
-  const int lane = threadIdx.x % LANES, partn = threadIdx.x / LANES;
-  const int col = (blockIdx.y * LANES + lane) * VEC;
+  const int col = (blockIdx.y * 256 + threadIdx.x) * VEC;
+  if (col >= H) return;
   const int r0 = seg_start[g], r1 = seg_start[g + 1];
-  float acc[VEC];
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
-  if (col < H) {
-    int r = r0 + partn;
-    for (; r + 3 * PARTS < r1; r += 4 * PARTS) {
-      long row[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int m = perm[r + q * PARTS];
-        row[q] = ((long)(m / B) * Bp + (m % B)) * Hp + col;
-      }
-      float v[4][VEC];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (VEC == 4) {
-          const f32x4_t t = *reinterpret_cast<const f32x4_t *>(dA + row[q]);
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) v[q][e] = t[e];
-        } else {
-          v[q][0] = dA[row[q]];
-        }
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[e] += v[q][e];
-    }
-    for (; r < r1; r += PARTS) {
-      const int m = perm[r];
-      const long rowi = ((long)(m / B) * Bp + (m % B)) * Hp + col;
-#pragma unroll
-      for (int e = 0; e < VEC; ++e) acc[e] += dA[rowi + e];
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < VEC; ++e) sh[partn][lane * VEC + e] = acc[e];
-  __syncthreads();
-  if (partn != 0 || col >= H) return;
-#pragma unroll
-  for (int q = 1; q < PARTS; ++q)
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) acc[e] += sh[q][lane * VEC + e];
   const int m0 = perm[r0];
   const int w = xp[(m0 / B) * Bp + (m0 % B)];
   const long idx = (long)w * H + col;
+  // the row being updated does not depend on the sum: ask for it first
+  float old[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) old[e] = 0.0f;
+  if (alpha != 0.0f) {
+    if (VEC == 4) {
+      const f32x4_t t = *reinterpret_cast<const f32x4_t *>(E + idx);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) old[e] = t[e];
+    } else {
+      old[0] = E[idx];
+    }
+  }
+  auto row_of = [&](int r) {
+    const int m = perm[r];
+    return ((long)(m / B) * Bp + (m % B)) * Hp + col;
+  };
+  auto load_row = [&](long at, float (&v)[VEC]) {
+    if (VEC == 4) {
+      const f32x4_t t = *reinterpret_cast<const f32x4_t *>(dA + at);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[e] = t[e];
+    } else {
+      v[0] = dA[at];
+    }
+  };
+  float acc[PARTS][VEC];
+#pragma unroll
+  for (int p = 0; p < PARTS; ++p)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[p][e] = 0.0f;
+  int r = r0;
+  for (; r + GROUP <= r1; r += GROUP) {
+    long at[GROUP];
+#pragma unroll
+    for (int k = 0; k < GROUP; ++k) at[k] = row_of(r + k);
+    float v[GROUP][VEC];
+#pragma unroll
+    for (int k = 0; k < GROUP; ++k) load_row(at[k], v[k]);
+#pragma unroll
+    for (int k = 0; k < GROUP; ++k)  // member r + k belongs to sum k % PARTS (r - r0 is a multiple of GROUP)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[k % PARTS][e] += v[k][e];
+  }
+  for (; r < r1; r += PARTS) {
+    float v[PARTS][VEC];
+#pragma unroll
+    for (int p = 0; p < PARTS; ++p) {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[p][e] = 0.0f;
+      if (r + p < r1) load_row(row_of(r + p), v[p]);
+    }
+#pragma unroll
+    for (int p = 0; p < PARTS; ++p)
+      if (r + p < r1) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[p][e] += v[p][e];
+      }
+  }
+#pragma unroll
+  for (int p = 1; p < PARTS; ++p)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[0][e] += acc[p][e];
   // compact_ld > 0: the run's result goes to row g of a compact [runs][compact_ld] buffer instead of row w
   const long oidx = compact_ld > 0 ? (long)g * compact_ld + col : idx;
+  float nv[VEC];
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) {
-    const float nv = ((alpha != 0.0f) ? alpha * E[idx + e] : 0.0f) - lr * acc[e];
-    out[oidx + e] = nv;
-    if (Ec) Ec[(long)w * ldc + col + e] = from_f32<T>(nv);
+  for (int e = 0; e < VEC; ++e) nv[e] = ((alpha != 0.0f) ? alpha * old[e] : 0.0f) - lr * acc[0][e];
+  if (VEC == 4) {
+    f32x4_t t;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) t[e] = nv[e];
+    *reinterpret_cast<f32x4_t *>(out + oidx) = t;
+  } else {
+    out[oidx] = nv[0];
+  }
+  if (Ec) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) Ec[(long)w * ldc + col + e] = from_f32<T>(nv[e]);
   }
 }
 

@@ -302,9 +302,11 @@ bool persistent_ok(const rnnlm_t *h) {
 
 // Per-step recurrent path for shapes the persistent kernel does not cover: with whole blocks of 256 streams
 // and a wide hidden layer the step's contraction is split over its contraction dimension (0: not split).
+// bf16: 256 x 128 tiles through the direct global->LDS kernels; fp32: 256 x 64 tiles through the register-staged one.
+int rnn_step_tile_n(const rnnlm_t *h) { return h->cfg.precision == RNNLM_FP32 ? 64 : 128; }
 int rnn_step_splits(const rnnlm_t *h) {
   if (h->Bp % 256 != 0 || h->Hp < 2048) return 0;
-  const long tiles = (long)(h->Bp / 256) * (h->Hp / 64);
+  const long tiles = (long)(h->Bp / 256) * (h->Hp / rnn_step_tile_n(h));
   long S = std::max<long>(1, 256 / tiles);
   const int BK = (h->cfg.precision == RNNLM_FP32) ? 32 : 64;
   S = std::min<long>(std::min<long>(S, 8), std::min<long>(h->Hp / BK, h->L.partElems / ((long)h->Bp * h->Hp)));
@@ -478,13 +480,17 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
     const T *B_ = at<T>(h, h->L.U_c);
     const int S = rnn_step_splits(h);
     if (S > 0) {
-      // wide step: all streams x 64 units per workgroup, contraction split S ways, then sum + sigmoid
+      // wide step: all streams x 128 (fp32: 64) units per workgroup, contraction split S ways, then sum + sigmoid
       const long per = (long)Bp * Hp;
       EpiPartial ep;
       ep.part = at<float>(h, h->L.part32);
       ep.ld = Hp;
       ep.split_stride = per;
-      HIP_TRY((launch_gemm<T, 256, 64, 4, 2, ROWK, ROWK>(st, A_, Hp, B_, Hp, Bp, Hp, Hp, S, ep)));
+      if constexpr (sizeof(T) == 2) {
+        HIP_TRY((launch_gemm_dma<256, 128, 4, 2, ROWK, ROWK>(st, A_, Hp, B_, Hp, Bp, Hp, Hp, S, ep)));
+      } else {
+        HIP_TRY((launch_gemm<T, 256, 64, 4, 2, ROWK, ROWK>(st, A_, Hp, B_, Hp, Bp, Hp, Hp, S, ep)));
+      }
       hipLaunchKernelGGL(rnn_step_fwd_kernel<T>, dim3(blocks_for(per / 4, 256)), dim3(256), 0, st,
                          at<float>(h, h->L.part32), per, S, epi.X, c.B, c.H, Hp, per / 4, epi.Hnext, epi.h_state);
       HIP_TRY(hipGetLastError());
@@ -775,7 +781,13 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
       ep.part = at<float>(h, h->L.part32);
       ep.ld = Hp;
       ep.split_stride = per;
-      if (K > 0) HIP_TRY((launch_gemm<T, 256, 64, 4, 2, ROWK, KROW>(st, A_, Hp, U_c, Hp, Bp, Hp, K, S, ep)));
+      if (K > 0) {
+        if constexpr (sizeof(T) == 2) {
+          HIP_TRY((launch_gemm_dma4<256, 128, 4, 2, ROWK, KROW>(st, A_, Hp, U_c, Hp, Bp, Hp, K, S, ep)));
+        } else {
+          HIP_TRY((launch_gemm<T, 256, 64, 4, 2, ROWK, KROW>(st, A_, Hp, U_c, Hp, Bp, Hp, K, S, ep)));
+        }
+      }
       hipLaunchKernelGGL(rnn_step_bwd_kernel<T>, dim3(blocks_for(per / 4, 256)), dim3(256), 0, st,
                          at<float>(h, h->L.part32), per, K > 0 ? S : 0, epi.dHs, epi.Hs, c.B, c.H, Hp, per / 4,
                          epi.dA32, epi.dAc);
@@ -874,10 +886,10 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     T *Ec = (c.P > 0 && u.refresh_copies) ? Wo_c : nullptr;
     const int W = h->D, Wp = h->Dp;
     if (W % 4 == 0) {
-      hipLaunchKernelGGL((scatter_update_kernel<4, T>), dim3(Tn * c.B, (W + 1023) / 1024), dim3(1024), 0, h->side, rows,
+      hipLaunchKernelGGL((scatter_update_kernel<4, T>), dim3(Tn * c.B, (W + 1023) / 1024), dim3(256), 0, h->side, rows,
                          Wp, W, c.B, Bp, xp, perm, seg, p_nseg(h), src, u.E, e_alpha, u.lr, u.e_compact_ld, Ec, Wp);
     } else {
-      hipLaunchKernelGGL((scatter_update_kernel<1, T>), dim3(Tn * c.B, (W + 255) / 256), dim3(1024), 0, h->side, rows,
+      hipLaunchKernelGGL((scatter_update_kernel<1, T>), dim3(Tn * c.B, (W + 255) / 256), dim3(256), 0, h->side, rows,
                          Wp, W, c.B, Bp, xp, perm, seg, p_nseg(h), src, u.E, e_alpha, u.lr, u.e_compact_ld, Ec, Wp);
     }
     HIP_TRY(hipGetLastError());

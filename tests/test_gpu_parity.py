@@ -230,7 +230,10 @@ BF16_SHAPES = [(3000, 256, 32, 4), (2049, 130, 5, 9), (5000, 384, 64, 6), (1000,
                # the persistent recurrent kernel's LDS-staged variants: 4 waves with 3 blocks per wave (Hp = 768),
                # 8 waves streaming 3 and 4 blocks per wave (Hp = 1536, 2048; several blocks of 32 streams)
                (900, 700, 6, 4), (900, 1500, 40, 3), (800, 2048, 70, 3),
-               (700, 256, 7, 1)]  # a single position: nothing flows back through time
+               (700, 256, 7, 1),  # a single position: nothing flows back through time
+               # per-step launches split over the contraction through the direct global->LDS kernels (whole blocks of
+               # 256 streams): cfg5's hidden size, ragged streams, H = 2048
+               (500, 4096, 256, 3), (500, 3000, 250, 2), (400, 2048, 256, 2)]
 
 
 @pytest.mark.parametrize("V,H,B,T", BF16_SHAPES)
