@@ -799,6 +799,70 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     }
   }
 
+  // E[w] -= lr * sum_{m: x[m] = w} dA[m]: on the side stream, behind the sort helpers already queued there (joined at
+  // the end of this function).
+  auto embedding_update = [&]() -> int {
+  {
+    StageTimer tm(h, RNNLM_STAGE_EMB, h->side);
+    // plain: rows of dA, width H.  Compressed: rows of dx, width P, added on top of the output-side update the
+    // same matrix has just received (training: in the master; gradient export: in the caller's buffer), and
+    // the compute copy of the tied matrix follows.
+    const float *rows = c.P > 0 ? at<float>(h, h->L.dX32) : dA32;
+    const float *src = (c.P > 0 && !u.refresh_copies) ? u.E : h->buf.E;
+    const float e_alpha = (c.P > 0 && !u.refresh_copies) ? 1.0f : u.alpha;
+    T *Ec = (c.P > 0 && u.refresh_copies) ? Wo_c : nullptr;
+    const int W = h->D, Wp = h->Dp;
+    if (W % 4 == 0) {
+      hipLaunchKernelGGL((scatter_update_kernel<4, T>), dim3(Tn * c.B, (W + 1023) / 1024), dim3(256), 0, h->side, rows,
+                         Wp, W, c.B, Bp, xp, perm, seg, p_nseg(h), src, u.E, e_alpha, u.lr, u.e_compact_ld, Ec, Wp);
+    } else {
+      hipLaunchKernelGGL((scatter_update_kernel<1, T>), dim3(Tn * c.B, (W + 255) / 256), dim3(256), 0, h->side, rows,
+                         Wp, W, c.B, Bp, xp, perm, seg, p_nseg(h), src, u.E, e_alpha, u.lr, u.e_compact_ld, Ec, Wp);
+    }
+    HIP_TRY(hipGetLastError());
+  }
+    return RNNLM_OK;
+  };
+  // U[i][j] -= lr * sum_m dA[m][i] Hprev[m][j], contracted transposed (tile rows = j, tile columns = i)
+  auto recurrent_update = [&](hipStream_t rs) -> int {
+  {
+    StageTimer tm(h, RNNLM_STAGE_REC_W, rs);
+    EpiSgdT<T> epi;
+    epi.W = h->buf.U;
+    epi.out = u.U;
+    epi.Wc = u.refresh_copies ? U_c : nullptr;
+    epi.WcT = u.refresh_copies ? at<T>(h, h->L.UT_c) : nullptr;  // the backward pass reads the transposed copy
+    epi.ldw = c.H;
+    epi.ldc = Hp;
+    epi.R = c.H;
+    epi.C = c.H;
+    epi.alpha = u.alpha;
+    epi.lr = u.lr;
+    if (sizeof(T) == 2 && (long)(Hp / BIG) * (Hp / BIG) >= 64) {
+      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW, true>(rs, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
+    } else if (Hp <= 1024) {  // small matrix: 64x64 tiles give up to 256 workgroups
+      HIP_TRY((launch_gemm<T, 64, 64, 2, 2, KROW, KROW>(rs, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
+    } else {
+      HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(rs, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
+    }
+  }
+    return RNNLM_OK;
+  };
+  // Plain architecture with the normalised criterion: the embedding update and the recurrent weight update need
+  // nothing from the output weight update, and the recurrent one has few tiles (64 at H = 2048): started on the
+  // side stream BEFORE the output weight update, they run on compute units that its last, partly empty round of
+  // tiles would leave idle (window time -2 % at H = 2048, -1.3 % at H = 1024).  At H = 4096 the recurrent update
+  // is a full round of 256 tiles by itself and nothing is gained (measured: -0.4 %, inside the noise), so the
+  // updates keep their place after the output weight update there.
+  const bool early_side = !nce && c.P == 0 && (long)(Hp / BIG) * (Hp / BIG) < 256;
+  if (early_side) {
+    int rc = side_fork(h, 0, st);
+    if (rc) return rc;
+    rc = embedding_update();
+    if (rc) return rc;
+    rc = recurrent_update(h->side);
+    if (rc) return rc;
+  }
   if (nce) {
     int rc = nce_update<T>(h, Tn, *nce, u, st);
     if (rc) return rc;
@@ -874,29 +938,11 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
       HIP_TRY((mid_gemm<T, ROWK, KROW>(st, dA_c, Hp, at<T>(h, h->L.A_c), h->Pp, Mp, h->Pp, Hp, 1, epi)));
     }
   }
-  // E[w] -= lr * sum_{m: x[m] = w} dA[m]: on the side stream, behind the sort helpers already queued there,
-  // next to the recurrent weight-gradient contraction of the main stream (joined at the end of this function;
-  // started after the large output weight update, which it would only slow down)
-  {
+  if (!early_side) {
     int rc = side_fork(h, 0, st);  // the side stream waits for everything queued so far
     if (rc) return rc;
-    StageTimer tm(h, RNNLM_STAGE_EMB, h->side);
-    // plain: rows of dA, width H.  Compressed: rows of dx, width P, added on top of the output-side update the
-    // same matrix has just received (training: in the master; gradient export: in the caller's buffer), and
-    // the compute copy of the tied matrix follows.
-    const float *rows = c.P > 0 ? at<float>(h, h->L.dX32) : dA32;
-    const float *src = (c.P > 0 && !u.refresh_copies) ? u.E : h->buf.E;
-    const float e_alpha = (c.P > 0 && !u.refresh_copies) ? 1.0f : u.alpha;
-    T *Ec = (c.P > 0 && u.refresh_copies) ? Wo_c : nullptr;
-    const int W = h->D, Wp = h->Dp;
-    if (W % 4 == 0) {
-      hipLaunchKernelGGL((scatter_update_kernel<4, T>), dim3(Tn * c.B, (W + 1023) / 1024), dim3(256), 0, h->side, rows,
-                         Wp, W, c.B, Bp, xp, perm, seg, p_nseg(h), src, u.E, e_alpha, u.lr, u.e_compact_ld, Ec, Wp);
-    } else {
-      hipLaunchKernelGGL((scatter_update_kernel<1, T>), dim3(Tn * c.B, (W + 255) / 256), dim3(256), 0, h->side, rows,
-                         Wp, W, c.B, Bp, xp, perm, seg, p_nseg(h), src, u.E, e_alpha, u.lr, u.e_compact_ld, Ec, Wp);
-    }
-    HIP_TRY(hipGetLastError());
+    rc = embedding_update();
+    if (rc) return rc;
   }
   if (c.P > 0) {
     // A[i][p] -= lr * sum_m da[m][i] x[m][p], contracted transposed (tile rows = p, tile columns = i)
@@ -914,27 +960,9 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     HIP_TRY((launch_gemm<T, 64, 64, 2, 2, KROW, KROW>(st, at<T>(h, h->L.Xp_c), h->Pp, dA_c, Hp, h->Pp, Hp, Mp, 1, epi)));
   }
 
-  // U[i][j] -= lr * sum_m dA[m][i] Hprev[m][j], contracted transposed (tile rows = j, tile columns = i)
-  {
-    StageTimer tm(h, RNNLM_STAGE_REC_W, st);
-    EpiSgdT<T> epi;
-    epi.W = h->buf.U;
-    epi.out = u.U;
-    epi.Wc = u.refresh_copies ? U_c : nullptr;
-    epi.WcT = u.refresh_copies ? at<T>(h, h->L.UT_c) : nullptr;  // the backward pass reads the transposed copy
-    epi.ldw = c.H;
-    epi.ldc = Hp;
-    epi.R = c.H;
-    epi.C = c.H;
-    epi.alpha = u.alpha;
-    epi.lr = u.lr;
-    if (sizeof(T) == 2 && (long)(Hp / BIG) * (Hp / BIG) >= 64) {
-      HIP_TRY((big_gemm<T, 2, 4, KROW, KROW, true>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
-    } else if (Hp <= 1024) {  // small matrix: 64x64 tiles give up to 256 workgroups
-      HIP_TRY((launch_gemm<T, 64, 64, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
-    } else {
-      HIP_TRY((launch_gemm<T, 128, 128, 2, 2, KROW, KROW>(st, Hs_c, Hp, dA_c, Hp, Hp, Hp, Mp, 1, epi)));
-    }
+  if (!early_side) {
+    int rc = recurrent_update(st);
+    if (rc) return rc;
   }
   // wait for the embedding update running on the side stream
   return side_join(h, 0, st);
