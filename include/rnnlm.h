@@ -280,8 +280,12 @@ int rnnlm_set_barrier_spin_limit(rnnlm_t *h, uint32_t polls);
  * AUTO (default): the XCD-local exchange when the placement probe at init allows it and there are at most 8
  * blocks of 32 streams, else the chip-wide one.  CHIP_WIDE: always agent-scope accesses and one counter for the
  * whole grid.  XCD_LOCAL: like AUTO, but RNNLM_ERR_ARG when the XCD-local exchange is not available for this
- * handle.  Both exchanges compute the same values in the same order: results are bitwise equal (tested).  Has
- * no effect on shapes that run one launch per step. */
+ * handle.  Both exchanges compute the same values in the same order: results are bitwise equal (tested).
+ * The widest recurrent shape (bf16, H padded to 4096, 256 streams) runs as one launch that keeps the
+ * state-to-state matrix in the register files of all compute units; it needs the same placement as the XCD-local
+ * exchange, and CHIP_WIDE selects one launch pair per step for it instead (same products, another order of
+ * additions: equal to bf16 rounding of the state, not bitwise).  No effect on other shapes that run one launch
+ * per step. */
 typedef enum { RNNLM_EXCHANGE_AUTO = 0, RNNLM_EXCHANGE_CHIP_WIDE = 1, RNNLM_EXCHANGE_XCD_LOCAL = 2 } rnnlm_exchange;
 int rnnlm_set_recurrent_exchange(rnnlm_t *h, int32_t mode);
 

@@ -18,6 +18,7 @@
 #include "nce.h"
 #include "rmsprop.h"
 #include "rnn_persistent.h"
+#include "rnn_resident.h"
 
 using namespace rnnlm_dev;
 
@@ -36,6 +37,9 @@ struct WsLayout {
   size_t gWo, gU, gb, gN, gbN;
   // compressed architecture (present when cfg.P > 0; then Wo_c holds the compute copy of the tied matrix E)
   size_t A_c, C_c, Xp_c, P_c, dP32, dP_c, dX32;
+  // partial sums of the chip-resident recurrent kernel (present for Hp = 4096, 256 streams, bf16)
+  size_t part_res, sync_res;
+  bool has_part_res;
   long partElems;
 };
 
@@ -250,6 +254,13 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
     L.dP_c = take((size_t)MpMax * Pp * es);
     L.dX32 = take((size_t)MpMax * Pp * 4);
   }
+  L.part_res = 0;
+  L.has_part_res = es == 2 && Pp == 0 && Hp == RES_HP && Bp == RES_BP;
+  L.sync_res = 0;
+  if (L.has_part_res) {
+    L.part_res = take((size_t)RES_PART_STEP * 4);
+    L.sync_res = take((size_t)RES_SYNC_WORDS * 4);
+  }
   L.scalars = take(256);  // [0]: int nseg, [4]: int nseg of the noise-contrastive update list, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64..131]: 17 barrier/ticket counters
   L.total = o;
 }
@@ -383,6 +394,42 @@ int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st
   return RNNLM_OK;
 }
 
+// Widest layer (Hp = 4096, 256 streams, bf16): one launch of 256 workgroups, one per compute unit, with the whole
+// state-to-state matrix resident in registers.  Needs the round-robin placement the init probe checks (32
+// workgroups on every XCD); RNNLM_EXCHANGE_CHIP_WIDE selects the per-step launches instead.
+bool resident_ok(const rnnlm_t *h) {
+  return h->L.has_part_res && h->xcd_local && h->exchange_mode != RNNLM_EXCHANGE_CHIP_WIDE &&
+         blocks_per_cu<rnn_resident_kernel<false>>(512) >= 1 && blocks_per_cu<rnn_resident_kernel<true>>(512) >= 1;
+}
+
+template <bool BACKWARD>
+int launch_rnn_resident(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st) {
+  typedef bf16_t T;
+  RnnResidentArgs ra;
+  RnnPersistArgs &a = ra.p;
+  a.W = BACKWARD ? at<T>(h, h->L.UT_c) : at<T>(h, h->L.U_c);
+  a.Hs = at<T>(h, h->L.Hs_c);
+  a.X = BACKWARD ? at<float>(h, h->L.dHs32) : at<float>(h, h->L.X32);
+  a.dA32 = at<float>(h, h->L.dA32);
+  a.dAc = at<T>(h, h->L.dA_c);
+  a.h_state = (!BACKWARD && advance_state) ? h->buf.h_state : nullptr;
+  a.counter = p_counter(h);  // zero here, as for the other persistent kernels
+  a.flags = p_flags(h);
+  a.T = Tn;
+  a.B = h->cfg.B;
+  a.H = h->cfg.H;
+  a.Bp = h->Bp;
+  a.Hp = h->Hp;
+  a.spin_limit = h->spin_limit;
+  ra.part = at<float>(h, h->L.part_res);
+  ra.sync = at<unsigned>(h, h->L.sync_res);
+  hipLaunchKernelGGL(fill_kernel<uint32_t>, dim3(blocks_for(RES_SYNC_WORDS, 256)), dim3(256), 0, st, ra.sync,
+                     (long)RES_SYNC_WORDS, 0u);
+  hipLaunchKernelGGL((rnn_resident_kernel<BACKWARD>), dim3(256), dim3(512), 0, st, ra);
+  HIP_TRY(hipGetLastError());
+  return RNNLM_OK;
+}
+
 struct UpdateTargets {
   // where each fused update writes: training -> the masters (alpha 1, lr), gradient export -> caller
   // buffers (alpha 0, lr -1, no compute-copy refresh, no state advance)
@@ -465,6 +512,10 @@ int forward_window(rnnlm_t *h, const int32_t *x, const int32_t *y, int Tn, float
   if (persistent_ok(h)) {
     StageTimer tm(h, RNNLM_STAGE_RNN_FWD, st);
     int rc = launch_rnn_persistent<T, false>(h, Tn, advance_state, st);
+    if (rc) return rc;
+  } else if (sizeof(T) == 2 && resident_ok(h)) {
+    StageTimer tm(h, RNNLM_STAGE_RNN_FWD, st);
+    int rc = launch_rnn_resident<false>(h, Tn, advance_state, st);
     if (rc) return rc;
   } else
   for (int t = 0; t < Tn; ++t) {
@@ -762,6 +813,10 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
   if (persistent_ok(h)) {
     StageTimer tm(h, RNNLM_STAGE_RNN_BWD, st);
     int rc = launch_rnn_persistent<T, true>(h, Tn, false, st);
+    if (rc) return rc;
+  } else if (sizeof(T) == 2 && resident_ok(h)) {
+    StageTimer tm(h, RNNLM_STAGE_RNN_BWD, st);
+    int rc = launch_rnn_resident<true>(h, Tn, false, st);
     if (rc) return rc;
   } else
   for (int t = Tn - 1; t >= 0; --t) {

@@ -533,6 +533,47 @@ def test_state_exchange_modes_agree_bitwise(precision, V, H, B, T, K):
         models[0].rnnlm_set_recurrent_exchange(3)
 
 
+def test_resident_recurrent_kernel_against_per_step_launches():
+    """Hidden size 4096 with 256 streams (cfg5's recurrent shape, small vocabulary): the one-launch kernel that
+    keeps the state-to-state matrix in registers against one launch pair per step (selected with
+    RNNLM_EXCHANGE_CHIP_WIDE).  Both add the same products in a different order (contraction split 4 x 2
+    against 8 ways), so states agree to bf16 rounding, not bitwise: log-probabilities and gradients of one
+    window from identical weights are compared at the tolerance of the oracle comparison, the carried state
+    after 12 trained windows stays close, and two runs of the resident kernel are bitwise equal (its order
+    of additions does not depend on which compute unit takes which part)."""
+    V, H, B, T, K = 700, 4096, 256, 8, 12
+    E, U, Wo, b = synth.make_weights(V, H, "normal", 0.01, 91)
+    tok = synth.zipf_tokens(K * B * T + B + 1, V, 1.05, 92, 25.0)
+    dtok = dev(tok)
+
+    def run(mode):
+        m = binding.Rnnlm(E, U, Wo, b, B, T, BF16)
+        m.rnnlm_set_recurrent_exchange(mode)
+        x, y = m.rnnlm_stream_chunk(dtok, 0, T)
+        grads = m.rnnlm_grad_chunk(x, y)
+        first = {k: v.cpu().numpy().copy() for k, v in grads.items()}
+        for k in range(K):
+            x, y = m.rnnlm_stream_chunk(dtok, k, T)
+            m.rnnlm_train_chunk(x, y, 0.05)
+        m.rnnlm_check()
+        out = (first, m.h_state.cpu().numpy().copy(), m.U.cpu().numpy().copy())
+        m.close()
+        return out
+
+    a = run(binding.RNNLM_EXCHANGE_AUTO)
+    a2 = run(binding.RNNLM_EXCHANGE_AUTO)
+    c = run(binding.RNNLM_EXCHANGE_CHIP_WIDE)
+    for n in a[0]:
+        assert np.array_equal(a[0][n], a2[0][n]), n
+    assert np.array_equal(a[1], a2[1]) and np.array_equal(a[2], a2[2])
+    for n in a[0]:
+        u, v = a[0][n].astype(np.float64), c[0][n].astype(np.float64)
+        scale = max(np.abs(v).max(), 1e-30)
+        assert np.abs(u - v).max() <= 2e-2 * scale, (n, np.abs(u - v).max(), scale)
+    assert np.abs(a[1] - c[1]).max() < 2e-2          # states lie in (0, 1)
+    assert np.abs(a[2] - c[2]).max() < 1e-4          # recurrent matrix after 12 windows (entries ~ 0.01)
+
+
 # ---- error reporting and checkpoint-style use ------------------------------------------------------------
 
 def test_nonfinite_sum_is_reported():
