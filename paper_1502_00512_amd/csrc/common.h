@@ -44,6 +44,15 @@ __device__ inline float from_f32<float>(float v) { return v; }
 template <>
 __device__ inline bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // round-to-nearest-even
 
+// Barrier and ticket counters of the persistent recurrent kernels.  Every counter has a 256-byte line to itself:
+// polls queue at the address they read, and with the counters of all eight XCDs in one line (or all workgroups
+// of the chip polling one word) an arrival took several microseconds to become visible to the pollers instead
+// of under one.  kind 0 (x = 0): the whole grid's counter of the chip-wide exchange; kind 1: step barrier of the
+// group on XCD x; kind 2: ticket dispenser of XCD x; kinds 3 and 4: the two levels of the resident kernel's
+// chip-wide barrier (arrivals of XCD x's workgroups; XCDs that have fully arrived, one copy per XCD).
+constexpr int SYNC_WORDS = 5 * 8 * 64;
+__host__ __device__ inline int sync_word(int kind, int x) { return (kind * 8 + x) * 64; }
+
 __device__ inline float sigmoidf_(float a) { return 1.0f / (1.0f + __expf(-a)); }
 
 }  // namespace rnnlm_dev

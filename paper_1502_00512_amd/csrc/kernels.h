@@ -21,7 +21,7 @@ __global__ void stream_chunk_kernel(const int32_t *__restrict__ tok, long L, lon
 // blockIdx.x < prep_blocks: token check + re-layout into the padded window: xp/yp[t*Bp + s]; padding rows
 //   get -1.  Ids outside [0, V) are clamped and raise flags[0].  Also marks padded positions with
 //   lse = +inf so that the softmax-gradient pass produces exact zeros there, copies the carried state into
-//   slot 0 of the hidden-state buffer (compute type, padded with zeros) and clears the 17 barrier / ticket
+//   slot 0 of the hidden-state buffer (compute type, padded with zeros) and clears the barrier / ticket
 //   counters of the persistent recurrent kernel that follows (slot / counters == nullptr: tokens only).
 //   prep_blocks covers max(Mp, Bp*Hp) threads.
 // blockIdx.x >= prep_blocks (present when X or Xc != nullptr): a1, embedding gather of padded row
@@ -65,7 +65,7 @@ __global__ void __launch_bounds__(256) prep_tokens_kernel(const int32_t *__restr
     return;
   }
   const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (counters && i < 17) counters[i] = 0u;
+  if (counters && i < SYNC_WORDS) counters[i] = 0u;
   if (slot && i < (long)Bp * Hp) {
     const int s = (int)(i / Hp), c = (int)(i % Hp);
     slot[i] = from_f32<T>((s < B && c < H) ? h_state[(long)s * H + c] : 0.0f);
@@ -231,13 +231,14 @@ __global__ void __launch_bounds__(1024) merge_stats_kernel(const float2 *__restr
 }
 
 // Sum of the window's log-probabilities in fp64 with a fixed reduction tree; raises flags[1] when the
-// result is not finite.  counters != nullptr: also clears the 17 barrier / ticket counters of the
+// result is not finite.  counters != nullptr: also clears the barrier / ticket counters of the
 // persistent recurrent kernel (this kernel sits between its forward and its backward launch).
 __global__ void sum_logp_kernel(const float *__restrict__ logp, int n, double *__restrict__ out,
                                 double *__restrict__ running, int32_t *__restrict__ flags,
                                 unsigned *__restrict__ counters) {
   __shared__ double sh[1024];
-  if (counters && threadIdx.x < 17) counters[threadIdx.x] = 0u;  // for the backward recurrent kernel
+  if (counters)  // for the backward recurrent kernel
+    for (int i = threadIdx.x; i < SYNC_WORDS; i += 1024) counters[i] = 0u;
   double a = 0.0;
   for (int i = threadIdx.x; i < n; i += 1024) a += (double)logp[i];
   sh[threadIdx.x] = a;

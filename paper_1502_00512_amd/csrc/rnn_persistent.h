@@ -24,8 +24,7 @@ struct RnnPersistArgs {
   float *dA32;        // backward: [T][Bp][Hp]
   void *dAc;          // backward: [T][Bp][Hp] compute type
   float *h_state;     // forward: [B][H] or nullptr
-  unsigned *counter;  // barrier counters, zero at launch: [0] whole grid; [1 + x] the group on XCD x;
-                      // [9 + x] ticket dispenser of XCD x
+  unsigned *counter;  // SYNC_WORDS barrier / ticket counters, zero at launch (see sync_word)
   int32_t *flags;     // flags[2] raised when a barrier wait expires
   int T, B, H, Bp, Hp;
   unsigned spin_limit;
@@ -223,13 +222,13 @@ __global__ void __launch_bounds__(64 * NWAVE, NWAVE == 8 ? 4 : 1) rnn_persistent
     const int x = xcc_id();
     if (x >= nsb) return;  // no group lives on this XCD
     if (threadIdx.x == 0)
-      s_ticket = (int)__hip_atomic_fetch_add(a.counter + 9 + x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_ticket = (int)__hip_atomic_fetch_add(a.counter + sync_word(2, x), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     sb = x;
     ub = s_ticket;
     nwg = (unsigned)(a.Hp / 32);
     if (ub >= (int)nwg) return;  // surplus workgroup
-    counter = a.counter + 1 + x;
+    counter = a.counter + sync_word(1, x);
   } else {
     sb = blockIdx.x % nsb;
     ub = blockIdx.x / nsb;
@@ -394,12 +393,12 @@ __global__ void __launch_bounds__(512, 2) rnn_persistent_wide_kernel(const RnnPe
   const int x = xcc_id();
   if (x >= nsb) return;  // no group lives on this XCD
   if (threadIdx.x == 0)
-    s_ticket = (int)__hip_atomic_fetch_add(a.counter + 9 + x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_ticket = (int)__hip_atomic_fetch_add(a.counter + sync_word(2, x), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   const int sb = x, ub = s_ticket;
   const unsigned nwg = (unsigned)(a.Hp / 64);
   if (ub >= (int)nwg) return;  // surplus workgroup
-  unsigned *counter = a.counter + 1 + x;
+  unsigned *counter = a.counter + sync_word(1, x);
   const int Hp = a.Hp, Bp = a.Bp;
   const long slot = (long)Bp * Hp;
   const int kq = wave * (KS * 16);

@@ -24,10 +24,9 @@
 // side), read only after the chip-wide barrier by agent-scope loads of addresses no compute unit has touched
 // since they were written.
 //
-// Barriers.  Every counter sits on a 256-byte line of its own and is polled by at most the 32 workgroups of
-// one XCD: pollers queue at the counter's address, and with all 256 workgroups polling one word (or the eight
-// XCD counters sharing a line) an arrival took 5-7 us to become visible instead of under 1.  The chip-wide
-// barrier counts arrivals per XCD; the last workgroup of an XCD adds one to a per-XCD copy of the global count.
+// Barriers.  Every counter sits on a line of its own (sync_word) and is polled by at most the 32 workgroups of
+// one XCD.  The chip-wide barrier counts arrivals per XCD; the last workgroup of an XCD adds one to every XCD's
+// copy of the count of XCDs that have arrived, and a workgroup polls its own XCD's copy.
 // Every wait is bounded: on expiry flags[2] is raised and every workgroup still runs to its end.
 #pragma once
 #include "rnn_persistent.h"
@@ -39,16 +38,9 @@ constexpr int RES_BP = 256;     // padded streams
 constexpr long RES_PART_XCD = 4L * RES_BP * (RES_HP / 8);  // floats of partial sums per XCD and step
 constexpr long RES_PART_STEP = 8 * RES_PART_XCD;           // floats per step (16 MB)
 
-// Barrier counters (zero at launch), 256 bytes apart.  kind 0: arrivals at the XCD barrier of XCD x;
-// kind 1: arrivals of XCD x's workgroups at the chip-wide barrier; kind 2: XCDs that have fully arrived at the
-// chip-wide barrier, one copy per XCD (polled only by that XCD's workgroups).
-constexpr int RES_SYNC_WORDS = 3 * 8 * 64;
-__host__ __device__ inline int res_sync_word(int kind, int x) { return (kind * 8 + x) * 64; }
-
 struct RnnResidentArgs {
   RnnPersistArgs p;
   float *part;  // [8 XCDs][4 kc][256 streams][512 units], reused by every step
-  unsigned *sync;  // RES_SYNC_WORDS counters, zero at launch, each on a 256-byte line of its own (see res_sync_word)
 };
 
 template <bool BACKWARD>
@@ -65,7 +57,7 @@ __global__ void __launch_bounds__(512) rnn_resident_kernel(const RnnResidentArgs
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int x = xcc_id();
   if (tid == 0)
-    s_ticket = (int)__hip_atomic_fetch_add(a.counter + 9 + x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_ticket = (int)__hip_atomic_fetch_add(a.counter + sync_word(2, x), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   __syncthreads();
   const int j = s_ticket;
   if (j >= 32) return;  // surplus workgroup
@@ -74,9 +66,9 @@ __global__ void __launch_bounds__(512) rnn_resident_kernel(const RnnResidentArgs
   const int lr = lane & 31, lk = (lane >> 5) * 8;
   const int n0 = x * 512 + uc * 128 + uq * 32;  // first unit of this wave (global index)
   const int k0 = kc * 1024 + kh * 512;          // first contraction index of this wave
-  unsigned *xcounter = ra.sync + res_sync_word(0, x);
-  unsigned *garrive = ra.sync + res_sync_word(1, x);
-  unsigned *ggo = ra.sync + res_sync_word(2, x);
+  unsigned *xcounter = a.counter + sync_word(1, x);
+  unsigned *garrive = a.counter + sync_word(3, x);
+  unsigned *ggo = a.counter + sync_word(4, x);
 
   // this wave's slice of the matrix, resident for all T steps: row n of W holds the k-contiguous operand
   bf16x8_t w[32];
@@ -324,7 +316,7 @@ __global__ void __launch_bounds__(512) rnn_resident_kernel(const RnnResidentArgs
         if (old + 1 == (unsigned)(step + 1) * 32u) {
 #pragma unroll
           for (int y = 0; y < 8; ++y)
-            __hip_atomic_fetch_add(ra.sync + res_sync_word(2, y), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(a.counter + sync_word(4, y), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
       copy_x(BACKWARD ? t - 1 : t + 1);

@@ -38,7 +38,7 @@ struct WsLayout {
   // compressed architecture (present when cfg.P > 0; then Wo_c holds the compute copy of the tied matrix E)
   size_t A_c, C_c, Xp_c, P_c, dP32, dP_c, dX32;
   // partial sums of the chip-resident recurrent kernel (present for Hp = 4096, 256 streams, bf16)
-  size_t part_res, sync_res;
+  size_t part_res, sync;
   bool has_part_res;
   long partElems;
 };
@@ -256,12 +256,9 @@ void make_layout(const rnnlm_config &c, int &Hp, int &Vp, int &Bp, int &MpMax, i
   }
   L.part_res = 0;
   L.has_part_res = es == 2 && Pp == 0 && Hp == RES_HP && Bp == RES_BP;
-  L.sync_res = 0;
-  if (L.has_part_res) {
-    L.part_res = take((size_t)RES_PART_STEP * 4);
-    L.sync_res = take((size_t)RES_SYNC_WORDS * 4);
-  }
-  L.scalars = take(256);  // [0]: int nseg, [4]: int nseg of the noise-contrastive update list, [8..19]: int flags[3], [32]: double sum, [40]: double running, [64..131]: 17 barrier/ticket counters
+  if (L.has_part_res) L.part_res = take((size_t)RES_PART_STEP * 4);
+  L.sync = take((size_t)SYNC_WORDS * 4);  // barrier / ticket counters of the persistent recurrent kernels
+  L.scalars = take(256);  // [0]: int nseg, [4]: int nseg of the noise-contrastive update list, [8..19]: int flags[3], [32]: double sum, [40]: double running
   L.total = o;
 }
 
@@ -274,7 +271,7 @@ int32_t *p_nseg2(rnnlm_t *h) { return at<int32_t>(h, h->L.scalars + 4); }
 int32_t *p_flags(rnnlm_t *h) { return at<int32_t>(h, h->L.scalars + 8); }
 double *p_sum(rnnlm_t *h) { return at<double>(h, h->L.scalars + 32); }
 double *p_running(rnnlm_t *h) { return at<double>(h, h->L.scalars + 40); }
-unsigned *p_counter(rnnlm_t *h) { return at<unsigned>(h, h->L.scalars + 64); }
+unsigned *p_counter(rnnlm_t *h) { return at<unsigned>(h, h->L.sync); }
 
 inline unsigned blocks_for(long n, int per) { return (unsigned)((n + per - 1) / per); }
 
@@ -353,7 +350,7 @@ int launch_rnn_persistent(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st
   a.Bp = h->Bp;
   a.Hp = h->Hp;
   a.spin_limit = h->spin_limit;
-  // the 17 counters are zero here: cleared by the token-preparation kernel (forward) and by the
+  // the counters are zero here: cleared by the token-preparation kernel (forward) and by the
   // log-probability sum (backward), which always run before this launch on the same stream
   // XCD-local mode: one group of Hp/32 workgroups per block of 32 streams, group x on XCD x
   const bool xcd = h->xcd_local && h->exchange_mode != RNNLM_EXCHANGE_CHIP_WIDE && h->Bp / 32 <= NUM_XCD;
@@ -422,9 +419,6 @@ int launch_rnn_resident(rnnlm_t *h, int Tn, bool advance_state, hipStream_t st) 
   a.Hp = h->Hp;
   a.spin_limit = h->spin_limit;
   ra.part = at<float>(h, h->L.part_res);
-  ra.sync = at<unsigned>(h, h->L.sync_res);
-  hipLaunchKernelGGL(fill_kernel<uint32_t>, dim3(blocks_for(RES_SYNC_WORDS, 256)), dim3(256), 0, st, ra.sync,
-                     (long)RES_SYNC_WORDS, 0u);
   hipLaunchKernelGGL((rnn_resident_kernel<BACKWARD>), dim3(256), dim3(512), 0, st, ra);
   HIP_TRY(hipGetLastError());
   return RNNLM_OK;
