@@ -55,6 +55,23 @@ __device__ inline void wait_own_stores() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
 }
 
+// s_waitcnt vmcnt(n) for a compile-time-unrolled n in {0, 4, 8, ..., MAXN} (the instruction takes an immediate).
+template <int MAXN>
+__device__ inline void wait_vm_loads(int n) {
+  static_assert(MAXN <= 60, "the counter has 6 bits");
+  switch (n) {
+    case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+    case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+    case 12: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+    case 16: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+    case 20: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
+    case 24: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
+    case 28: asm volatile("s_waitcnt vmcnt(28)" ::: "memory"); break;
+    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+  }
+}
+
 __device__ inline void xcd_barrier(unsigned *counter, unsigned target, unsigned spin_limit, int32_t *flags) {
   wait_own_stores();  // this wave's state stores are in the XCD's L2
   __syncthreads();    // ... and so are those of every other wave of the workgroup
@@ -312,10 +329,14 @@ __global__ void __launch_bounds__(64 * NWAVE, NWAVE == 8 ? 4 : 1) rnn_persistent
         };
 #pragma unroll
         for (int b = 0; b < NBLK; ++b) copy_block(b, sw + b * 4096);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies have landed in LDS
+        // block by block as this wave's copies land in LDS (4 loads per block, returned in order)
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk)
-          f[kk] = *reinterpret_cast<const bf16x8_t *>(sw + (kk >> 2) * 4096 + frag_off[kk & 3]);
+        for (int b = 0; b < NBLK; ++b) {
+          wait_vm_loads<4 * (NBLK - 1)>(4 * (NBLK - 1 - b));
+#pragma unroll
+          for (int kk = 4 * b; kk < 4 * b + 4; ++kk)
+            f[kk] = *reinterpret_cast<const bf16x8_t *>(sw + (kk >> 2) * 4096 + frag_off[kk & 3]);
+        }
       } else
 #endif
       {
@@ -466,9 +487,10 @@ __global__ void __launch_bounds__(512, 2) rnn_persistent_wide_kernel(const RnnPe
                        : "s"(lds_addr), "v"(goff[i]), "s"(rsrc), "s"(soff + b * 128)
                        : "memory", "m0");
         }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's copies have landed in LDS
 #pragma unroll
       for (int kk = 0; kk < KS; kk += 2) {
+        // block by block as this wave's copies land in LDS (4 loads per block, returned in order)
+        if ((kk & 3) == 0) wait_vm_loads<4 * (NBLK - 1)>(4 * (NBLK - 1 - (kk >> 2)));
         const bf16x8_t f0 = *reinterpret_cast<const bf16x8_t *>(sw + (kk >> 2) * 4096 + frag_off[kk & 3]);
         const bf16x8_t f1 = *reinterpret_cast<const bf16x8_t *>(sw + ((kk + 1) >> 2) * 4096 + frag_off[(kk + 1) & 3]);
 #pragma unroll
