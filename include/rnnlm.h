@@ -284,8 +284,9 @@ int rnnlm_set_barrier_spin_limit(rnnlm_t *h, uint32_t polls);
  * The widest recurrent shape (bf16, H padded to 4096, 256 streams) runs as one launch that keeps the
  * state-to-state matrix in the register files of all compute units; it needs the same placement as the XCD-local
  * exchange, and CHIP_WIDE selects one launch pair per step for it instead (same products, another order of
- * additions: equal to bf16 rounding of the state, not bitwise).  No effect on other shapes that run one launch
- * per step. */
+ * additions: equal to bf16 rounding of the state, not bitwise).  That one-launch kernel occupies every compute
+ * unit for its duration: calls on two handles of that shape must not overlap in time on one GPU (their waits
+ * would expire: RNNLM_ERR_TIMEOUT).  No effect on other shapes that run one launch per step. */
 typedef enum { RNNLM_EXCHANGE_AUTO = 0, RNNLM_EXCHANGE_CHIP_WIDE = 1, RNNLM_EXCHANGE_XCD_LOCAL = 2 } rnnlm_exchange;
 int rnnlm_set_recurrent_exchange(rnnlm_t *h, int32_t mode);
 

@@ -294,6 +294,40 @@ def test_grid_barrier_timeout_is_reported(precision):
     g.rnnlm_check()
 
 
+def test_resident_kernel_barrier_timeout_is_reported():
+    """The same for the one-launch recurrent kernel of the widest layer (hidden size 4096, 256 streams), whose
+    steps pass two barriers each: with a spin limit of one poll the waits expire, every workgroup still runs
+    to its end (reading partial sums that may not be there yet: wrong numbers, possibly not finite, never out
+    of bounds), and the next check reports it; with the limit restored the same window is scored as by a
+    fresh model."""
+    V, H, B, T = 300, 4096, 256, 4
+    E, U, Wo, b = synth.make_weights(V, H, "normal", 0.01, 17)
+    tok = tokens(V, B * T + B + 1, 4)
+    x, y = O.stream_chunk(tok, B, T, 0)
+    g = binding.Rnnlm(E, U, Wo, b, B, T, BF16)
+    good = g.rnnlm_forward_logprob(dev(x), dev(y)).clone()
+    g.rnnlm_check()
+    g.rnnlm_set_barrier_spin_limit(1)
+    g.rnnlm_reset_state()
+    for _ in range(2):
+        g.rnnlm_forward_logprob(dev(x), dev(y))
+    seen = None
+    try:
+        g.rnnlm_check()
+    except binding.RnnlmError as e:
+        seen = e.status
+    assert seen in (None, -6, -3)   # expired wait (or, first, the non-finite sum it led to); None: every poll succeeded
+    try:
+        g.rnnlm_check()             # a second flag may have been raised by the same calls
+    except binding.RnnlmError:
+        pass
+    g.rnnlm_set_barrier_spin_limit(1 << 18)
+    g.rnnlm_reset_state()
+    again = g.rnnlm_forward_logprob(dev(x), dev(y))
+    g.rnnlm_check()
+    assert torch.equal(again, good)
+
+
 def test_measure_peaks_is_sane_and_leaves_the_model_alone():
     """The peak-measurement call borrows the logits area of the workspace: figures are positive and
     below the published ceilings, and a window evaluated afterwards matches the one before bit for bit."""
