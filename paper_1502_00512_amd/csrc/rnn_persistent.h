@@ -39,8 +39,9 @@ struct RnnPersistArgs {
 // XCD-local mode.  The workgroups that exchange state with one another are exactly those of one block
 // of 32 streams.  When such a group runs on ONE accelerator die (XCD) they share its L2, and the step
 // barrier and the state exchange need nothing beyond that L2: plain stores (the vector L1 is
-// write-through), a counter updated by L2 atomics, and plain loads (a step reads only addresses that no
-// wave of its CU has touched since the kernel started, so the L1 cannot hold a stale copy).  Placement
+// write-through), a counter updated by atomic adds and polled by loads that bypass the L1, and plain loads
+// (a step reads only addresses that no wave of its CU has touched since the kernel started, so the L1
+// cannot hold a stale copy).  Placement
 // does not rely on the dispatch order: every workgroup reads the id of the XCD it runs on, groups are
 // bound to XCDs (stream block x <-> XCD x), and a per-XCD ticket counter hands out the unit blocks;
 // surplus workgroups and those on XCDs without a group exit at once.  The host enables this mode only
@@ -78,7 +79,8 @@ __device__ inline void xcd_barrier(unsigned *counter, unsigned target, unsigned 
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned spins = 0;
-    // read-modify-write atomics execute in the L2: an OR with 0 is a coherent read of the counter
+    // an agent-scope OR with 0: a read of the counter that cannot be served by this compute unit's L1 (the
+    // compiler emits it as an agent-scope load)
     while (__hip_atomic_fetch_or(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
       __builtin_amdgcn_s_sleep(1);
       if (++spins >= spin_limit) {
