@@ -109,7 +109,11 @@ constexpr int dma4_stage_bytes() {
   return (need + 1023) / 1024 * 1024;
 }
 
-template <int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi>
+// PERSIST (epilogues that leave the LDS alone): the grid is one workgroup per compute unit and each walks the
+// work items id, id + grid, ... (the grid is a multiple of 8, so a workgroup stays on the XCD whose chunk of
+// tiles it walks); the first three K blocks of the next tile are requested before the current tile's epilogue
+// starts, so the next main loop finds them in LDS instead of waiting a memory round trip per tile.
+template <int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi, bool PERSIST = false>
 __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma4_kernel(const GemmShape g, const Epi epi) {
 #if defined(__HIP_DEVICE_COMPILE__)
   constexpr int NT = WGM * WGN * 64;
@@ -122,10 +126,17 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma4_kernel(const GemmShap
   __shared__ __attribute__((aligned(1024))) char stage2[SBYTES];
   __shared__ __attribute__((aligned(1024))) char stage3[SBYTES];
 
+  static_assert(!PERSIST || Epi::template lds_bytes<BM, BN>() == 0, "the next tile's blocks land while the epilogue runs");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WGM, wn = wave / WGM;
+  const int nwork = g.perXcd * NUM_XCD;
+  const int stride = PERSIST ? (int)gridDim.x : nwork;
+  DmaLoader32<BM, LA, NT> la;
+  DmaLoader32<BN, LB, NT> lb;
+  bool prefetched = false;  // the loaders are set up for this tile and its first three blocks are in flight
+  for (int wid = blockIdx.x; wid < nwork; wid += stride) {
   int tile_m, tile_n, split;
-  if (!map_workgroup(g, blockIdx.x, split, tile_m, tile_n)) return;  // uniform for the workgroup
+  if (!map_workgroup(g, wid, split, tile_m, tile_n)) continue;  // uniform for the workgroup (never after a prefetch)
   // g.kBlocks counts 64-deep blocks; this kernel walks 32-deep ones
   const int kb0 = 2 * split * g.kBlocksPerSplit;
   const int kb1 = 2 * min((split + 1) * g.kBlocksPerSplit, g.kBlocks);
@@ -134,19 +145,20 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma4_kernel(const GemmShap
   f32x16_t acc[TM][TN];
   epi.template init<TM, TN>(acc, tile_m * BM + wm * WTM, tile_n * BN + wn * WTN, lane, split);
 
-  DmaLoader32<BM, LA, NT> la;
-  DmaLoader32<BN, LB, NT> lb;
-  la.init(static_cast<const char *>(g.A), g.bytesA, g.lda * 2, (long)tile_m * BM, (long)kb0 * BK, tid);
-  lb.init(static_cast<const char *>(g.B), g.bytesB, g.ldb * 2, (long)tile_n * BN, (long)kb0 * BK, tid);
+  if (!prefetched) {
+    la.init(static_cast<const char *>(g.A), g.bytesA, g.lda * 2, (long)tile_m * BM, (long)kb0 * BK, tid);
+    lb.init(static_cast<const char *>(g.B), g.bytesB, g.ldb * 2, (long)tile_n * BN, (long)kb0 * BK, tid);
+  }
   const int lr = lane & 31;
 
   // block index clamped to the last one: the final iterations re-fetch it (into a stage nobody reads any
   // more) instead of branching, so the number of loads per block and wave is always the same
-  auto fetch = [&](char *stage, int kb) {
-    kb = min(kb, nk - 1);
+  auto fetch_of = [&](char *stage, int kb, int nblocks) {
+    kb = min(kb, nblocks - 1);
     la.issue(stage, kb, tid);
     lb.issue(stage + BM * 64, kb, tid);
   };
+  auto fetch = [&](char *stage, int kb) { fetch_of(stage, kb, nk); };
   constexpr int LOADS_PER_BLOCK = DmaLoader32<BM, LA, NT>::PER + DmaLoader32<BN, LB, NT>::PER;
   static_assert(2 * LOADS_PER_BLOCK <= 15, "outstanding-load count must fit the low bits of vmcnt");
   // "this wave's loads of all but the two youngest blocks have landed, and its LDS reads have returned":
@@ -195,9 +207,11 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma4_kernel(const GemmShap
   };
 
   if (nk > 0) {
-    fetch(stage0, 0);
-    fetch(stage1, 1);
-    fetch(stage2, 2);
+    if (!prefetched) {
+      fetch(stage0, 0);
+      fetch(stage1, 1);
+      fetch(stage2, 2);
+    }
     __builtin_amdgcn_s_waitcnt(WAIT_TWO_BLOCKS);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -212,6 +226,25 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma4_kernel(const GemmShap
   }
   __builtin_amdgcn_s_waitcnt(7 << 4);  // vmcnt(0) lgkmcnt(0): every load of this wave has landed
   __syncthreads();  // ... and everyone's, and all fragment reads are done: the epilogue reuses the stages
+  const int this_m = tile_m, this_n = tile_n, this_split = split;
+  prefetched = false;
+  if (PERSIST) {
+    // the next work item of this workgroup: loaders re-aimed, first three blocks requested (older than every
+    // access of the epilogue below, so the waits of the next main loop still count the right loads)
+    int nm, nn, ns;
+    if (wid + stride < nwork && map_workgroup(g, wid + stride, ns, nm, nn)) {
+      const int nkb0 = 2 * ns * g.kBlocksPerSplit;
+      const int nnk = 2 * min((ns + 1) * g.kBlocksPerSplit, g.kBlocks) - nkb0;
+      if (nnk > 0) {
+        la.init(static_cast<const char *>(g.A), g.bytesA, g.lda * 2, (long)nm * BM, (long)nkb0 * BK, tid);
+        lb.init(static_cast<const char *>(g.B), g.bytesB, g.ldb * 2, (long)nn * BN, (long)nkb0 * BK, tid);
+        fetch_of(stage0, 0, nnk);
+        fetch_of(stage1, 1, nnk);
+        fetch_of(stage2, 2, nnk);
+        prefetched = true;
+      }
+    }
+  }
   EpiCtx ctx;
   ctx.smem_lo = stage0;
   ctx.smem_hi = stage2;
@@ -219,18 +252,19 @@ __global__ void __launch_bounds__(WGM *WGN * 64) gemm_dma4_kernel(const GemmShap
   ctx.q[1] = stage1;
   ctx.q[2] = stage2;
   ctx.q[3] = stage3;
-  ctx.tile_row0 = tile_m * BM;
-  ctx.tile_col0 = tile_n * BN;
+  ctx.tile_row0 = this_m * BM;
+  ctx.tile_col0 = this_n * BN;
   ctx.wrow = wm * WTM;
   ctx.wcol = wn * WTN;
   ctx.lane = lane;
   ctx.tid = tid;
-  ctx.split = split;
+  ctx.split = this_split;
   epi.template run<BM, BN, TM, TN, NT>(acc, ctx);
+  }
 #endif  // __HIP_DEVICE_COMPILE__
 }
 
-template <int BM, int BN, int WGM, int WGN, int LA, int LB, class Epi>
+template <int BM, int BN, int WGM, int WGN, int LA, int LB, bool PERSIST = false, class Epi>
 inline hipError_t launch_gemm_dma4(hipStream_t stream, const void *A, long lda, const void *B, long ldb, long Mg,
                                    long Ng, long K, int splits, const Epi &epi, int band = 4) {
   constexpr int BK = 64;  // splits are made of 64-deep blocks, as in launch_gemm_dma
@@ -257,8 +291,10 @@ inline hipError_t launch_gemm_dma4(hipStream_t stream, const void *A, long lda, 
   g.perXcd = (int)((total + NUM_XCD - 1) / NUM_XCD);
   g.bandOverN = band < 0;
   g.band = band < 0 ? -band : band;
-  hipLaunchKernelGGL((gemm_dma4_kernel<BM, BN, WGM, WGN, LA, LB, Epi>), dim3((unsigned)(g.perXcd * NUM_XCD)),
-                     dim3(WGM * WGN * 64), 0, stream, g, epi);
+  unsigned grid = (unsigned)(g.perXcd * NUM_XCD);
+  if (PERSIST && grid > 256u) grid = 256u;  // one workgroup per compute unit
+  hipLaunchKernelGGL((gemm_dma4_kernel<BM, BN, WGM, WGN, LA, LB, Epi, PERSIST>), dim3(grid), dim3(WGM * WGN * 64), 0,
+                     stream, g, epi);
   return hipGetLastError();
 }
 

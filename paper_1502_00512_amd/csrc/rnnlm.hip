@@ -127,7 +127,10 @@ template <typename T, int WGM, int WGN, int LA, int LB, bool RING4, class Epi>
 hipError_t big_gemm(hipStream_t st, const void *A, long lda, const void *B, long ldb, long Mg, long Ng, long K,
                     int splits, const Epi &epi, int band = 4) {
   if constexpr (sizeof(T) == 2 && RING4) {
-    return launch_gemm_dma4<BIG, BIG, WGM, WGN, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
+    // epilogues that leave the LDS alone run as one persistent workgroup per compute unit, which requests the
+    // next tile's first K blocks before its epilogue
+    constexpr bool PERSIST = Epi::template lds_bytes<BIG, BIG>() == 0;
+    return launch_gemm_dma4<BIG, BIG, WGM, WGN, LA, LB, PERSIST>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
   } else if constexpr (sizeof(T) == 2) {
     return launch_gemm_dma<BIG, BIG, WGM, WGN, LA, LB>(st, A, lda, B, ldb, Mg, Ng, K, splits, epi, band);
   } else {
