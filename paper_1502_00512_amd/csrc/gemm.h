@@ -842,15 +842,22 @@ struct EpiSgd : EpiZeroInit {
       };
       if (alpha != 0.0f) {
         static_assert(TM % 2 == 0, "two row blocks in flight");
+        // (scheduling barriers: left alone, the compiler starts applying the first values after a third of the
+        // requests and issues the rest only when those have arrived, one memory round trip later)
         float wa[TN][16], wb[TN][16];
         request(0, wa);
         request(1, wb);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < TM; i += 2) {
           apply(i, wa);
+          __builtin_amdgcn_sched_barrier(0);
           if (i + 2 < TM) request(i + 2, wa);
+          __builtin_amdgcn_sched_barrier(0);
           apply(i + 1, wb);
+          __builtin_amdgcn_sched_barrier(0);
           if (i + 3 < TM) request(i + 3, wb);
+          __builtin_amdgcn_sched_barrier(0);
         }
       } else {
         float wz[TN][16];
