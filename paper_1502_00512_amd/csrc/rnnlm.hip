@@ -902,19 +902,21 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     return RNNLM_OK;
   };
   // Plain architecture with the normalised criterion: the embedding update and the recurrent weight update need
-  // nothing from the output weight update, and the recurrent one has few tiles (64 at H = 2048): started on the
-  // side stream BEFORE the output weight update, they run on compute units that its last, partly empty round of
-  // tiles would leave idle (window time -2 % at H = 2048, -1.3 % at H = 1024).  At H = 4096 the recurrent update
-  // is a full round of 256 tiles by itself and nothing is gained (measured: -0.4 %, inside the noise), so the
-  // updates keep their place after the output weight update there.
-  const bool early_side = !nce && c.P == 0 && (long)(Hp / BIG) * (Hp / BIG) < 256;
+  // nothing from the output weight update: started on the side stream BEFORE it, they run on the compute units
+  // that its last, partly empty round of tiles leaves idle (window time -2 % at H = 2048, -1.3 % at H = 1024).  At
+  // H = 4096 the recurrent update is a full round of 256 tiles by itself and keeps its place after the output
+  // weight update; the embedding update goes first there as well.
+  const bool early_side = !nce && c.P == 0;
+  const bool early_rec = early_side && (long)(Hp / BIG) * (Hp / BIG) < 256;
   if (early_side) {
     int rc = side_fork(h, 0, st);
     if (rc) return rc;
     rc = embedding_update();
     if (rc) return rc;
-    rc = recurrent_update(h->side);
-    if (rc) return rc;
+    if (early_rec) {
+      rc = recurrent_update(h->side);
+      if (rc) return rc;
+    }
   }
   if (nce) {
     int rc = nce_update<T>(h, Tn, *nce, u, st);
@@ -1021,7 +1023,7 @@ int backward_window(rnnlm_t *h, int Tn, const UpdateTargets &u, const NceCall *n
     HIP_TRY((launch_gemm<T, 64, 64, 2, 2, KROW, KROW>(st, at<T>(h, h->L.Xp_c), h->Pp, dA_c, Hp, h->Pp, Hp, Mp, 1, epi)));
   }
 
-  if (!early_side) {
+  if (!early_rec) {
     int rc = recurrent_update(st);
     if (rc) return rc;
   }
